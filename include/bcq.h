@@ -1,0 +1,129 @@
+/*
+ * bcq.h -- C ABI of the MI355X (gfx950) AnyBCQ inference library.
+ *
+ * The library computes the multi-precision binary-coded-quantisation product
+ *
+ *     y[b][r] = sum_{i < p_b} sum_j alpha^{(p_b)}_i[r][j / group] * B_i[r][j] * x[b][j]
+ *
+ * where B_i in {-1,+1} are bit-planes shared by all precisions, each precision p
+ * owns a group-wise scale set alpha^{(p)}, and request b runs at precision p_b
+ * using only the first p_b planes (paper sections 2.2, 3.1 and 3.3).
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; no entry point synchronises or allocates.
+ *   - The caller owns every buffer and must keep it alive until the enqueued
+ *     work has finished.  The library keeps no reference after that.
+ *   - Functions return BCQ_OK or a negative bcq_status; they never throw, never
+ *     terminate the process and enqueue nothing when they return an error.
+ *   - bcq_half is the raw 16-bit pattern of an IEEE binary16 value.
+ *
+ * Storage format (section 3.3, bit-plane storage; Fig. 1 caption: 0 means -1)
+ *   planes  uint32 [n_planes][m][n/32], plane-major then row-major.  Input
+ *           column j of row r in plane i is bit (j & 31) of word
+ *           planes[(i*m + r)*(n/32) + (j >> 5)]; bit 1 = +1, bit 0 = -1.
+ *           Plane 0 is the first (coarsest) plane; precision p reads planes
+ *           0..p-1 and never touches the others.
+ *   scales  bcq_half [p][m][n/group] for the set of precision p: one scale per
+ *           (plane, output row, `group` consecutive input columns).
+ *   x       bcq_half [batch][n], y  bcq_half [batch][m], both row-major.
+ *
+ * Shape rules: m >= 1, n >= group, group % 32 == 0, n % group == 0,
+ * 1 <= p <= p_max <= BCQ_MAX_PLANES, batch >= 0 (0 is a no-op).
+ * planes, scales and x must be 16-byte aligned, y 2-byte aligned.
+ * Accumulation is in fp32; the result is rounded once to binary16.
+ */
+#ifndef BCQ_H
+#define BCQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t bcq_half;
+
+#define BCQ_MAX_PLANES 8
+
+typedef enum {
+    BCQ_OK = 0,
+    BCQ_ERR_NULL = -1,       /* a required pointer is NULL */
+    BCQ_ERR_BAD_P = -2,      /* precision / plane count out of range */
+    BCQ_ERR_BAD_SHAPE = -3,  /* m, n, batch or group violate the shape rules */
+    BCQ_ERR_ALIGN = -4,      /* a pointer is not aligned as required */
+    BCQ_ERR_HIP = -5,        /* the HIP runtime reported an error at launch */
+    BCQ_ERR_VARIANT = -6     /* a forced kernel variant cannot run this problem */
+} bcq_status;
+
+/* Kernel variants for bcq_select_kernel (benchmarks and tests only). */
+typedef enum {
+    BCQ_KERNEL_AUTO = 0,       /* pick by shape and batch */
+    BCQ_KERNEL_SIGN_SELECT = 1,/* generic per-bit add/subtract kernel, any legal shape */
+    BCQ_KERNEL_PLANE_MFMA = 2, /* bit-planes fed to the FP4 matrix pipe, small batches */
+    BCQ_KERNEL_DEQUANT_MFMA = 3/* dequantise to fp16 tiles in LDS + fp16 MFMA, large batches */
+} bcq_kernel;
+
+/* Static, NUL-terminated description of a status code.  Host call. */
+const char *bcq_strerror(int status);
+
+/*
+ * Force one kernel variant for later bcq_gemv / bcq_gemm_mixed calls of this
+ * process (BCQ_KERNEL_AUTO restores the default choice).  A forced variant
+ * that cannot handle a problem makes the call return BCQ_ERR_VARIANT.
+ * Returns BCQ_OK, or BCQ_ERR_VARIANT for an unknown id.  Host call, not
+ * thread-safe against concurrent launches.
+ */
+int bcq_select_kernel(int variant);
+
+/* Name of the variant the most recent successful launch used ("" before any). */
+const char *bcq_last_kernel(void);
+
+/*
+ * bcq_pack -- bit-plane storage (section 3.3): turn +-1 codes into planes.
+ *   codes   int8  [n_planes][m][n]; a value > 0 is the code +1, anything else -1
+ *   planes  uint32 [n_planes][m][n/32], written in the storage format above
+ * n % 32 == 0, 1 <= n_planes <= BCQ_MAX_PLANES.  Integer work, bit-exact.
+ */
+int bcq_pack(const int8_t *codes, uint32_t *planes, int n_planes,
+             int64_t m, int64_t n, void *stream);
+
+/* bcq_unpack -- inverse of bcq_pack: bit 1 -> +1, bit 0 -> -1 (int8). */
+int bcq_unpack(const uint32_t *planes, int8_t *codes, int n_planes,
+               int64_t m, int64_t n, void *stream);
+
+/*
+ * bcq_gemv -- the AnyBCQ kernel of section 3.3 at one precision for the whole
+ * batch: for every plane i < p form B_i x by adding/subtracting activations,
+ * multiply by alpha_i, accumulate, and return after plane p.
+ *   planes    uint32 [>= p][m][n/32]; only planes 0..p-1 are read
+ *   scales_p  bcq_half [p][m][n/group], the scale set OF PRECISION p
+ *   x         bcq_half [batch][n]
+ *   y         bcq_half [batch][m] (written)
+ */
+int bcq_gemv(const uint32_t *planes, const bcq_half *scales_p, int p,
+             const bcq_half *x, bcq_half *y,
+             int64_t m, int64_t n, int batch, int group, void *stream);
+
+/*
+ * bcq_gemm_mixed -- per-request precision (sections 1 and 3.3): request b uses
+ * planes 0..p_req[b]-1 with the scale set of precision p_req[b]; the planes
+ * are stored once to p_max and read once up to max_b p_req[b].
+ *   planes       uint32 [p_max][m][n/32]
+ *   scales_by_p  HOST array of p_max+1 device pointers; entry q is the set of
+ *                precision q ([q][m][n/group]); entry 0 is ignored; an entry
+ *                may be NULL if no request uses that precision (a request that
+ *                does name it is then computed as all-zero output)
+ *   p_req        DEVICE int32 [batch]; values are clamped to [1, p_max]
+ *   x, y         as for bcq_gemv
+ */
+int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p,
+                   const int32_t *p_req, int p_max,
+                   const bcq_half *x, bcq_half *y,
+                   int64_t m, int64_t n, int batch, int group, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCQ_H */

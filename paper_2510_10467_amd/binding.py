@@ -1,0 +1,141 @@
+"""ctypes binding of the C ABI in ``include/bcq.h``.
+
+Argument marshalling only: every step of the product runs in the HIP kernels.
+PyTorch supplies device memory and the current stream.  There is no CPU
+fallback: if the shared library is missing the import of this module's
+functions raises, and every call checks that its tensors live on the GPU.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbcq_hip.so")
+_lib = None
+
+BCQ_MAX_PLANES = 8
+KERNEL_AUTO, KERNEL_SIGN_SELECT, KERNEL_PLANE_MFMA, KERNEL_DEQUANT_MFMA = 0, 1, 2, 3
+KERNEL_IDS = {"auto": 0, "sign_select": 1, "plane_mfma": 2, "dequant_mfma": 3}
+
+
+class BcqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().bcq_strerror(status).decode()} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load ``libbcq_hip.so`` (built in-tree by ``build.py``); fail loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "or `python paper_2510_10467_amd/build.py`")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        L.bcq_strerror.restype = ctypes.c_char_p
+        L.bcq_strerror.argtypes = [i32]
+        L.bcq_select_kernel.argtypes = [i32]
+        L.bcq_last_kernel.restype = ctypes.c_char_p
+        L.bcq_pack.argtypes = [vp, vp, i32, i64, i64, vp]
+        L.bcq_unpack.argtypes = [vp, vp, i32, i64, i64, vp]
+        L.bcq_gemv.argtypes = [vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
+        L.bcq_gemm_mixed.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
+        for f in (L.bcq_select_kernel, L.bcq_pack, L.bcq_unpack, L.bcq_gemv, L.bcq_gemm_mixed):
+            f.restype = i32
+        _lib = L
+    return _lib
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor (there is no CPU path)")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise BcqError(status, where)
+
+
+def select_kernel(variant) -> None:
+    """Force a kernel variant by name or id ('auto' restores the default choice)."""
+    vid = KERNEL_IDS[variant] if isinstance(variant, str) else int(variant)
+    _check(lib().bcq_select_kernel(vid), "bcq_select_kernel")
+
+
+def last_kernel() -> str:
+    return lib().bcq_last_kernel().decode()
+
+
+def bcq_pack(codes: torch.Tensor, planes: torch.Tensor | None = None) -> torch.Tensor:
+    """int8 codes [P][m][n] (>0 is +1) -> int32-typed planes [P][m][n/32] holding the uint32 words."""
+    P, m, n = codes.shape
+    if planes is None:
+        planes = torch.empty((P, m, n // 32), dtype=torch.int32, device=codes.device)
+    _check(lib().bcq_pack(_dev(codes, torch.int8, "codes"), _dev(planes, torch.int32, "planes"), P, m, n, _stream()),
+           "bcq_pack")
+    return planes
+
+
+def bcq_unpack(planes: torch.Tensor, codes: torch.Tensor | None = None) -> torch.Tensor:
+    """planes [P][m][n/32] -> int8 codes [P][m][n] in {-1,+1}."""
+    P, m, words = planes.shape
+    if codes is None:
+        codes = torch.empty((P, m, words * 32), dtype=torch.int8, device=planes.device)
+    _check(lib().bcq_unpack(_dev(planes, torch.int32, "planes"), _dev(codes, torch.int8, "codes"), P, m, words * 32,
+                            _stream()), "bcq_unpack")
+    return codes
+
+
+def bcq_gemv(planes: torch.Tensor, scales_p: torch.Tensor, p: int, x: torch.Tensor,
+             y: torch.Tensor | None = None, group: int = 128) -> torch.Tensor:
+    """Uniform precision: y[b][r] = sum_{i<p} sum_j scales_p[i][r][j/group] * B_i[r][j] * x[b][j]."""
+    _, m, words = planes.shape
+    n = words * 32
+    batch = x.shape[0]
+    if x.shape != (batch, n) or scales_p.shape != (p, m, n // group) or planes.shape[0] < p:
+        raise ValueError("bcq_gemv: inconsistent shapes")
+    if y is None:
+        y = torch.empty((batch, m), dtype=torch.float16, device=x.device)
+    elif y.shape != (batch, m):
+        raise ValueError("bcq_gemv: y has the wrong shape")
+    _check(lib().bcq_gemv(_dev(planes, torch.int32, "planes"), _dev(scales_p, torch.float16, "scales_p"), p,
+                          _dev(x, torch.float16, "x"), _dev(y, torch.float16, "y"), m, n, batch, group, _stream()),
+           "bcq_gemv")
+    return y
+
+
+def bcq_gemm_mixed(planes: torch.Tensor, scales_by_p: dict, p_req: torch.Tensor, x: torch.Tensor,
+                   y: torch.Tensor | None = None, group: int = 128) -> torch.Tensor:
+    """Per-request precision: request b uses planes 0..p_req[b]-1 and scale set scales_by_p[p_req[b]]."""
+    p_max, m, words = planes.shape
+    n = words * 32
+    batch = x.shape[0]
+    if x.shape != (batch, n) or p_req.shape != (batch,):
+        raise ValueError("bcq_gemm_mixed: inconsistent shapes")
+    ptrs = (ctypes.c_void_p * (p_max + 1))()
+    for q, s in scales_by_p.items():
+        if not 1 <= q <= p_max or s.shape != (q, m, n // group):
+            raise ValueError(f"bcq_gemm_mixed: bad scale set for precision {q}")
+        ptrs[q] = _dev(s, torch.float16, f"scales_by_p[{q}]")
+    if y is None:
+        y = torch.empty((batch, m), dtype=torch.float16, device=x.device)
+    elif y.shape != (batch, m):
+        raise ValueError("bcq_gemm_mixed: y has the wrong shape")
+    _check(lib().bcq_gemm_mixed(_dev(planes, torch.int32, "planes"), ctypes.cast(ptrs, ctypes.c_void_p),
+                                _dev(p_req, torch.int32, "p_req"), p_max, _dev(x, torch.float16, "x"),
+                                _dev(y, torch.float16, "y"), m, n, batch, group, _stream()), "bcq_gemm_mixed")
+    return y

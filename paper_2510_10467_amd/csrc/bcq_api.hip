@@ -1,0 +1,155 @@
+// C ABI of the library: argument checks and kernel choice.  All arithmetic
+// lives in the kernel files; this file never touches tensor data.
+#include <hip/hip_runtime.h>
+
+#include "bcq.h"
+#include "bcq_internal.hpp"
+
+namespace {
+
+int g_forced = BCQ_KERNEL_AUTO;
+const char *g_last = "";
+
+bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_shape(int64_t m, int64_t n, int batch, int group)
+{
+    if (m < 1 || n < 1 || batch < 0 || group < 32 || (group % 32) != 0 || n < group || (n % group) != 0)
+        return BCQ_ERR_BAD_SHAPE;
+    // index arithmetic inside the kernels is 64-bit, but word counts per row are kept in int
+    if (n > (int64_t(1) << 30) || m > (int64_t(1) << 40)) return BCQ_ERR_BAD_SHAPE;
+    return BCQ_OK;
+}
+
+int run(const bcq::GemmArgs &a, hipStream_t stream)
+{
+    using namespace bcq;
+    hipError_t err;
+    int choice = g_forced;
+    if (choice == BCQ_KERNEL_AUTO) {
+        if (dequant_mfma_supports(a) && a.batch > 16) choice = BCQ_KERNEL_DEQUANT_MFMA;
+        else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
+        else choice = BCQ_KERNEL_SIGN_SELECT;
+    }
+    switch (choice) {
+    case BCQ_KERNEL_SIGN_SELECT:
+        if (!sign_select_supports(a)) return BCQ_ERR_VARIANT;
+        err = sign_select_launch(a, stream);
+        g_last = "sign_select";
+        break;
+    case BCQ_KERNEL_PLANE_MFMA:
+        if (!plane_mfma_supports(a)) return BCQ_ERR_VARIANT;
+        err = plane_mfma_launch(a, stream);
+        g_last = "plane_mfma";
+        break;
+    case BCQ_KERNEL_DEQUANT_MFMA:
+        if (!dequant_mfma_supports(a)) return BCQ_ERR_VARIANT;
+        err = dequant_mfma_launch(a, stream);
+        g_last = "dequant_mfma";
+        break;
+    default:
+        return BCQ_ERR_VARIANT;
+    }
+    return err == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *bcq_strerror(int status)
+{
+    switch (status) {
+    case BCQ_OK: return "ok";
+    case BCQ_ERR_NULL: return "a required pointer is NULL";
+    case BCQ_ERR_BAD_P: return "precision or plane count out of range";
+    case BCQ_ERR_BAD_SHAPE: return "shape violates m>=1, n>=group, group%32==0, n%group==0, batch>=0";
+    case BCQ_ERR_ALIGN: return "pointer not aligned (planes/scales/x: 16 bytes, y: 2 bytes)";
+    case BCQ_ERR_HIP: return "HIP runtime error at kernel launch";
+    case BCQ_ERR_VARIANT: return "forced kernel variant unknown or unable to run this problem";
+    default: return "unknown status";
+    }
+}
+
+int bcq_select_kernel(int variant)
+{
+    if (variant < BCQ_KERNEL_AUTO || variant > BCQ_KERNEL_DEQUANT_MFMA) return BCQ_ERR_VARIANT;
+    g_forced = variant;
+    return BCQ_OK;
+}
+
+const char *bcq_last_kernel(void) { return g_last; }
+
+int bcq_pack(const int8_t *codes, uint32_t *planes, int n_planes, int64_t m, int64_t n, void *stream)
+{
+    if (!codes || !planes) return BCQ_ERR_NULL;
+    if (n_planes < 1 || n_planes > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
+    if (m < 1 || n < 32 || (n % 32) != 0) return BCQ_ERR_BAD_SHAPE;
+    if (!aligned(codes, 16) || !aligned(planes, 4)) return BCQ_ERR_ALIGN;
+    return bcq::pack_launch(codes, planes, n_planes, m, n, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? BCQ_OK : BCQ_ERR_HIP;
+}
+
+int bcq_unpack(const uint32_t *planes, int8_t *codes, int n_planes, int64_t m, int64_t n, void *stream)
+{
+    if (!codes || !planes) return BCQ_ERR_NULL;
+    if (n_planes < 1 || n_planes > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
+    if (m < 1 || n < 32 || (n % 32) != 0) return BCQ_ERR_BAD_SHAPE;
+    if (!aligned(codes, 16) || !aligned(planes, 4)) return BCQ_ERR_ALIGN;
+    return bcq::unpack_launch(planes, codes, n_planes, m, n, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? BCQ_OK : BCQ_ERR_HIP;
+}
+
+int bcq_gemv(const uint32_t *planes, const bcq_half *scales_p, int p, const bcq_half *x, bcq_half *y,
+             int64_t m, int64_t n, int batch, int group, void *stream)
+{
+    if (!planes || !scales_p || !x || !y) return BCQ_ERR_NULL;
+    if (p < 1 || p > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
+    if (int rc = check_shape(m, n, batch, group)) return rc;
+    if (!aligned(planes, 16) || !aligned(scales_p, 16) || !aligned(x, 16) || !aligned(y, 2)) return BCQ_ERR_ALIGN;
+    if (batch == 0) return BCQ_OK;
+    bcq::GemmArgs a{};
+    a.planes = planes;
+    a.scales[p] = reinterpret_cast<const _Float16 *>(scales_p);
+    a.p_req = nullptr;
+    a.uniform_p = p;
+    a.p_max = p;
+    a.x = reinterpret_cast<const _Float16 *>(x);
+    a.y = reinterpret_cast<_Float16 *>(y);
+    a.m = m;
+    a.n = n;
+    a.batch = batch;
+    a.group = group;
+    return run(a, static_cast<hipStream_t>(stream));
+}
+
+int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p, const int32_t *p_req, int p_max,
+                   const bcq_half *x, bcq_half *y, int64_t m, int64_t n, int batch, int group, void *stream)
+{
+    if (!planes || !scales_by_p || !p_req || !x || !y) return BCQ_ERR_NULL;
+    if (p_max < 1 || p_max > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
+    if (int rc = check_shape(m, n, batch, group)) return rc;
+    if (!aligned(planes, 16) || !aligned(x, 16) || !aligned(y, 2) || !aligned(p_req, 4)) return BCQ_ERR_ALIGN;
+    bcq::GemmArgs a{};
+    bool any = false;
+    for (int q = 1; q <= p_max; ++q) {
+        if (!aligned(scales_by_p[q], 16)) return BCQ_ERR_ALIGN;
+        a.scales[q] = reinterpret_cast<const _Float16 *>(scales_by_p[q]);
+        any = any || scales_by_p[q] != nullptr;
+    }
+    if (!any) return BCQ_ERR_NULL;
+    if (batch == 0) return BCQ_OK;
+    a.planes = planes;
+    a.p_req = p_req;
+    a.uniform_p = 0;
+    a.p_max = p_max;
+    a.x = reinterpret_cast<const _Float16 *>(x);
+    a.y = reinterpret_cast<_Float16 *>(y);
+    a.m = m;
+    a.n = n;
+    a.batch = batch;
+    a.group = group;
+    return run(a, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Internal launch descriptor shared by the dispatcher and the kernel files.
+// Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bcq.h"
+
+namespace bcq {
+
+// One product call, uniform or per-request precision.
+struct GemmArgs {
+    const uint32_t *planes;                          // [>= p_max][m][n/32]
+    const _Float16 *scales[BCQ_MAX_PLANES + 1];      // [q] = scale set of precision q, or nullptr
+    const int32_t *p_req;                            // device int32[batch], nullptr when uniform
+    int uniform_p;                                   // > 0: every request runs at this precision
+    int p_max;                                       // planes stored / upper bound of any p_req
+    const _Float16 *x;                               // [batch][n]
+    _Float16 *y;                                     // [batch][m]
+    int64_t m, n;
+    int batch;
+    int group;
+};
+
+// Precision of request b: the uniform one, or p_req[b] clamped to [1, p_max];
+// 0 when that precision has no scale set (the request then yields zeros).
+__device__ __forceinline__ int request_precision(const GemmArgs &a, int b)
+{
+    int p = a.uniform_p;
+    if (p == 0) {
+        p = a.p_req[b];
+        p = p < 1 ? 1 : (p > a.p_max ? a.p_max : p);
+    }
+    return a.scales[p] ? p : 0;
+}
+
+// Kernel families.  *_supports tells whether the family can run the problem;
+// *_launch enqueues it on `stream` and returns the HIP launch status.
+bool sign_select_supports(const GemmArgs &a);
+hipError_t sign_select_launch(const GemmArgs &a, hipStream_t stream);
+
+bool plane_mfma_supports(const GemmArgs &a);
+hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream);
+
+bool dequant_mfma_supports(const GemmArgs &a);
+hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream);
+
+hipError_t pack_launch(const int8_t *codes, uint32_t *planes, int n_planes, int64_t m, int64_t n, hipStream_t stream);
+hipError_t unpack_launch(const uint32_t *planes, int8_t *codes, int n_planes, int64_t m, int64_t n, hipStream_t stream);
+
+}  // namespace bcq

@@ -1,0 +1,84 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2510_10467_amd import build as hip_build
+    if hip_build.is_stale():
+        hip_build.build()
+    import paper_2510_10467_amd as bcq
+    return bcq.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "bcq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bcq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_strerror", "bcq_select_kernel",
+            "bcq_last_kernel"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in bcq.h but not exported"
+
+
+def test_strerror_covers_all_codes(lib):
+    seen = set()
+    for code in range(0, -7, -1):
+        msg = lib.bcq_strerror(code).decode()
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 7
+    assert lib.bcq_strerror(-99).decode() == "unknown status"
+
+
+def test_argument_validation_without_device(lib):
+    # pointers are never dereferenced on an error path, so fake aligned addresses are enough
+    P, S, X, Y = 0x1000, 0x2000, 0x3000, 0x4000
+    gemv = lib.bcq_gemv
+    assert gemv(None, S, 2, X, Y, 16, 128, 1, 128, None) == -1
+    assert gemv(P, S, 0, X, Y, 16, 128, 1, 128, None) == -2
+    assert gemv(P, S, 9, X, Y, 16, 128, 1, 128, None) == -2
+    assert gemv(P, S, 2, X, Y, 0, 128, 1, 128, None) == -3
+    assert gemv(P, S, 2, X, Y, 16, 192, 1, 128, None) == -3      # n % group != 0
+    assert gemv(P, S, 2, X, Y, 16, 128, 1, 48, None) == -3       # group % 32 != 0
+    assert gemv(P, S, 2, X, Y, 16, 64, 1, 128, None) == -3       # n < group
+    assert gemv(P, S, 2, X, Y, 16, 128, -1, 128, None) == -3
+    assert gemv(P + 4, S, 2, X, Y, 16, 128, 1, 128, None) == -4
+    assert gemv(P, S, 2, X + 2, Y, 16, 128, 1, 128, None) == -4
+    assert gemv(P, S, 2, X, Y + 1, 16, 128, 1, 128, None) == -4
+    assert gemv(P, S, 2, X, Y, 16, 128, 0, 128, None) == 0       # empty batch: no-op
+    ptrs = (ctypes.c_void_p * 5)(None, None, S, None, None)
+    mixed = lib.bcq_gemm_mixed
+    assert mixed(P, ptrs, None, 4, X, Y, 16, 128, 1, 128, None) == -1
+    assert mixed(P, ptrs, 0x5000, 0, X, Y, 16, 128, 1, 128, None) == -2
+    assert mixed(P, ptrs, 0x5000, 4, X, Y, 16, 100, 1, 128, None) == -3
+    assert mixed(P, ptrs, 0x5000, 4, X, Y, 16, 128, 0, 128, None) == 0
+    none = (ctypes.c_void_p * 5)()
+    assert mixed(P, none, 0x5000, 4, X, Y, 16, 128, 1, 128, None) == -1
+    assert lib.bcq_pack(0x1000, 0x2000, 4, 8, 48, None) == -3
+    assert lib.bcq_pack(0x1000, 0x2000, 0, 8, 64, None) == -2
+    assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1
+    assert lib.bcq_select_kernel(17) == -6
+    assert lib.bcq_select_kernel(0) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    planes = torch.zeros((2, 4, 4), dtype=torch.int32)
+    scales = torch.zeros((2, 4, 1), dtype=torch.float16)
+    x = torch.zeros((1, 128), dtype=torch.float16)
+    with pytest.raises(TypeError):
+        bcq.bcq_gemv(planes, scales, 2, x)

@@ -1,0 +1,64 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element,
+on the same seeded inputs.  Integer work (packing) is bit-exact; products must satisfy
+|y - y_ref| <= 4e-3 * sum_j |W_p[r,j] x_j| + one binary16 ulp."""
+import numpy as np
+import pytest
+
+import synthetic_inputs as syn
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from tests import gpu_util
+    return gpu_util
+
+
+def test_pack_unpack_bit_exact(gpu, oracle):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    for (P, m, n, seed) in [(4, 37, 4096, 0), (1, 1, 32, 1), (3, 130, 224, 2), (8, 5, 1024, 3)]:
+        codes = syn.make_codes(P, m, n, seed=(100, seed))
+        if seed == 2:
+            codes[0, 0, :8] = [0, -5, 127, -128, 1, 2, 0, 0]      # zero / negative mean -1, any positive means +1
+        planes = bcq.bcq_pack(gpu.to_dev(codes))
+        torch.cuda.synchronize()
+        host = oracle.pack(codes)
+        assert np.array_equal(planes.cpu().numpy().view(np.uint32), host), f"pack P={P} m={m} n={n}"
+        back = bcq.bcq_unpack(planes)
+        assert np.array_equal(back.cpu().numpy(), oracle.unpack(host))
+        raw = syn.make_planes(m, n, p_max=P, seed=(100, seed))
+        again = bcq.bcq_pack(bcq.bcq_unpack(gpu.to_dev(raw)))
+        assert np.array_equal(again.cpu().numpy().view(np.uint32), raw), "pack(unpack(w)) != w"
+
+
+SMALL_SHAPES = [
+    # m, n, group: several tiles plus ragged tails in m, odd group counts in n
+    (1, 128, 128), (16, 1024, 128), (37, 2048, 128), (131, 4096, 128), (70, 1536, 128), (33, 640, 128),
+    (19, 256, 64), (8, 96, 32), (40, 5120, 128),
+]
+
+
+@pytest.mark.parametrize("m,n,group", SMALL_SHAPES)
+def test_sign_select_uniform(gpu, m, n, group):
+    layer = syn.make_layer(m, n, group=group, seed=(110, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 3, 5):
+        x = syn.make_x(batch, n, seed=(110, batch))
+        for p in (1, 2, 3, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "sign_select", group)
+            assert used == "sign_select"
+
+
+@pytest.mark.parametrize("m,n,group", [(37, 2048, 128), (16, 1024, 128), (19, 256, 64)])
+def test_sign_select_mixed(gpu, m, n, group):
+    layer = syn.make_layer(m, n, group=group, seed=(120, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 6, 16):
+        x = syn.make_x(batch, n, seed=(120, batch))
+        p_req = syn.make_p_req(batch, 1, 4, seed=(120, batch))
+        gpu.check_mixed(dl, p_req, x, "sign_select", group)

@@ -62,3 +62,30 @@ def test_sign_select_mixed(gpu, m, n, group):
         x = syn.make_x(batch, n, seed=(120, batch))
         p_req = syn.make_p_req(batch, 1, 4, seed=(120, batch))
         gpu.check_mixed(dl, p_req, x, "sign_select", group)
+
+
+PLANE_MFMA_SHAPES = [
+    # m, n: one and several K slices of 1024 columns, ragged row tails, chunked K (n = 28672)
+    (16, 1024), (37, 2048), (131, 4096), (40, 5120), (75, 14336), (50, 28672), (1, 1024), (530, 3072),
+]
+
+
+@pytest.mark.parametrize("m,n", PLANE_MFMA_SHAPES)
+def test_plane_mfma_uniform(gpu, m, n):
+    layer = syn.make_layer(m, n, seed=(130, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 2, 3, 4, 7):
+        x = syn.make_x(batch, n, seed=(130, batch))
+        for p in (1, 2, 3, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "plane_mfma")
+            assert used == "plane_mfma"
+
+
+@pytest.mark.parametrize("m,n", [(37, 2048), (131, 4096), (75, 14336)])
+def test_plane_mfma_mixed(gpu, m, n):
+    layer = syn.make_layer(m, n, seed=(140, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 4, 6, 16):
+        x = syn.make_x(batch, n, seed=(140, batch))
+        p_req = syn.make_p_req(batch, 1, 4, seed=(140, batch))
+        gpu.check_mixed(dl, p_req, x, "plane_mfma")

@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the AnyBCQ bit-plane product on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): the seven linear
+layers of one Llama-3-8B decoder block (q, k, v, o, gate, up, down), batch 1,
+group 128, each run at precision p = 2, 3 and 4 -- 21 bcq_gemv calls per step.
+Inputs are seeded and synthetic (synthetic_inputs.py) and resident in HBM before
+the timed region.  To keep reads coming from HBM rather than the 256 MB last
+level cache, successive steps rotate over distinct copies of the whole layer
+set (>= 1 GiB in total).  Each step is one HIP-graph replay, so host launch
+cost does not pace the GPU.
+
+Prints ONE JSON line:
+  value     effective HBM GB/s over the timed steps = algorithmic bytes / time,
+            algorithmic bytes per call = m*n*p/8 (planes) + m*(n/128)*p*2
+            (scales) + n*2 (x) + m*2 (y)
+  roofline  the dominant kernel (plane_mfma_kernel<4> on a 14336x4096 layer):
+            algorithmic bytes per launch / mean launch duration, measured with
+            HIP events around back-to-back launches on the launch stream,
+            against the 8 TB/s HBM peak
+  cpu_baseline  the float64 oracle timed on the host cores on one copy of the
+            same layer set (a reported baseline, not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PRECISIONS = (2, 3, 4)
+MIN_ROTATION_BYTES = 1 << 30
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying HIP graphs")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    import synthetic_inputs as syn
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    bcq.lib()                                        # fail loudly if the HIP library is missing
+
+    layers = syn.LLAMA3_8B_LAYERS
+    set_bytes = sum(m * n * syn.P_MAX // 8 + sum(m * (n // syn.GROUP) * p * 2 for p in PRECISIONS) for _, m, n in layers)
+    copies = max(2, -(-MIN_ROTATION_BYTES // set_bytes))
+
+    def upload(a):
+        return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+
+    # ---- inputs: `copies` independent layer sets, resident in HBM ------------------------------
+    host_copy0 = None
+    dev_sets = []
+    for c in range(copies):
+        host = [syn.make_layer(m, n, seed=(2, c, li), precisions=PRECISIONS) for li, (_, m, n) in enumerate(layers)]
+        if c == 0:
+            host_copy0 = host
+        dev_sets.append([(upload(L.planes), {p: upload(s) for p, s in L.scales.items()}) for L in host])
+        del host
+    xs_host = {n: syn.make_x(1, n, seed=(2, n)) for n in sorted({n for _, _, n in layers})}
+    xs = {n: upload(x) for n, x in xs_host.items()}
+    ys = [torch.empty((1, m), dtype=torch.float16, device=dev) for _, m, _ in layers]
+    torch.cuda.synchronize()
+
+    def run_step(c, precisions=PRECISIONS):
+        for p in precisions:
+            for li, (_, m, n) in enumerate(layers):
+                planes, scales = dev_sets[c][li]
+                bcq.bcq_gemv(planes, scales[p], p, xs[n], ys[li])
+
+    bytes_per_p = {p: sum(syn.algorithmic_bytes(m, n, p, 1) for _, m, n in layers) for p in PRECISIONS}
+    bytes_per_step = sum(bytes_per_p.values())
+
+    # ---- one HIP graph per copy (a step = one replay) ----------------------------------------
+    def capture(fn):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g
+
+    run_step(0)
+    torch.cuda.synchronize()
+    kernel_name = bcq.last_kernel()
+    if args.no_graph:
+        step_fns = [lambda c=c: run_step(c) for c in range(copies)]
+    else:
+        graphs = [capture(lambda c=c: run_step(c)) for c in range(copies)]
+        step_fns = [g.replay for g in graphs]
+
+    def timed(fns, count, warmup):
+        for i in range(warmup):
+            fns[i % len(fns)]()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(count):
+            fns[i % len(fns)]()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / count            # ms per call
+
+    ms_per_step = timed(step_fns, args.steps, args.warmup)
+    value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-precision step times (7 calls each) ---------------------------------------------
+    per_p = {}
+    for p in PRECISIONS:
+        if args.no_graph:
+            fns = [lambda c=c, p=p: run_step(c, (p,)) for c in range(copies)]
+        else:
+            fns = [capture(lambda c=c, p=p: run_step(c, (p,))).replay for c in range(copies)]
+        ms = timed(fns, max(args.steps // 2, 8), max(args.warmup // 2, 4))
+        per_p[str(p)] = {"us_per_layer_set": round(ms * 1e3, 3), "us_per_gemv_mean": round(ms * 1e3 / len(layers), 3),
+                         "effective_GBps": round(bytes_per_p[p] / (ms * 1e-3) / 1e9, 1),
+                         "pct_of_hbm_peak": round(100 * bytes_per_p[p] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+
+    # ---- roofline of the dominant kernel: gate/up-shaped layer at p = 4 -----------------------
+    def kernel_time_us(li, p, launches=64):
+        """Mean duration of back-to-back launches of one (layer, p), rotating over the copies."""
+        _, m, n = layers[li]
+        same_shape = [k for k, (_, mm, nn) in enumerate(layers) if (mm, nn) == (m, n)]
+        bufs = [(dev_sets[c][k][0], dev_sets[c][k][1][p]) for c in range(copies) for k in same_shape]
+
+        def burst():
+            for i in range(launches):
+                pl, sc = bufs[i % len(bufs)]
+                bcq.bcq_gemv(pl, sc, p, xs[n], ys[li])
+        burst()
+        torch.cuda.synchronize()
+        fn = burst if args.no_graph else capture(burst).replay
+        return timed([fn], 10, 3) * 1e3 / launches
+
+    dom_li = [i for i, (name, _, _) in enumerate(layers) if name == "gate_proj"][0]
+    dom_p = 4
+    _, dm, dn = layers[dom_li]
+    dom_us = kernel_time_us(dom_li, dom_p)
+    dom_bytes = syn.algorithmic_bytes(dm, dn, dom_p, 1)
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": f"plane_mfma_kernel<{dom_p}> m={dm} n={dn} batch=1",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3)}
+
+    details = None
+    if args.details:
+        details = {"kernels": []}
+        seen = set()
+        for li, (name, m, n) in enumerate(layers):
+            if (m, n) in seen:
+                continue
+            seen.add((m, n))
+            for p in PRECISIONS:
+                us = kernel_time_us(li, p)
+                by = syn.algorithmic_bytes(m, n, p, 1)
+                details["kernels"].append({"m": m, "n": n, "p": p, "us": round(us, 3),
+                                           "GBps": round(by / (us * 1e-6) / 1e9, 1),
+                                           "pct_of_hbm_peak": round(100 * by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 2)})
+        # fp16 GEMV of the same shape on the same GPU (library GEMV), rotating over distinct matrices
+        ws = [torch.randn((dm, dn), dtype=torch.float16, device=dev) for _ in range(12)]
+        xv = xs[dn][0]
+
+        def fp16_burst():
+            for i in range(48):
+                torch.mv(ws[i % len(ws)], xv)
+        fp16_burst()
+        torch.cuda.synchronize()
+        us16 = timed([fp16_burst], 10, 3) * 1e3 / 48
+        details["fp16_gemv"] = {"m": dm, "n": dn, "us": round(us16, 3), "GBps": round(2 * dm * dn / (us16 * 1e-6) / 1e9, 1)}
+        del ws
+
+    # ---- CPU baseline: the oracle as it stands, on one copy of the same layer set -------------
+    cpu_baseline = None
+    if not args.skip_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        for p in PRECISIONS:
+            for li, (_, m, n) in enumerate(layers):
+                oracle.gemv(host_copy0[li].planes, host_copy0[li].scales[p], xs_host[n])
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": round(bytes_per_step / dt / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(),
+                        "kind": "oracle", "seconds": round(dt, 2),
+                        "sample": "one step: the 7 Llama-3-8B layers at p=2,3,4, batch 1 (21 oracle products, float64)"}
+
+    out = {
+        "metric": "bcq_gemv effective HBM GB/s, Llama-3-8B linear set, batch 1, p=2/3/4",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp4 signs x e5m2 activation terms, fp32 accumulate (fp16 in/out)", "data": "synthetic",
+        "config": {"workload": "Llama-3-8B-shaped linear set (q,k,v,o,gate,up,down), batch 1, group 128, p in {2,3,4}; "
+                               "one step = 21 bcq_gemv calls", "kernel": kernel_name,
+                   "weight_copies_rotated": copies, "rotation_bytes": copies * set_bytes,
+                   "launch": "python loop" if args.no_graph else "hip graph replay per step"},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "bytes_per_step": bytes_per_step,
+        "per_precision": per_p,
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    if details:
+        out["details"] = details
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -65,7 +65,148 @@ __device__ __forceinline__ void quarter_transpose(uint32_t &v0, uint32_t &v1, ui
     s = __builtin_amdgcn_permlane16_swap(v2, v3, false, false); v2 = s[0]; v3 = s[1];
 }
 
-template <int P>
+// Sweep of one wave over its K slices for PH planes; returns this lane's partial sum.
+//   p_mine   precision of the request this lane reports on (0: none)
+//   sptr     scale set of that precision (any valid set when p_mine == 0)
+template <int PH>
+__device__ __forceinline__ float sweep(const GemmArgs &a, unsigned char *lds, int KS, int nchunk, int ks, int q, int lane,
+                                       int tid, int nthreads, int b0, int nb, int64_t row, int p_mine,
+                                       const _Float16 *sptr)
+{
+    const int nrows = 4 * nb;
+    const int words = (int)(a.n >> 5);
+    const int ngroups = (int)(a.n >> 7);
+    const int nslices = (int)(a.n / kSliceCols);
+    const int chunk_cols = KS * kSliceCols;
+    const int image_bytes = KS * kSliceGroups * 128 * nrows;      // followed by 16 zero bytes, then the staging area
+    const int stage_off = image_bytes + 16;
+    const int arow = lane & 15;
+
+    if (tid < 4) reinterpret_cast<uint32_t *>(lds + image_bytes)[tid] = 0u;
+
+    float acc = 0.f;
+    for (int chunk = 0; chunk < nchunk; ++chunk) {
+        const int slice = chunk * KS + ks;                         // global K slice of this wave
+        const bool slice_ok = slice < nslices;
+        const int slice_c = slice_ok ? slice : nslices - 1;
+        const int p_eff = slice_ok ? p_mine : 0;
+
+        // ---- 1. issue every plane and scale load of this wave, unconditionally -------------
+        u32x4 wlo[PH], whi[PH];
+        u32x4 sc[PH];
+#pragma unroll
+        for (int i = 0; i < PH; ++i) {
+            const u32x4 *wp = reinterpret_cast<const u32x4 *>(
+                a.planes + ((int64_t)i * a.m + row) * words + slice_c * (kSliceCols / 32) + q * 8);
+            wlo[i] = __builtin_nontemporal_load(wp);                // group 2q of the slice
+            whi[i] = __builtin_nontemporal_load(wp + 1);            // group 2q + 1
+            const int ii = min(i, max(p_mine, 1) - 1);             // stay inside the lane's own scale set
+            sc[i] = *reinterpret_cast<const u32x4 *>(sptr + ((int64_t)ii * a.m + row) * ngroups + slice_c * kSliceGroups);
+        }
+
+        // ---- 2. workgroup builds the activation image of this chunk ------------------------
+        if (chunk > 0) __syncthreads();                            // previous image and staging no longer read
+        {
+            // 2a. stage the chunk's activations in LDS, 16 bytes per thread and trip, coalesced
+            const int64_t col0 = (int64_t)chunk * chunk_cols;
+            const int per_req = chunk_cols / 8;                     // 16-byte units per request
+            const int total = nb * per_req;
+            u32x4 *stage = reinterpret_cast<u32x4 *>(lds + stage_off);
+            for (int base = 0; base < total; base += 2 * nthreads) {
+                u32x4 xv[2];
+                int idx[2];
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {                    // both loads in flight before any use
+                    idx[k2] = base + k2 * nthreads + tid;
+                    const int ic = min(idx[k2], total - 1);
+                    const int b = ic / per_req;
+                    const int64_t col = col0 + (int64_t)(ic - b * per_req) * 8;
+                    xv[k2] = *reinterpret_cast<const u32x4 *>(a.x + (int64_t)(b0 + b) * a.n + min(col, a.n - 8));
+                    if (col >= a.n) xv[k2] = u32x4{0, 0, 0, 0};     // ragged last chunk: columns past n are zero
+                }
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+                    if (idx[k2] < total) stage[idx[k2]] = xv[k2];
+            }
+            __syncthreads();
+            // 2b. one task = four columns (stride 4) of one request -> one dword in each of the four term rows
+            const unsigned short *xs = reinterpret_cast<const unsigned short *>(lds + stage_off);
+            const int ntask = nb * KS * 256;
+            for (int task = tid; task < ntask; task += nthreads) {
+                const int dw = task & 3, qa = (task >> 2) & 3, h = (task >> 4) & 1;
+                const int rest = task >> 5;
+                const int b = rest % nb, g = rest / nb;
+                // operand byte 8z + tt of lane quarter qa pairs with column 64h + 32(qa>>1) + 4tt + 3 - (2(qa&1) + z)
+                const int z = dw >> 1;
+                const int cl0 = 64 * h + 32 * (qa >> 1) + 16 * (dw & 1) + 3 - (2 * (qa & 1) + z);
+                const unsigned short *src = xs + b * chunk_cols + g * 128 + cl0;
+                const uint32_t v01 = (uint32_t)src[0] | ((uint32_t)src[4] << 16);
+                const uint32_t v23 = (uint32_t)src[8] | ((uint32_t)src[12] << 16);
+                // exact split into four E5M2 terms: top bytes of the running binary16 remainders
+                h2 r01 = __builtin_bit_cast(h2, v01), r23 = __builtin_bit_cast(h2, v23);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(lds + image_offset(g, h, qa, 4 * b, nrows) + 4 * dw);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
+                    const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
+                    r01 = r01 - __builtin_bit_cast(h2, t01);
+                    r23 = r23 - __builtin_bit_cast(h2, t23);
+                    dst[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);   // bytes: col0, col0+4, col0+8, col0+12
+                }
+            }
+        }
+        __syncthreads();
+
+        // scales of planes this lane must not use (beyond its precision, or a slice past the end) become zero
+#pragma unroll
+        for (int i = 0; i < PH; ++i)
+            if (!(i < p_eff)) sc[i] = u32x4{0, 0, 0, 0};
+
+        // ---- 3. per group: expand plane words, one MFMA per (group, plane), scale, accumulate
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            // after the transpose, register t of quarter q is dword q of group 2t + j of the slice
+            uint32_t wt[PH][4];
+#pragma unroll
+            for (int i = 0; i < PH; ++i) {
+                const u32x4 src = j ? whi[i] : wlo[i];
+                wt[i][0] = src.x; wt[i][1] = src.y; wt[i][2] = src.z; wt[i][3] = src.w;
+                quarter_transpose(wt[i][0], wt[i][1], wt[i][2], wt[i][3]);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int gl = 2 * t + j;                           // group inside the slice
+                const int gc = ks * kSliceGroups + gl;
+                // lanes whose operand row is unused read the 16 zero bytes behind the image
+                const int o_lo = arow < nrows ? image_offset(gc, 0, q, arow, nrows) : image_bytes;
+                const int o_hi = arow < nrows ? image_offset(gc, 1, q, arow, nrows) : image_bytes;
+                const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + o_lo);
+                const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + o_hi);
+                const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+#pragma unroll
+                for (int i = 0; i < PH; ++i) {
+                    const uint32_t w = wt[i][t];
+                    v8i wb = {0, 0, 0, 0, 0, 0, 0, 0};
+                    wb[0] = (int)((w & 0x88888888u) | 0x22222222u);
+                    wb[1] = (int)(((w << 1) & 0x88888888u) | 0x22222222u);
+                    wb[2] = (int)(((w << 2) & 0x88888888u) | 0x22222222u);
+                    wb[3] = (int)(((w << 3) & 0x88888888u) | 0x22222222u);
+                    v4f d = {0.f, 0.f, 0.f, 0.f};
+                    // A: E5M2 activation terms (cbsz = 1), B: FP4 signs (blgp = 4), no block scaling
+                    d = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, d, 1, 4, 0, 0, 0, 0);
+                    const uint32_t sw = sc[i][gl >> 1];
+                    const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
+                    const float s = (d[0] + d[1]) + (d[2] + d[3]);
+                    // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
+                    acc = fmaf(-alpha, s, acc);
+                }
+            }
+        }
+    }
+    return acc;
+}
+
+template <int P, bool MIXED>
 __global__ __launch_bounds__(1024) void plane_mfma_kernel(GemmArgs a, int KS, int RB, int nchunk)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -79,131 +220,34 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(GemmArgs a, int KS, in
     const int q = lane >> 4;                  // lane quarter: K sub-block on the weight side, request on the output side
     const int b0 = blockIdx.y * kMaxBatchTile;
     const int nb = min(kMaxBatchTile, a.batch - b0);
-    const int nrows = 4 * nb;
-    const int words = (int)(a.n >> 5);
-    const int ngroups = (int)(a.n >> 7);
 
     int64_t row = ((int64_t)blockIdx.x * RB + rb) * 16 + (lane & 15);
     const bool row_ok = row < a.m;
     if (!row_ok) row = a.m - 1;               // keep loads in bounds; the result is discarded
 
-    // precision of the request this lane reports on, and the deepest plane any request of the tile needs
-    int p_mine = 0, p_hi = 0;
-    for (int b = 0; b < nb; ++b) {
-        int pb = request_precision(a, b0 + b);
-        p_hi = max(p_hi, pb);
-        if (b == q) p_mine = pb;
-    }
-    const _Float16 *scale_set = a.scales[p_mine];
-
     float acc = 0.f;
-    for (int chunk = 0; chunk < nchunk; ++chunk) {
-        const int slice = chunk * KS + ks;                         // global K slice index of this wave
-        const int nslices = (int)(a.n / kSliceCols);
-        const bool slice_ok = slice < nslices;
-        const int slice_c = slice_ok ? slice : nslices - 1;
-
-        // ---- 1. issue this wave's plane and scale loads ------------------------------------
-        u32x4 wlo[P], whi[P];
-        uint4 sc[P];
-#pragma unroll
-        for (int i = 0; i < P; ++i) {
-            wlo[i] = u32x4{0, 0, 0, 0};
-            whi[i] = u32x4{0, 0, 0, 0};
-            sc[i] = make_uint4(0, 0, 0, 0);
-            if (i < p_hi) {
-                const u32x4 *wp = reinterpret_cast<const u32x4 *>(
-                    a.planes + ((int64_t)i * a.m + row) * words + slice_c * (kSliceCols / 32) + q * 8);
-                wlo[i] = __builtin_nontemporal_load(wp);            // group 2q of the slice
-                whi[i] = __builtin_nontemporal_load(wp + 1);        // group 2q + 1
-            }
-            if (i < p_mine)
-                sc[i] = *reinterpret_cast<const uint4 *>(
-                    scale_set + ((int64_t)i * a.m + row) * ngroups + slice_c * kSliceGroups);
+    if constexpr (!MIXED) {
+        acc = sweep<P>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, P, a.scales[P]);
+    } else {
+        // precision of the request this lane reports on, and the deepest plane any request of the tile needs
+        int p_mine = 0, p_hi = 0;
+        for (int b = 0; b < nb; ++b) {
+            const int pb = request_precision(a, b0 + b);
+            p_hi = max(p_hi, pb);
+            if (b == q) p_mine = pb;
         }
-
-        // ---- 2. workgroup builds the activation image of this chunk ------------------------
-        if (chunk > 0) __syncthreads();                            // previous image no longer read
-        {
-            const int chunk_cols = KS * kSliceCols;
-            const int64_t col0 = (int64_t)chunk * chunk_cols;
-            const int pairs = chunk_cols / 2;
-            for (int idx = tid; idx < nb * pairs; idx += nthreads) {
-                const int b = idx / pairs;
-                const int c = (idx - b * pairs) * 2;                // even column inside the chunk
-                uint32_t v = 0;
-                if (col0 + c < a.n)
-                    v = *reinterpret_cast<const uint32_t *>(a.x + (int64_t)(b0 + b) * a.n + col0 + c);
-                // exact split of both halves into four E5M2 terms (top bytes of the running remainders)
-                uint32_t t[4];
-                h2 r = __builtin_bit_cast(h2, v);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    t[k] = __builtin_bit_cast(uint32_t, r) & 0xFF00FF00u;
-                    r = r - __builtin_bit_cast(h2, t[k]);
-                }
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int cl = (c + e) & 127;                   // column inside its group
-                    const int g = (c + e) >> 7;
-                    const int h = cl >> 6, u = (cl >> 5) & 1, tt = (cl >> 2) & 7;
-                    const int inv = (~cl) & 3;                      // 3 - (cl & 3) = shift that exposes this bit
-                    const int qa = 2 * u + (inv >> 1);
-                    const int off = image_offset(g, h, qa, 4 * b, nrows) + 8 * (inv & 1) + tt;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) lds[off + 16 * k] = (unsigned char)(t[k] >> (e ? 24 : 8));
-                }
-            }
-        }
-        __syncthreads();
-
-        // ---- 3. per group: expand plane words, one MFMA per (group, plane), scale, accumulate
-        const int arow = lane & 15;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            // after the transpose, register t of quarter q is dword q of group 2t + j of the slice
-            uint32_t wt[P][4];
-#pragma unroll
-            for (int i = 0; i < P; ++i) {
-                const u32x4 src = j ? whi[i] : wlo[i];
-                wt[i][0] = src.x; wt[i][1] = src.y; wt[i][2] = src.z; wt[i][3] = src.w;
-                quarter_transpose(wt[i][0], wt[i][1], wt[i][2], wt[i][3]);
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int gl = 2 * t + j;                           // group inside the slice
-                v8i xa = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (arow < nrows) {
-                    const int gc = ks * kSliceGroups + gl;
-                    const uint4 lo = *reinterpret_cast<const uint4 *>(lds + image_offset(gc, 0, q, arow, nrows));
-                    const uint4 hi = *reinterpret_cast<const uint4 *>(lds + image_offset(gc, 1, q, arow, nrows));
-                    xa[0] = lo.x; xa[1] = lo.y; xa[2] = lo.z; xa[3] = lo.w;
-                    xa[4] = hi.x; xa[5] = hi.y; xa[6] = hi.z; xa[7] = hi.w;
-                }
-#pragma unroll
-                for (int i = 0; i < P; ++i) {
-                    if (i < p_hi) {
-                        const uint32_t w = wt[i][t];
-                        v8i wb = {0, 0, 0, 0, 0, 0, 0, 0};
-                        wb[0] = (int)((w & 0x88888888u) | 0x22222222u);
-                        wb[1] = (int)(((w << 1) & 0x88888888u) | 0x22222222u);
-                        wb[2] = (int)(((w << 2) & 0x88888888u) | 0x22222222u);
-                        wb[3] = (int)(((w << 3) & 0x88888888u) | 0x22222222u);
-                        v4f d = {0.f, 0.f, 0.f, 0.f};
-                        // A: E5M2 activation terms (cbsz = 1), B: FP4 signs (blgp = 4), no block scaling
-                        d = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, d, 1, 4, 0, 0, 0, 0);
-                        const uint32_t sw = (gl >> 1) == 0 ? sc[i].x : (gl >> 1) == 1 ? sc[i].y : (gl >> 1) == 2 ? sc[i].z : sc[i].w;
-                        const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
-                        const float s = (d[0] + d[1]) + (d[2] + d[3]);
-                        // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
-                        if (slice_ok) acc = fmaf(-alpha, s, acc);
-                    }
-                }
-            }
+        const _Float16 *sptr = a.scales[p_mine > 0 ? p_mine : p_hi];
+        // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
+        switch (p_hi) {
+        case 1: acc = sweep<1>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
+        case 2: if constexpr (P >= 2) acc = sweep<2>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
+        case 3: if constexpr (P >= 3) acc = sweep<3>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
+        case 4: if constexpr (P >= 4) acc = sweep<4>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
+        default: break;                                            // no request has a scale set: zeros
         }
     }
 
-    // ---- 4. combine the KS partial sums of each row block in a fixed order, store binary16 --
+    // ---- combine the KS partial sums of each row block in a fixed order, store binary16 -----
     __syncthreads();
     float *red = reinterpret_cast<float *>(lds);
     red[wave * 64 + lane] = acc;
@@ -220,11 +264,15 @@ struct Plan {
     size_t lds_bytes;
 };
 
+constexpr size_t kLdsBudget = 128 * 1024;     // of the 160 KiB per CU
+
 Plan make_plan(const GemmArgs &a)
 {
     const int nslices = (int)(a.n / kSliceCols);
     const int nb = a.batch < kMaxBatchTile ? a.batch : kMaxBatchTile;
-    const int ks_cap = 16 / nb;                       // activation image <= 64 KiB per chunk
+    // per slice and request: 4 KiB of operand image + 2 KiB of staged activations
+    int ks_cap = (int)(kLdsBudget / (6144 * (size_t)nb));
+    if (ks_cap > 16) ks_cap = 16;
     int KS = 1;
     for (int d = 1; d <= ks_cap && d <= nslices; ++d)
         if (nslices % d == 0) KS = d;
@@ -232,13 +280,27 @@ Plan make_plan(const GemmArgs &a)
     Plan pl;
     pl.KS = KS;
     pl.nchunk = (nslices + KS - 1) / KS;
-    pl.RB = KS >= 8 ? 1 : 8 / KS;
+    pl.RB = 1;
+    while (pl.RB * 2 * KS <= 16) pl.RB *= 2;                 // up to 16 waves share one activation image
     const int64_t row_blocks = (a.m + 15) / 16;
-    while (pl.RB > 1 && row_blocks / pl.RB < 512) pl.RB /= 2;     // keep enough workgroups to fill 256 CUs
-    size_t image = (size_t)KS * kSliceGroups * 512 * nb;
+    while (pl.RB > 1 && (row_blocks + pl.RB - 1) / pl.RB < 256) pl.RB /= 2;   // but keep one workgroup per CU
+    size_t image = (size_t)KS * kSliceGroups * 512 * nb + 16 + (size_t)KS * kSliceCols * 2 * nb;
     size_t red = (size_t)KS * pl.RB * 64 * sizeof(float);
     pl.lds_bytes = image > red ? image : red;
     return pl;
+}
+
+template <typename K>
+hipError_t launch_one(K kernel, const GemmArgs &a, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
+{
+    if (pl.lds_bytes > 64 * 1024) {
+        // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kernel, grid, block, pl.lds_bytes, stream, a, pl.KS, pl.RB, pl.nchunk);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -255,13 +317,15 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     const int64_t row_blocks = (a.m + 15) / 16;
     dim3 grid((unsigned)((row_blocks + pl.RB - 1) / pl.RB), (unsigned)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile));
     dim3 block(64 * pl.KS * pl.RB);
+    const bool mixed = a.uniform_p == 0;
+#define BCQ_LAUNCH(PP, MM) return launch_one(plane_mfma_kernel<PP, MM>, a, pl, grid, block, stream)
     switch (a.p_max) {
-    case 1: hipLaunchKernelGGL(plane_mfma_kernel<1>, grid, block, pl.lds_bytes, stream, a, pl.KS, pl.RB, pl.nchunk); break;
-    case 2: hipLaunchKernelGGL(plane_mfma_kernel<2>, grid, block, pl.lds_bytes, stream, a, pl.KS, pl.RB, pl.nchunk); break;
-    case 3: hipLaunchKernelGGL(plane_mfma_kernel<3>, grid, block, pl.lds_bytes, stream, a, pl.KS, pl.RB, pl.nchunk); break;
-    default: hipLaunchKernelGGL(plane_mfma_kernel<4>, grid, block, pl.lds_bytes, stream, a, pl.KS, pl.RB, pl.nchunk); break;
+    case 1: if (mixed) BCQ_LAUNCH(1, true); else BCQ_LAUNCH(1, false);
+    case 2: if (mixed) BCQ_LAUNCH(2, true); else BCQ_LAUNCH(2, false);
+    case 3: if (mixed) BCQ_LAUNCH(3, true); else BCQ_LAUNCH(3, false);
+    default: if (mixed) BCQ_LAUNCH(4, true); else BCQ_LAUNCH(4, false);
     }
-    return hipGetLastError();
+#undef BCQ_LAUNCH
 }
 
 }  // namespace bcq

@@ -7,20 +7,21 @@
 // is issued as ONE v_mfma_f32_16x16x128_f8f6f4:
 //
 //   * weight operand (MFMA "B", 16 columns = 16 weight rows): every weight bit
-//     becomes an FP4 (E2M1) code 0x2 | sign, i.e. exactly +-1.  Four AND/OR
-//     (three of them after a shift) turn a 32-bit plane word into the lane's four
-//     operand registers.  Which bit lands in which K slot is a fixed
-//     permutation, mirrored on the activation side.
+//     becomes the FP4 (E2M1) code 0x2 | sign, i.e. exactly +-1: one AND-OR per
+//     operand register, three of them after a shift.  Which bit lands in which
+//     K slot is a fixed permutation, mirrored on the activation side.
 //   * activation operand (MFMA "A", 16 rows): binary16 activations are split
 //     EXACTLY into four E5M2 terms (E5M2 is the top byte of binary16, so
 //     x = t0 + t1 + t2 + t3 with t_k = top byte of the running remainder).  Row
 //     4*b + k of the operand holds term k of request b, so one instruction
 //     serves up to four requests.  The split is done once per workgroup and
-//     parked in LDS in operand-register order.
+//     parked in LDS in operand-register order.  Operand rows of absent requests
+//     hold arbitrary finite or non-finite data: row m of the result depends on
+//     row m of the operand only, and those result rows are never stored.
 //   * result: lane (row r, request b) receives the four term sums of its own
 //     row, adds them, multiplies by alpha_i[r][group] of ITS request's
 //     precision, and accumulates in fp32.  Requests at different precisions
-//     share the plane sweep; a lane simply stops accumulating at p_b.
+//     share the plane sweep; a lane's scales beyond p_b are zero.
 //
 // Work split: a workgroup owns RB blocks of 16 rows and the whole K range;
 // wave (rb, ks) handles K slice ks (1024 columns) of row block rb, issues all
@@ -45,13 +46,35 @@ constexpr int kSliceGroups = 8;
 constexpr int kMaxBatchTile = 4;            // requests per MFMA (4 E5M2 terms each = 16 operand rows)
 constexpr int kMaxP = 4;                    // planes this kernel keeps in registers
 
-// Byte offset inside the LDS activation image.
-//   g: group within the chunk, h: operand register half (0: regs 0-3, 1: regs 4-7),
-//   qa: lane quarter, row: 4*request + term, nrows = 4 * requests in the tile.
-__device__ __forceinline__ int image_offset(int g, int h, int qa, int row, int nrows)
-{
-    return ((((g * 2 + h) * 4 + qa) * nrows) + row) * 16;
-}
+// Uniform launch parameters, computed on the host so the kernel does no address algebra of its own.
+struct PlaneMfmaParams {
+    const unsigned char *planes;            // plane 0
+    const unsigned char *x;                 // activations of request 0 of the whole batch
+    _Float16 *y;
+    const unsigned char *scales[BCQ_MAX_PLANES + 1];   // scale set per precision (bytes)
+    const int32_t *p_req;                   // per-request precisions (mixed) or nullptr
+    uint32_t plane_stride;                  // bytes between planes:      m * n / 8
+    uint32_t row_stride;                    // bytes between plane rows:  n / 8
+    uint32_t scale_plane_stride;            // bytes between scale planes: m * (n/128) * 2
+    uint32_t scale_row_stride;              // bytes between scale rows:   (n/128) * 2
+    uint32_t x_stride;                      // bytes between requests:    n * 2
+    uint32_t m;
+    int batch, p_max, uniform_p;
+    int KS, RB, nchunk, nslices;
+};
+
+// LDS layout of one chunk for NB requests per tile and KS slices:
+//   [0, image)        operand image: 16-byte rows at ((g*2 + h)*4 + qa)*4NB + row
+//   [image, total)    staged binary16 activations of the chunk, request-major
+template <int NB>
+struct Lds {
+    static constexpr int kRows = 4 * NB;
+    static constexpr int kGroupBytes = 2 * 4 * kRows * 16;          // one group's image: 512 * NB
+    static constexpr int kSliceImage = kSliceGroups * kGroupBytes;   // 4 KiB * NB
+    static constexpr int kSliceStage = kSliceCols * 2;               // per request
+    __host__ __device__ static constexpr int stage_off(int KS) { return KS * kSliceImage; }
+    __host__ __device__ static constexpr int total(int KS) { return KS * (kSliceImage + NB * kSliceStage); }
+};
 
 // 4x4 transpose of one dword per register across the four lane quarters
 // (lanes l, l+16, l+32, l+48): afterwards register t of quarter q holds what
@@ -65,93 +88,113 @@ __device__ __forceinline__ void quarter_transpose(uint32_t &v0, uint32_t &v1, ui
     s = __builtin_amdgcn_permlane16_swap(v2, v3, false, false); v2 = s[0]; v3 = s[1];
 }
 
-// Sweep of one wave over its K slices for PH planes; returns this lane's partial sum.
-//   p_mine   precision of the request this lane reports on (0: none)
-//   sptr     scale set of that precision (any valid set when p_mine == 0)
-template <int PH>
-__device__ __forceinline__ float sweep(const GemmArgs &a, unsigned char *lds, int KS, int nchunk, int ks, int q, int lane,
-                                       int tid, int nthreads, int b0, int nb, int64_t row, int p_mine,
-                                       const _Float16 *sptr)
+// 32 weight bits -> the lane's four FP4 operand registers (8 codes each).
+// Register s, nibble i carries bit 4i + 3 - s in its sign position over the code of 1.0.
+// `sign` and `one` hold 0x88888888 and 0x22222222 in registers so each line is one V_AND_OR_B32.
+__device__ __forceinline__ v8i expand_plane_word(uint32_t w, uint32_t sign, uint32_t one)
 {
-    const int nrows = 4 * nb;
-    const int words = (int)(a.n >> 5);
-    const int ngroups = (int)(a.n >> 7);
-    const int nslices = (int)(a.n / kSliceCols);
-    const int chunk_cols = KS * kSliceCols;
-    const int image_bytes = KS * kSliceGroups * 128 * nrows;      // followed by 16 zero bytes, then the staging area
-    const int stage_off = image_bytes + 16;
-    const int arow = lane & 15;
+    v8i r = {0, 0, 0, 0, 0, 0, 0, 0};
+    r[0] = (int)((w & sign) | one);
+    r[1] = (int)(((w << 1) & sign) | one);
+    r[2] = (int)(((w << 2) & sign) | one);
+    r[3] = (int)(((w << 3) & sign) | one);
+    return r;
+}
 
-    if (tid < 4) reinterpret_cast<uint32_t *>(lds + image_bytes)[tid] = 0u;
+// Sweep of one wave over its K slices for PH planes; returns this lane's partial sum.
+//   voff_w   this lane's byte offset into a plane: row * row_stride + q * 32
+//   voff_s   this lane's byte offset into a scale plane: row * scale_row_stride
+//   p_mine   precision of the request this lane reports on (0: none); sbase its scale set
+template <int PH, int NB>
+__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int q, int r16, int tid,
+                                       int nthreads, int b0, int nb, uint32_t voff_w, uint32_t voff_s, int p_mine,
+                                       const unsigned char *sbase)
+{
+    using L = Lds<NB>;
+    const int KS = pr.KS;
+    const int stage_off = L::stage_off(KS);
+    const int units = KS * (kSliceCols / 8);                        // 16-byte activation units per request and chunk
+
+    // constants kept in registers so that (w & sign) | one is a single three-operand instruction
+    uint32_t sign = 0x88888888u, one = 0x22222222u;
+    asm volatile("" : "+v"(one));
+    asm volatile("" : "+s"(sign));
+
+    // operand-image address of this lane: row min(r16, 4NB-1) of quarter q, first group of the wave's slice
+    const int arow = r16 < L::kRows ? r16 : L::kRows - 1;
+    const int img_lane = ks * L::kSliceImage + (q * L::kRows + arow) * 16;
+
+    // stage-2 task constants: task = 32 * group + (h, qa, dw); a thread keeps (h, qa, dw) and strides over groups
+    const int dw = tid & 3, qa = (tid >> 2) & 3, h = (tid >> 4) & 1, z = dw >> 1;
+    // operand byte 8z + tt of lane quarter qa pairs with column 64h + 32(qa>>1) + 4tt + 3 - (2(qa&1) + z)
+    const int cl0 = 64 * h + 32 * (qa >> 1) + 16 * (dw & 1) + 3 - (2 * (qa & 1) + z);
+    const int task_src = stage_off + ((tid >> 5) * 128 + cl0) * 2;
+    const int task_dst = (tid >> 5) * L::kGroupBytes + ((h * 4 + qa) * L::kRows) * 16 + 4 * dw;
+    const int task_groups = nthreads >> 5;                          // groups covered per trip
 
     float acc = 0.f;
-    for (int chunk = 0; chunk < nchunk; ++chunk) {
-        const int slice = chunk * KS + ks;                         // global K slice of this wave
-        const bool slice_ok = slice < nslices;
-        const int slice_c = slice_ok ? slice : nslices - 1;
+    for (int chunk = 0; chunk < pr.nchunk; ++chunk) {
+        const int slice = chunk * KS + ks;                          // global K slice of this wave
+        const bool slice_ok = slice < pr.nslices;
+        const int slice_c = slice_ok ? slice : pr.nslices - 1;
         const int p_eff = slice_ok ? p_mine : 0;
+        const uint32_t chunk_byte0 = (uint32_t)chunk * KS * kSliceCols * 2;   // first activation byte of the chunk
+        const uint32_t x_bytes = pr.x_stride;                                 // bytes per request = columns * 2
 
-        // ---- 1. issue every plane and scale load of this wave, unconditionally -------------
-        u32x4 wlo[PH], whi[PH];
-        u32x4 sc[PH];
+        // ---- 1. activations first (they are needed first), then every plane and scale load --
+        u32x4 xv[NB][2];
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2) {
+                const uint32_t u = k2 * nthreads + tid;
+                uint32_t off = chunk_byte0 + u * 16;
+                const bool ok = u < (uint32_t)units && off < x_bytes && b < nb;
+                off = ok ? off : 0;
+                xv[b][k2] = *reinterpret_cast<const u32x4 *>(pr.x + (size_t)(b0 + (b < nb ? b : 0)) * x_bytes + off);
+                if (!ok) xv[b][k2] = u32x4{0, 0, 0, 0};             // ragged last chunk: columns past n are zero
+            }
+        u32x4 wlo[PH], whi[PH], sc[PH];
 #pragma unroll
         for (int i = 0; i < PH; ++i) {
-            const u32x4 *wp = reinterpret_cast<const u32x4 *>(
-                a.planes + ((int64_t)i * a.m + row) * words + slice_c * (kSliceCols / 32) + q * 8);
-            wlo[i] = __builtin_nontemporal_load(wp);                // group 2q of the slice
-            whi[i] = __builtin_nontemporal_load(wp + 1);            // group 2q + 1
-            const int ii = min(i, max(p_mine, 1) - 1);             // stay inside the lane's own scale set
-            sc[i] = *reinterpret_cast<const u32x4 *>(sptr + ((int64_t)ii * a.m + row) * ngroups + slice_c * kSliceGroups);
+            const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8);
+            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_w));        // group 2q
+            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_w + 16));   // group 2q + 1
+            const int ii = min(i, max(p_mine, 1) - 1);              // stay inside the lane's own scale set
+            sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + voff_s +
+                                                     (uint32_t)slice_c * (kSliceGroups * 2));
         }
 
-        // ---- 2. workgroup builds the activation image of this chunk ------------------------
-        if (chunk > 0) __syncthreads();                            // previous image and staging no longer read
-        {
-            // 2a. stage the chunk's activations in LDS, 16 bytes per thread and trip, coalesced
-            const int64_t col0 = (int64_t)chunk * chunk_cols;
-            const int per_req = chunk_cols / 8;                     // 16-byte units per request
-            const int total = nb * per_req;
-            u32x4 *stage = reinterpret_cast<u32x4 *>(lds + stage_off);
-            for (int base = 0; base < total; base += 2 * nthreads) {
-                u32x4 xv[2];
-                int idx[2];
+        // ---- 2. workgroup builds the operand image of this chunk --------------------------
+        if (chunk > 0) __syncthreads();                             // previous image and staging no longer read
 #pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {                    // both loads in flight before any use
-                    idx[k2] = base + k2 * nthreads + tid;
-                    const int ic = min(idx[k2], total - 1);
-                    const int b = ic / per_req;
-                    const int64_t col = col0 + (int64_t)(ic - b * per_req) * 8;
-                    xv[k2] = *reinterpret_cast<const u32x4 *>(a.x + (int64_t)(b0 + b) * a.n + min(col, a.n - 8));
-                    if (col >= a.n) xv[k2] = u32x4{0, 0, 0, 0};     // ragged last chunk: columns past n are zero
-                }
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
-                    if (idx[k2] < total) stage[idx[k2]] = xv[k2];
+            for (int k2 = 0; k2 < 2; ++k2) {
+                const int u = k2 * nthreads + tid;
+                if (u < units) *reinterpret_cast<u32x4 *>(lds + stage_off + b * KS * L::kSliceStage + u * 16) = xv[b][k2];
             }
-            __syncthreads();
-            // 2b. one task = four columns (stride 4) of one request -> one dword in each of the four term rows
-            const unsigned short *xs = reinterpret_cast<const unsigned short *>(lds + stage_off);
-            const int ntask = nb * KS * 256;
-            for (int task = tid; task < ntask; task += nthreads) {
-                const int dw = task & 3, qa = (task >> 2) & 3, h = (task >> 4) & 1;
-                const int rest = task >> 5;
-                const int b = rest % nb, g = rest / nb;
-                // operand byte 8z + tt of lane quarter qa pairs with column 64h + 32(qa>>1) + 4tt + 3 - (2(qa&1) + z)
-                const int z = dw >> 1;
-                const int cl0 = 64 * h + 32 * (qa >> 1) + 16 * (dw & 1) + 3 - (2 * (qa & 1) + z);
-                const unsigned short *src = xs + b * chunk_cols + g * 128 + cl0;
-                const uint32_t v01 = (uint32_t)src[0] | ((uint32_t)src[4] << 16);
-                const uint32_t v23 = (uint32_t)src[8] | ((uint32_t)src[12] << 16);
+        __syncthreads();
+        // one task = four columns (stride 4) of one request -> one dword in each of the four term rows
+        for (int g = tid >> 5, src = task_src, dst = task_dst; g < KS * kSliceGroups;
+             g += task_groups, src += task_groups * 256, dst += task_groups * L::kGroupBytes) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const unsigned short *s16 = reinterpret_cast<const unsigned short *>(lds + src + b * KS * L::kSliceStage);
+                const uint32_t v01 = (uint32_t)s16[0] | ((uint32_t)s16[4] << 16);
+                const uint32_t v23 = (uint32_t)s16[8] | ((uint32_t)s16[12] << 16);
                 // exact split into four E5M2 terms: top bytes of the running binary16 remainders
                 h2 r01 = __builtin_bit_cast(h2, v01), r23 = __builtin_bit_cast(h2, v23);
-                uint32_t *dst = reinterpret_cast<uint32_t *>(lds + image_offset(g, h, qa, 4 * b, nrows) + 4 * dw);
+                uint32_t *d32 = reinterpret_cast<uint32_t *>(lds + dst + b * 64);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
                     const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
-                    r01 = r01 - __builtin_bit_cast(h2, t01);
-                    r23 = r23 - __builtin_bit_cast(h2, t23);
-                    dst[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);   // bytes: col0, col0+4, col0+8, col0+12
+                    if (j < 3) {
+                        r01 = r01 - __builtin_bit_cast(h2, t01);
+                        r23 = r23 - __builtin_bit_cast(h2, t23);
+                    }
+                    d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);   // bytes: col0, col0+4, col0+8, col0+12
                 }
             }
         }
@@ -169,34 +212,29 @@ __device__ __forceinline__ float sweep(const GemmArgs &a, unsigned char *lds, in
             uint32_t wt[PH][4];
 #pragma unroll
             for (int i = 0; i < PH; ++i) {
-                const u32x4 src = j ? whi[i] : wlo[i];
-                wt[i][0] = src.x; wt[i][1] = src.y; wt[i][2] = src.z; wt[i][3] = src.w;
+                const u32x4 srcw = j ? whi[i] : wlo[i];
+                wt[i][0] = srcw.x; wt[i][1] = srcw.y; wt[i][2] = srcw.z; wt[i][3] = srcw.w;
                 quarter_transpose(wt[i][0], wt[i][1], wt[i][2], wt[i][3]);
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int gl = 2 * t + j;                           // group inside the slice
-                const int gc = ks * kSliceGroups + gl;
-                // lanes whose operand row is unused read the 16 zero bytes behind the image
-                const int o_lo = arow < nrows ? image_offset(gc, 0, q, arow, nrows) : image_bytes;
-                const int o_hi = arow < nrows ? image_offset(gc, 1, q, arow, nrows) : image_bytes;
-                const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + o_lo);
-                const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + o_hi);
+                const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes);
+                const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes + L::kGroupBytes / 2);
                 const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+                v4f d[PH];
 #pragma unroll
                 for (int i = 0; i < PH; ++i) {
-                    const uint32_t w = wt[i][t];
-                    v8i wb = {0, 0, 0, 0, 0, 0, 0, 0};
-                    wb[0] = (int)((w & 0x88888888u) | 0x22222222u);
-                    wb[1] = (int)(((w << 1) & 0x88888888u) | 0x22222222u);
-                    wb[2] = (int)(((w << 2) & 0x88888888u) | 0x22222222u);
-                    wb[3] = (int)(((w << 3) & 0x88888888u) | 0x22222222u);
-                    v4f d = {0.f, 0.f, 0.f, 0.f};
-                    // A: E5M2 activation terms (cbsz = 1), B: FP4 signs (blgp = 4), no block scaling
-                    d = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, d, 1, 4, 0, 0, 0, 0);
+                    const v8i wb = expand_plane_word(wt[i][t], sign, one);
+                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+                    // A: E5M2 activation terms (cbsz = 1), B: FP4 weight codes (blgp = 4), no block scaling
+                    d[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, zero, 1, 4, 0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < PH; ++i) {
                     const uint32_t sw = sc[i][gl >> 1];
                     const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
-                    const float s = (d[0] + d[1]) + (d[2] + d[3]);
+                    const float s = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
                     // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
                     acc = fmaf(-alpha, s, acc);
                 }
@@ -206,8 +244,8 @@ __device__ __forceinline__ float sweep(const GemmArgs &a, unsigned char *lds, in
     return acc;
 }
 
-template <int P, bool MIXED>
-__global__ __launch_bounds__(1024) void plane_mfma_kernel(GemmArgs a, int KS, int RB, int nchunk)
+template <int P, int NB, bool MIXED>
+__global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -215,35 +253,41 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(GemmArgs a, int KS, in
     const int nthreads = blockDim.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int KS = pr.KS;
     const int ks = wave % KS;                 // K slice of this wave inside a chunk
     const int rb = wave / KS;                 // row block of this wave inside the workgroup
     const int q = lane >> 4;                  // lane quarter: K sub-block on the weight side, request on the output side
+    const int r16 = lane & 15;
     const int b0 = blockIdx.y * kMaxBatchTile;
-    const int nb = min(kMaxBatchTile, a.batch - b0);
+    const int nb = min(NB, pr.batch - b0);
 
-    int64_t row = ((int64_t)blockIdx.x * RB + rb) * 16 + (lane & 15);
-    const bool row_ok = row < a.m;
-    if (!row_ok) row = a.m - 1;               // keep loads in bounds; the result is discarded
+    uint32_t row = (blockIdx.x * pr.RB + rb) * 16 + r16;
+    const bool row_ok = row < pr.m;
+    if (!row_ok) row = pr.m - 1;              // keep loads in bounds; the result is discarded
+    const uint32_t voff_w = row * pr.row_stride + q * 32;
+    const uint32_t voff_s = row * pr.scale_row_stride;
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, P, a.scales[P]);
+        acc = sweep<P, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, P, pr.scales[P]);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs
         int p_mine = 0, p_hi = 0;
         for (int b = 0; b < nb; ++b) {
-            const int pb = request_precision(a, b0 + b);
+            int pb = pr.p_req[b0 + b];
+            pb = pb < 1 ? 1 : (pb > pr.p_max ? pr.p_max : pb);
+            if (!pr.scales[pb]) pb = 0;        // no scale set for that precision: the request yields zeros
             p_hi = max(p_hi, pb);
             if (b == q) p_mine = pb;
         }
-        const _Float16 *sptr = a.scales[p_mine > 0 ? p_mine : p_hi];
+        const unsigned char *sbase = pr.scales[p_mine > 0 ? p_mine : p_hi];
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
-        case 2: if constexpr (P >= 2) acc = sweep<2>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
-        case 3: if constexpr (P >= 3) acc = sweep<3>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
-        case 4: if constexpr (P >= 4) acc = sweep<4>(a, lds, KS, nchunk, ks, q, lane, tid, nthreads, b0, nb, row, p_mine, sptr); break;
-        default: break;                                            // no request has a scale set: zeros
+        case 1: acc = sweep<1, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 2: acc = sweep<2, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 3: acc = sweep<3, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 4: acc = sweep<4, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        default: break;                                             // no request has a scale set: zeros
         }
     }
 
@@ -255,43 +299,47 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(GemmArgs a, int KS, in
     if (ks == 0) {
         float v = 0.f;
         for (int k = 0; k < KS; ++k) v += red[(rb * KS + k) * 64 + lane];
-        if (row_ok && q < nb) a.y[(int64_t)(b0 + q) * a.m + row] = (_Float16)v;
+        if (row_ok && q < nb) pr.y[(size_t)(b0 + q) * pr.m + row] = (_Float16)v;
     }
 }
 
+constexpr size_t kLdsBudget = 128 * 1024;     // of the 160 KiB per CU
+
+int lds_total(int NB, int KS)
+{
+    return NB == 1 ? Lds<1>::total(KS) : NB == 2 ? Lds<2>::total(KS) : Lds<4>::total(KS);
+}
+
 struct Plan {
-    int KS, RB, nchunk;
+    int NB, KS, RB, nchunk;
     size_t lds_bytes;
 };
-
-constexpr size_t kLdsBudget = 128 * 1024;     // of the 160 KiB per CU
 
 Plan make_plan(const GemmArgs &a)
 {
     const int nslices = (int)(a.n / kSliceCols);
-    const int nb = a.batch < kMaxBatchTile ? a.batch : kMaxBatchTile;
-    // per slice and request: 4 KiB of operand image + 2 KiB of staged activations
-    int ks_cap = (int)(kLdsBudget / (6144 * (size_t)nb));
-    if (ks_cap > 16) ks_cap = 16;
+    Plan pl;
+    pl.NB = a.batch == 1 ? 1 : a.batch == 2 ? 2 : 4;
+    int ks_cap = 16;
+    while (ks_cap > 1 && (size_t)lds_total(pl.NB, ks_cap) > kLdsBudget) --ks_cap;
     int KS = 1;
     for (int d = 1; d <= ks_cap && d <= nslices; ++d)
         if (nslices % d == 0) KS = d;
     if (KS < ks_cap / 2 && nslices > ks_cap) KS = ks_cap;   // awkward factorisation: ragged last chunk instead
-    Plan pl;
     pl.KS = KS;
     pl.nchunk = (nslices + KS - 1) / KS;
     pl.RB = 1;
-    while (pl.RB * 2 * KS <= 16) pl.RB *= 2;                 // up to 16 waves share one activation image
+    while (pl.RB * 2 * KS <= 16) pl.RB *= 2;                 // up to 16 waves share one operand image
     const int64_t row_blocks = (a.m + 15) / 16;
     while (pl.RB > 1 && (row_blocks + pl.RB - 1) / pl.RB < 256) pl.RB /= 2;   // but keep one workgroup per CU
-    size_t image = (size_t)KS * kSliceGroups * 512 * nb + 16 + (size_t)KS * kSliceCols * 2 * nb;
+    size_t image = (size_t)lds_total(pl.NB, KS);
     size_t red = (size_t)KS * pl.RB * 64 * sizeof(float);
     pl.lds_bytes = image > red ? image : red;
     return pl;
 }
 
 template <typename K>
-hipError_t launch_one(K kernel, const GemmArgs &a, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
+hipError_t launch_one(K kernel, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
 {
     if (pl.lds_bytes > 64 * 1024) {
         // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
@@ -299,33 +347,63 @@ hipError_t launch_one(K kernel, const GemmArgs &a, const Plan &pl, dim3 grid, di
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kernel, grid, block, pl.lds_bytes, stream, a, pl.KS, pl.RB, pl.nchunk);
+    hipLaunchKernelGGL(kernel, grid, block, pl.lds_bytes, stream, pr);
     return hipGetLastError();
+}
+
+template <int NB>
+hipError_t launch_nb(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
+{
+    if (a.uniform_p == 0) return launch_one(plane_mfma_kernel<kMaxP, NB, true>, pr, pl, grid, block, stream);
+    switch (a.uniform_p) {
+    case 1: return launch_one(plane_mfma_kernel<1, NB, false>, pr, pl, grid, block, stream);
+    case 2: return launch_one(plane_mfma_kernel<2, NB, false>, pr, pl, grid, block, stream);
+    case 3: return launch_one(plane_mfma_kernel<3, NB, false>, pr, pl, grid, block, stream);
+    default: return launch_one(plane_mfma_kernel<4, NB, false>, pr, pl, grid, block, stream);
+    }
 }
 
 }  // namespace
 
 bool plane_mfma_supports(const GemmArgs &a)
 {
-    return a.group == 128 && (a.n % kSliceCols) == 0 && a.p_max <= kMaxP &&
+    // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
+    const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31) &&
+                              a.m < (int64_t(1) << 27);
+    return a.group == 128 && (a.n % kSliceCols) == 0 && a.p_max <= kMaxP && small_enough &&
            (a.batch + kMaxBatchTile - 1) / kMaxBatchTile <= 65535;
 }
 
 hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
 {
     const Plan pl = make_plan(a);
+    PlaneMfmaParams pr{};
+    pr.planes = reinterpret_cast<const unsigned char *>(a.planes);
+    pr.x = reinterpret_cast<const unsigned char *>(a.x);
+    pr.y = a.y;
+    for (int q = 0; q <= BCQ_MAX_PLANES; ++q) pr.scales[q] = reinterpret_cast<const unsigned char *>(a.scales[q]);
+    pr.p_req = a.p_req;
+    pr.plane_stride = (uint32_t)(a.m * (a.n / 8));
+    pr.row_stride = (uint32_t)(a.n / 8);
+    pr.scale_plane_stride = (uint32_t)(a.m * (a.n / 128) * 2);
+    pr.scale_row_stride = (uint32_t)((a.n / 128) * 2);
+    pr.x_stride = (uint32_t)(a.n * 2);
+    pr.m = (uint32_t)a.m;
+    pr.batch = a.batch;
+    pr.p_max = a.p_max;
+    pr.uniform_p = a.uniform_p;
+    pr.KS = pl.KS;
+    pr.RB = pl.RB;
+    pr.nchunk = pl.nchunk;
+    pr.nslices = (int)(a.n / kSliceCols);
     const int64_t row_blocks = (a.m + 15) / 16;
     dim3 grid((unsigned)((row_blocks + pl.RB - 1) / pl.RB), (unsigned)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile));
     dim3 block(64 * pl.KS * pl.RB);
-    const bool mixed = a.uniform_p == 0;
-#define BCQ_LAUNCH(PP, MM) return launch_one(plane_mfma_kernel<PP, MM>, a, pl, grid, block, stream)
-    switch (a.p_max) {
-    case 1: if (mixed) BCQ_LAUNCH(1, true); else BCQ_LAUNCH(1, false);
-    case 2: if (mixed) BCQ_LAUNCH(2, true); else BCQ_LAUNCH(2, false);
-    case 3: if (mixed) BCQ_LAUNCH(3, true); else BCQ_LAUNCH(3, false);
-    default: if (mixed) BCQ_LAUNCH(4, true); else BCQ_LAUNCH(4, false);
+    switch (pl.NB) {
+    case 1: return launch_nb<1>(a, pr, pl, grid, block, stream);
+    case 2: return launch_nb<2>(a, pr, pl, grid, block, stream);
+    default: return launch_nb<4>(a, pr, pl, grid, block, stream);
     }
-#undef BCQ_LAUNCH
 }
 
 }  // namespace bcq

@@ -61,11 +61,14 @@ struct PlaneMfmaParams {
     uint32_t m;
     int batch, p_max, uniform_p;
     int KS, RB, nchunk, nslices;
+    float inv_quarter, inv_ks;              // 1 / (threads / 4) and 1 / KS, for small exact integer divisions
 };
 
 // LDS layout of one chunk for NB requests per tile and KS slices:
 //   [0, image)        operand image: 16-byte rows at ((g*2 + h)*4 + qa)*4NB + row
-//   [image, total)    staged binary16 activations of the chunk, request-major
+//   [image, scales)   staged binary16 activations of the chunk, request-major
+//   [scales, red)     staged scales of the chunk, 16 bytes per thread (uniform precision)
+//   [red, total)      one fp32 partial sum per thread for the final combine
 template <int NB>
 struct Lds {
     static constexpr int kRows = 4 * NB;
@@ -73,7 +76,11 @@ struct Lds {
     static constexpr int kSliceImage = kSliceGroups * kGroupBytes;   // 4 KiB * NB
     static constexpr int kSliceStage = kSliceCols * 2;               // per request
     __host__ __device__ static constexpr int stage_off(int KS) { return KS * kSliceImage; }
-    __host__ __device__ static constexpr int total(int KS) { return KS * (kSliceImage + NB * kSliceStage); }
+    // staged scales of the chunk (uniform precision only): one 16-byte unit per thread
+    __host__ __device__ static constexpr int scale_off(int KS) { return KS * (kSliceImage + NB * kSliceStage); }
+    // per-wave partial sums for the final combine
+    __host__ __device__ static constexpr int red_off(int KS, int RB) { return scale_off(KS) + 64 * KS * RB * 16; }
+    __host__ __device__ static constexpr int total(int KS, int RB) { return red_off(KS, RB) + 64 * KS * RB * 4; }
 };
 
 // 4x4 transpose of one dword per register across the four lane quarters
@@ -102,17 +109,20 @@ __device__ __forceinline__ v8i expand_plane_word(uint32_t w, uint32_t sign, uint
 }
 
 // Sweep of one wave over its K slices for PH planes; returns this lane's partial sum.
-//   voff_w   this lane's byte offset into a plane: row * row_stride + q * 32
+//   voff_w   this lane's byte offset into a plane: row * row_stride + q * 16
 //   voff_s   this lane's byte offset into a scale plane: row * scale_row_stride
 //   p_mine   precision of the request this lane reports on (0: none); sbase its scale set
-template <int PH, int NB>
-__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int q, int r16, int tid,
-                                       int nthreads, int b0, int nb, uint32_t voff_w, uint32_t voff_s, int p_mine,
-                                       const unsigned char *sbase)
+// MIXED: every lane loads its own request's scales from global memory.  Otherwise the
+// workgroup stages the (shared) scale set of the chunk in LDS, one 16-byte unit per thread.
+template <int PH, int NB, bool MIXED>
+__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int q, int r16,
+                                       int tid, int nthreads, int b0, int nb, uint32_t voff_w, uint32_t voff_s,
+                                       int p_mine, const unsigned char *sbase)
 {
     using L = Lds<NB>;
     const int KS = pr.KS;
     const int stage_off = L::stage_off(KS);
+    const int scale_off = L::scale_off(KS);
     const int units = KS * (kSliceCols / 8);                        // 16-byte activation units per request and chunk
 
     // constants kept in registers so that (w & sign) | one is a single three-operand instruction
@@ -132,6 +142,15 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
     const int task_dst = (tid >> 5) * L::kGroupBytes + ((h * 4 + qa) * L::kRows) * 16 + 4 * dw;
     const int task_groups = nthreads >> 5;                          // groups covered per trip
 
+    // scale staging (uniform precision): thread tid fetches unit (plane sp, row srow, slice ssl) of the chunk
+    const int quarter = nthreads >> 2;                              // units per plane: 16 rows * RB * KS
+    const int sp = (int)(((float)tid + 0.5f) * pr.inv_quarter);
+    const int su = tid - sp * quarter;
+    const int srow_local = (int)(((float)su + 0.5f) * pr.inv_ks);   // row inside the workgroup's RB*16 rows
+    const int ssl = su - srow_local * KS;
+    const uint32_t srow = min((uint32_t)(blockIdx.x * pr.RB * 16 + srow_local), pr.m - 1);
+    const int my_scale_unit = ((rb * 16 + r16) * KS + ks) * 16;     // + plane * quarter * 16
+
     float acc = 0.f;
     for (int chunk = 0; chunk < pr.nchunk; ++chunk) {
         const int slice = chunk * KS + ks;                          // global K slice of this wave
@@ -141,7 +160,11 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         const uint32_t chunk_byte0 = (uint32_t)chunk * KS * kSliceCols * 2;   // first activation byte of the chunk
         const uint32_t x_bytes = pr.x_stride;                                 // bytes per request = columns * 2
 
-        // ---- 1. activations first (they are needed first), then every plane and scale load --
+        // ---- 1. loads in the order of use: activations, scales, then the two halves of every plane.
+        // The wave raises its issue priority for the burst so that its loads enter the memory queues
+        // together instead of interleaved with those of younger waves: waves then receive their data
+        // one after the other and the arithmetic of the early ones overlaps the loads of the late ones.
+        __builtin_amdgcn_s_setprio(3);
         u32x4 xv[NB][2];
 #pragma unroll
         for (int b = 0; b < NB; ++b)
@@ -154,16 +177,30 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 xv[b][k2] = *reinterpret_cast<const u32x4 *>(pr.x + (size_t)(b0 + (b < nb ? b : 0)) * x_bytes + off);
                 if (!ok) xv[b][k2] = u32x4{0, 0, 0, 0};             // ragged last chunk: columns past n are zero
             }
-        u32x4 wlo[PH], whi[PH], sc[PH];
+        u32x4 sc[PH], sstage;
+        if constexpr (MIXED) {
 #pragma unroll
-        for (int i = 0; i < PH; ++i) {
-            const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8);
-            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_w));        // group 2q
-            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_w + 16));   // group 2q + 1
-            const int ii = min(i, max(p_mine, 1) - 1);              // stay inside the lane's own scale set
-            sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + voff_s +
-                                                     (uint32_t)slice_c * (kSliceGroups * 2));
+            for (int i = 0; i < PH; ++i) {
+                const int ii = min(i, max(p_mine, 1) - 1);          // stay inside the lane's own scale set
+                sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + voff_s +
+                                                         (uint32_t)slice_c * (kSliceGroups * 2));
+            }
+        } else {
+            const int sslice = min(chunk * KS + ssl, pr.nslices - 1);
+            const int spc = sp < PH ? sp : PH - 1;
+            sstage = *reinterpret_cast<const u32x4 *>(sbase + (size_t)spc * pr.scale_plane_stride +
+                                                      srow * pr.scale_row_stride + (uint32_t)sslice * (kSliceGroups * 2));
         }
+        u32x4 wlo[PH], whi[PH];
+#pragma unroll
+        for (int i = 0; i < PH; ++i)                                // groups q of the slice; 64 contiguous bytes per row
+            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
+                pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w));
+#pragma unroll
+        for (int i = 0; i < PH; ++i)                                // groups 4 + q
+            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
+                pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w + 64));
+        __builtin_amdgcn_s_setprio(0);
 
         // ---- 2. workgroup builds the operand image of this chunk --------------------------
         if (chunk > 0) __syncthreads();                             // previous image and staging no longer read
@@ -174,6 +211,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 const int u = k2 * nthreads + tid;
                 if (u < units) *reinterpret_cast<u32x4 *>(lds + stage_off + b * KS * L::kSliceStage + u * 16) = xv[b][k2];
             }
+        if constexpr (!MIXED) *reinterpret_cast<u32x4 *>(lds + scale_off + tid * 16) = sstage;
         __syncthreads();
         // one task = four columns (stride 4) of one request -> one dword in each of the four term rows
         for (int g = tid >> 5, src = task_src, dst = task_dst; g < KS * kSliceGroups;
@@ -198,6 +236,11 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 }
             }
         }
+        if constexpr (!MIXED) {
+#pragma unroll
+            for (int i = 0; i < PH; ++i)
+                sc[i] = *reinterpret_cast<const u32x4 *>(lds + scale_off + i * quarter * 16 + my_scale_unit);
+        }
         __syncthreads();
 
         // scales of planes this lane must not use (beyond its precision, or a slice past the end) become zero
@@ -208,7 +251,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         // ---- 3. per group: expand plane words, one MFMA per (group, plane), scale, accumulate
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            // after the transpose, register t of quarter q is dword q of group 2t + j of the slice
+            // after the transpose, register t of quarter q is dword q of group 4j + t of the slice
             uint32_t wt[PH][4];
 #pragma unroll
             for (int i = 0; i < PH; ++i) {
@@ -218,7 +261,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const int gl = 2 * t + j;                           // group inside the slice
+                const int gl = 4 * j + t;                           // group inside the slice
                 const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes);
                 const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes + L::kGroupBytes / 2);
                 const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
@@ -264,12 +307,12 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     uint32_t row = (blockIdx.x * pr.RB + rb) * 16 + r16;
     const bool row_ok = row < pr.m;
     if (!row_ok) row = pr.m - 1;              // keep loads in bounds; the result is discarded
-    const uint32_t voff_w = row * pr.row_stride + q * 32;
+    const uint32_t voff_w = row * pr.row_stride + q * 16;
     const uint32_t voff_s = row * pr.scale_row_stride;
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, P, pr.scales[P]);
+        acc = sweep<P, NB, false>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, P, pr.scales[P]);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs
         int p_mine = 0, p_hi = 0;
@@ -283,17 +326,16 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
         const unsigned char *sbase = pr.scales[p_mine > 0 ? p_mine : p_hi];
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 2: acc = sweep<2, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 3: acc = sweep<3, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 4: acc = sweep<4, NB>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 1: acc = sweep<1, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 2: acc = sweep<2, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 3: acc = sweep<3, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 4: acc = sweep<4, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }
 
     // ---- combine the KS partial sums of each row block in a fixed order, store binary16 -----
-    __syncthreads();
-    float *red = reinterpret_cast<float *>(lds);
+    float *red = reinterpret_cast<float *>(lds + Lds<NB>::red_off(KS, pr.RB));
     red[wave * 64 + lane] = acc;
     __syncthreads();
     if (ks == 0) {
@@ -305,9 +347,9 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
 
 constexpr size_t kLdsBudget = 128 * 1024;     // of the 160 KiB per CU
 
-int lds_total(int NB, int KS)
+int lds_total(int NB, int KS, int RB)
 {
-    return NB == 1 ? Lds<1>::total(KS) : NB == 2 ? Lds<2>::total(KS) : Lds<4>::total(KS);
+    return NB == 1 ? Lds<1>::total(KS, RB) : NB == 2 ? Lds<2>::total(KS, RB) : Lds<4>::total(KS, RB);
 }
 
 struct Plan {
@@ -321,20 +363,20 @@ Plan make_plan(const GemmArgs &a)
     Plan pl;
     pl.NB = a.batch == 1 ? 1 : a.batch == 2 ? 2 : 4;
     int ks_cap = 16;
-    while (ks_cap > 1 && (size_t)lds_total(pl.NB, ks_cap) > kLdsBudget) --ks_cap;
+    while (ks_cap > 1 && (size_t)lds_total(pl.NB, ks_cap, 1) > kLdsBudget) --ks_cap;
     int KS = 1;
     for (int d = 1; d <= ks_cap && d <= nslices; ++d)
         if (nslices % d == 0) KS = d;
     if (KS < ks_cap / 2 && nslices > ks_cap) KS = ks_cap;   // awkward factorisation: ragged last chunk instead
     pl.KS = KS;
     pl.nchunk = (nslices + KS - 1) / KS;
+    // Small workgroups (one row block) start and finish at different times, which keeps loads of
+    // some overlapping the arithmetic of others; several row blocks share an image only when there
+    // are far more row blocks than the CUs can hold at once.
     pl.RB = 1;
-    while (pl.RB * 2 * KS <= 16) pl.RB *= 2;                 // up to 16 waves share one operand image
     const int64_t row_blocks = (a.m + 15) / 16;
-    while (pl.RB > 1 && (row_blocks + pl.RB - 1) / pl.RB < 256) pl.RB /= 2;   // but keep one workgroup per CU
-    size_t image = (size_t)lds_total(pl.NB, KS);
-    size_t red = (size_t)KS * pl.RB * 64 * sizeof(float);
-    pl.lds_bytes = image > red ? image : red;
+    while (pl.RB * 2 * KS <= 8 && row_blocks / (pl.RB * 2) >= 2048) pl.RB *= 2;
+    pl.lds_bytes = (size_t)lds_total(pl.NB, KS, pl.RB);
     return pl;
 }
 
@@ -396,6 +438,8 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.RB = pl.RB;
     pr.nchunk = pl.nchunk;
     pr.nslices = (int)(a.n / kSliceCols);
+    pr.inv_quarter = 1.0f / (float)(16 * pl.KS * pl.RB);
+    pr.inv_ks = 1.0f / (float)pl.KS;
     const int64_t row_blocks = (a.m + 15) / 16;
     dim3 grid((unsigned)((row_blocks + pl.RB - 1) / pl.RB), (unsigned)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile));
     dim3 block(64 * pl.KS * pl.RB);

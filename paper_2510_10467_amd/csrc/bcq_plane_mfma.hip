@@ -61,13 +61,13 @@ struct PlaneMfmaParams {
     uint32_t m;
     int batch, p_max, uniform_p;
     int KS, RB, nchunk, nslices;
-    float inv_quarter, inv_ks;              // 1 / (threads / 4) and 1 / KS, for small exact integer divisions
+    uint32_t ntiles, nwg_rows;              // batch tiles of four requests; row-block groups (workgroups per tile)
+    float inv_span;                         // 1 / (8 * ntiles)
 };
 
 // LDS layout of one chunk for NB requests per tile and KS slices:
 //   [0, image)        operand image: 16-byte rows at ((g*2 + h)*4 + qa)*4NB + row
-//   [image, scales)   staged binary16 activations of the chunk, request-major
-//   [scales, red)     staged scales of the chunk, 16 bytes per thread (uniform precision)
+//   [image, red)      staged binary16 activations of the chunk, request-major
 //   [red, total)      one fp32 partial sum per thread for the final combine
 template <int NB>
 struct Lds {
@@ -76,10 +76,8 @@ struct Lds {
     static constexpr int kSliceImage = kSliceGroups * kGroupBytes;   // 4 KiB * NB
     static constexpr int kSliceStage = kSliceCols * 2;               // per request
     __host__ __device__ static constexpr int stage_off(int KS) { return KS * kSliceImage; }
-    // staged scales of the chunk (uniform precision only): one 16-byte unit per thread
-    __host__ __device__ static constexpr int scale_off(int KS) { return KS * (kSliceImage + NB * kSliceStage); }
     // per-wave partial sums for the final combine
-    __host__ __device__ static constexpr int red_off(int KS, int RB) { return scale_off(KS) + 64 * KS * RB * 16; }
+    __host__ __device__ static constexpr int red_off(int KS, int RB) { return KS * (kSliceImage + NB * kSliceStage); }
     __host__ __device__ static constexpr int total(int KS, int RB) { return red_off(KS, RB) + 64 * KS * RB * 4; }
 };
 
@@ -112,17 +110,15 @@ __device__ __forceinline__ v8i expand_plane_word(uint32_t w, uint32_t sign, uint
 //   voff_w   this lane's byte offset into a plane: row * row_stride + q * 16
 //   voff_s   this lane's byte offset into a scale plane: row * scale_row_stride
 //   p_mine   precision of the request this lane reports on (0: none); sbase its scale set
-// MIXED: every lane loads its own request's scales from global memory.  Otherwise the
-// workgroup stages the (shared) scale set of the chunk in LDS, one 16-byte unit per thread.
+// MIXED: lanes of different quarters may belong to requests of different precisions.
 template <int PH, int NB, bool MIXED>
-__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int q, int r16,
-                                       int tid, int nthreads, int b0, int nb, uint32_t voff_w, uint32_t voff_s,
-                                       int p_mine, const unsigned char *sbase)
+__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks,
+                                       int q, int r16, int tid, int nthreads, int b0, int nb, uint32_t voff_w,
+                                       uint32_t voff_s, int p_mine, const unsigned char *sbase)
 {
     using L = Lds<NB>;
     const int KS = pr.KS;
     const int stage_off = L::stage_off(KS);
-    const int scale_off = L::scale_off(KS);
     const int units = KS * (kSliceCols / 8);                        // 16-byte activation units per request and chunk
 
     // constants kept in registers so that (w & sign) | one is a single three-operand instruction
@@ -141,15 +137,6 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
     const int task_src = stage_off + ((tid >> 5) * 128 + cl0) * 2;
     const int task_dst = (tid >> 5) * L::kGroupBytes + ((h * 4 + qa) * L::kRows) * 16 + 4 * dw;
     const int task_groups = nthreads >> 5;                          // groups covered per trip
-
-    // scale staging (uniform precision): thread tid fetches unit (plane sp, row srow, slice ssl) of the chunk
-    const int quarter = nthreads >> 2;                              // units per plane: 16 rows * RB * KS
-    const int sp = (int)(((float)tid + 0.5f) * pr.inv_quarter);
-    const int su = tid - sp * quarter;
-    const int srow_local = (int)(((float)su + 0.5f) * pr.inv_ks);   // row inside the workgroup's RB*16 rows
-    const int ssl = su - srow_local * KS;
-    const uint32_t srow = min((uint32_t)(blockIdx.x * pr.RB * 16 + srow_local), pr.m - 1);
-    const int my_scale_unit = ((rb * 16 + r16) * KS + ks) * 16;     // + plane * quarter * 16
 
     float acc = 0.f;
     for (int chunk = 0; chunk < pr.nchunk; ++chunk) {
@@ -177,19 +164,12 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 xv[b][k2] = *reinterpret_cast<const u32x4 *>(pr.x + (size_t)(b0 + (b < nb ? b : 0)) * x_bytes + off);
                 if (!ok) xv[b][k2] = u32x4{0, 0, 0, 0};             // ragged last chunk: columns past n are zero
             }
-        u32x4 sc[PH], sstage;
-        if constexpr (MIXED) {
+        u32x4 sc[PH];
 #pragma unroll
-            for (int i = 0; i < PH; ++i) {
-                const int ii = min(i, max(p_mine, 1) - 1);          // stay inside the lane's own scale set
-                sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + voff_s +
-                                                         (uint32_t)slice_c * (kSliceGroups * 2));
-            }
-        } else {
-            const int sslice = min(chunk * KS + ssl, pr.nslices - 1);
-            const int spc = sp < PH ? sp : PH - 1;
-            sstage = *reinterpret_cast<const u32x4 *>(sbase + (size_t)spc * pr.scale_plane_stride +
-                                                      srow * pr.scale_row_stride + (uint32_t)sslice * (kSliceGroups * 2));
+        for (int i = 0; i < PH; ++i) {
+            const int ii = MIXED ? min(i, max(p_mine, 1) - 1) : i;  // stay inside the lane's own scale set
+            sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + voff_s +
+                                                     (uint32_t)slice_c * (kSliceGroups * 2));
         }
         u32x4 wlo[PH], whi[PH];
 #pragma unroll
@@ -211,7 +191,6 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 const int u = k2 * nthreads + tid;
                 if (u < units) *reinterpret_cast<u32x4 *>(lds + stage_off + b * KS * L::kSliceStage + u * 16) = xv[b][k2];
             }
-        if constexpr (!MIXED) *reinterpret_cast<u32x4 *>(lds + scale_off + tid * 16) = sstage;
         __syncthreads();
         // one task = four columns (stride 4) of one request -> one dword in each of the four term rows
         for (int g = tid >> 5, src = task_src, dst = task_dst; g < KS * kSliceGroups;
@@ -235,11 +214,6 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                     d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);   // bytes: col0, col0+4, col0+8, col0+12
                 }
             }
-        }
-        if constexpr (!MIXED) {
-#pragma unroll
-            for (int i = 0; i < PH; ++i)
-                sc[i] = *reinterpret_cast<const u32x4 *>(lds + scale_off + i * quarter * 16 + my_scale_unit);
         }
         __syncthreads();
 
@@ -301,10 +275,23 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     const int rb = wave / KS;                 // row block of this wave inside the workgroup
     const int q = lane >> 4;                  // lane quarter: K sub-block on the weight side, request on the output side
     const int r16 = lane & 15;
-    const int b0 = blockIdx.y * kMaxBatchTile;
+    // Workgroup id -> (row-block group, batch tile).  Ids that differ by 8 run on the same XCD (ids
+    // are dealt round-robin to the 8 XCDs), so the tiles of one row-block group are placed 8 apart:
+    // they start close in time on one XCD and all but the first find the planes in that XCD's L2.
+    const uint32_t ntiles = pr.ntiles;
+    uint32_t tile = 0, wg = blockIdx.x;                             // one tile: the mapping is the identity
+    if (ntiles > 1) {
+        const uint32_t span_index = (uint32_t)(((float)blockIdx.x + 0.5f) * pr.inv_span);   // id / (8 * ntiles), ids < 2^21
+        const uint32_t rem = blockIdx.x - span_index * 8 * ntiles;
+        tile = rem >> 3;
+        wg = span_index * 8 + (rem & 7);                            // row-block group of this workgroup
+    }
+    if (wg >= pr.nwg_rows) return;                                  // padding of the last span (whole workgroup)
+    const int b0 = tile * kMaxBatchTile;
     const int nb = min(NB, pr.batch - b0);
+    const uint32_t wg_rows0 = wg * pr.RB * 16;
 
-    uint32_t row = (blockIdx.x * pr.RB + rb) * 16 + r16;
+    uint32_t row = wg_rows0 + rb * 16 + r16;
     const bool row_ok = row < pr.m;
     if (!row_ok) row = pr.m - 1;              // keep loads in bounds; the result is discarded
     const uint32_t voff_w = row * pr.row_stride + q * 16;
@@ -312,7 +299,7 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB, false>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, P, pr.scales[P]);
+        acc = sweep<P, NB, false>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, P, pr.scales[P]);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs
         int p_mine = 0, p_hi = 0;
@@ -326,10 +313,10 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
         const unsigned char *sbase = pr.scales[p_mine > 0 ? p_mine : p_hi];
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 2: acc = sweep<2, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 3: acc = sweep<3, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 4: acc = sweep<4, NB, true>(pr, lds, ks, rb, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 1: acc = sweep<1, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 2: acc = sweep<2, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 3: acc = sweep<3, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 4: acc = sweep<4, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }
@@ -413,7 +400,7 @@ bool plane_mfma_supports(const GemmArgs &a)
     const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31) &&
                               a.m < (int64_t(1) << 27);
     return a.group == 128 && (a.n % kSliceCols) == 0 && a.p_max <= kMaxP && small_enough &&
-           (a.batch + kMaxBatchTile - 1) / kMaxBatchTile <= 65535;
+           ((a.m + 15) / 16 + 8) * ((a.batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);
 }
 
 hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
@@ -438,10 +425,12 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.RB = pl.RB;
     pr.nchunk = pl.nchunk;
     pr.nslices = (int)(a.n / kSliceCols);
-    pr.inv_quarter = 1.0f / (float)(16 * pl.KS * pl.RB);
-    pr.inv_ks = 1.0f / (float)pl.KS;
     const int64_t row_blocks = (a.m + 15) / 16;
-    dim3 grid((unsigned)((row_blocks + pl.RB - 1) / pl.RB), (unsigned)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile));
+    pr.ntiles = (uint32_t)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile);
+    pr.nwg_rows = (uint32_t)((row_blocks + pl.RB - 1) / pl.RB);
+    // ids are grouped in spans of 8 row-block groups x ntiles; the last span may be partly empty
+    dim3 grid((pr.nwg_rows + 7) / 8 * 8 * pr.ntiles);
+    pr.inv_span = 1.0f / (float)(8 * pr.ntiles);
     dim3 block(64 * pl.KS * pl.RB);
     switch (pl.NB) {
     case 1: return launch_nb<1>(a, pr, pl, grid, block, stream);

@@ -89,3 +89,44 @@ def test_plane_mfma_mixed(gpu, m, n):
         x = syn.make_x(batch, n, seed=(140, batch))
         p_req = syn.make_p_req(batch, 1, 4, seed=(140, batch))
         gpu.check_mixed(dl, p_req, x, "plane_mfma")
+
+
+@pytest.mark.parametrize("m,n", [(37, 2048), (131, 4096), (70, 1536), (64, 640), (200, 8192)])
+def test_dequant_mfma_uniform(gpu, m, n):
+    layer = syn.make_layer(m, n, seed=(150, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 17, 64, 100, 256):
+        x = syn.make_x(batch, n, seed=(150, batch))
+        for p in (1, 2, 3, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma")
+            assert used == "dequant_mfma"
+
+
+def test_forced_variant_that_cannot_run_is_an_error(gpu):
+    import paper_2510_10467_amd as bcq
+    layer = syn.make_layer(16, 640, seed=(160, 0))            # n is not a multiple of 1024
+    dl = gpu.DeviceLayer(layer)
+    x = gpu.to_dev(syn.make_x(1, 640, seed=(160, 0)))
+    bcq.select_kernel("plane_mfma")
+    try:
+        with pytest.raises(bcq.BcqError) as e:
+            bcq.bcq_gemv(dl.planes, dl.scales[2], 2, x)
+        assert e.value.status == -6
+    finally:
+        bcq.select_kernel("auto")
+    # the default choice falls back to a kernel that can
+    gpu.check_gemv(dl, 2, syn.make_x(1, 640, seed=(160, 0)), "auto")
+
+
+def test_auto_dispatch_by_batch(gpu):
+    layer = syn.make_layer(96, 2048, seed=(170, 0))
+    dl = gpu.DeviceLayer(layer)
+    used, _ = gpu.check_gemv(dl, 3, syn.make_x(1, 2048, seed=(170, 1)), "auto")
+    assert used == "plane_mfma"
+    used, _ = gpu.check_gemv(dl, 3, syn.make_x(16, 2048, seed=(170, 2)), "auto")
+    assert used == "plane_mfma"
+    used, _ = gpu.check_gemv(dl, 3, syn.make_x(128, 2048, seed=(170, 3)), "auto")
+    assert used == "dequant_mfma"
+    p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
+    used, _ = gpu.check_mixed(dl, p_req, syn.make_x(40, 2048, seed=(170, 4)), "auto")
+    assert used == "plane_mfma"

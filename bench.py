@@ -48,7 +48,93 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying HIP graphs")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
+    ap.add_argument("--suite", choices=["decode", "mixed", "large"], default=None,
+                    help="instead of the headline workload, time another workload family and print its table")
     return ap.parse_args()
+
+
+def run_suite(args, torch, bcq, syn, dev):
+    """Other workload families: decode batches, per-request precision, Llama-3-70B shapes with large batches.
+
+    Every entry is the mean time of back-to-back launches (one HIP graph) rotating over enough
+    distinct weight copies to exceed the last-level cache; GB/s uses the algorithmic bytes."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(syn.BASE_SEED)
+
+    def device_layer(m, n):
+        # same distributions as synthetic_inputs, drawn on the GPU to keep set-up short for the big shapes
+        planes = torch.randint(-2 ** 31, 2 ** 31 - 1, (syn.P_MAX, m, n // 32), dtype=torch.int32, device=dev, generator=gen)
+        scales = {}
+        for p in (2, 3, 4):
+            a1 = (torch.randn((m, n // syn.GROUP), device=dev, generator=gen) * 0.02).abs()
+            rows = [a1]
+            for _ in range(1, p):
+                rows.append(rows[-1] * (0.4 + 0.2 * torch.rand((m, n // syn.GROUP), device=dev, generator=gen)))
+            scales[p] = torch.stack(rows).half().contiguous()
+        return planes, scales
+
+    def timed_graph(fn, reps=10, warm=3):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        for _ in range(warm):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rows = []
+    launches = 16
+
+    def bench_shape(m, n, batches, precisions, mixed=False):
+        copies = max(2, -(-MIN_ROTATION_BYTES // (m * n // 2)))
+        copies = min(copies, 24)
+        sets = [device_layer(m, n) for _ in range(copies)]
+        for batch in batches:
+            x = torch.randn((batch, n), device=dev, generator=gen).half()
+            y = torch.empty((batch, m), dtype=torch.float16, device=dev)
+            for p in precisions:
+                def burst():
+                    for i in range(launches):
+                        pl, sc = sets[i % copies]
+                        bcq.bcq_gemv(pl, sc[p], p, x, y)
+                us = timed_graph(burst) * 1e3 / launches
+                by = syn.algorithmic_bytes(m, n, p, batch)
+                rows.append({"m": m, "n": n, "batch": batch, "p": p, "kernel": bcq.last_kernel(), "us": round(us, 2),
+                             "GBps": round(by / us / 1e3, 1), "pct_of_hbm_peak": round(100 * by / us / 1e3 / HBM_PEAK_GBS, 2),
+                             "TFLOPs": round(2.0 * m * n * batch / us / 1e6, 1)})
+            if mixed:
+                p_req_h = syn.make_p_req(batch, 2, 4, seed=(4, batch))
+                p_req = torch.from_numpy(p_req_h).to(dev)
+
+                def burst_mixed():
+                    for i in range(launches):
+                        pl, sc = sets[i % copies]
+                        bcq.bcq_gemm_mixed(pl, sc, p_req, x, y)
+                us = timed_graph(burst_mixed) * 1e3 / launches
+                pmax = int(p_req_h.max())
+                by = m * n * pmax // 8 + sum(m * (n // syn.GROUP) * q * 2 for q in sorted(set(p_req_h.tolist()))) + batch * (n + m) * 2
+                rows.append({"m": m, "n": n, "batch": batch, "p": "mixed:" + ",".join(str(v) for v in p_req_h.tolist()),
+                             "kernel": bcq.last_kernel(), "us": round(us, 2), "GBps": round(by / us / 1e3, 1),
+                             "pct_of_hbm_peak": round(100 * by / us / 1e3 / HBM_PEAK_GBS, 2)})
+        del sets
+
+    if args.suite == "decode":
+        for (m, n) in ((14336, 4096), (4096, 14336)):
+            bench_shape(m, n, (1, 2, 4, 8, 16, 32), PRECISIONS)
+    elif args.suite == "mixed":
+        bench_shape(14336, 4096, (16,), PRECISIONS, mixed=True)
+    else:
+        for (_, m, n) in syn.LLAMA3_70B_SHAPES:
+            bench_shape(m, n, (1, 16, 64, 256), PRECISIONS)
+    return {"suite": args.suite, "unit": "us per call", "data": "synthetic", "rows": rows}
 
 
 def main():
@@ -66,6 +152,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     bcq.lib()                                        # fail loudly if the HIP library is missing
+
+    if args.suite:
+        print(json.dumps(run_suite(args, torch, bcq, syn, dev)))
+        return
 
     layers = syn.LLAMA3_8B_LAYERS
     set_bytes = sum(m * n * syn.P_MAX // 8 + sum(m * (n // syn.GROUP) * p * 2 for p in PRECISIONS) for _, m, n in layers)

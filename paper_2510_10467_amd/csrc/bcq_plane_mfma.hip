@@ -357,12 +357,13 @@ Plan make_plan(const GemmArgs &a)
     if (KS < ks_cap / 2 && nslices > ks_cap) KS = ks_cap;   // awkward factorisation: ragged last chunk instead
     pl.KS = KS;
     pl.nchunk = (nslices + KS - 1) / KS;
-    // Small workgroups (one row block) start and finish at different times, which keeps loads of
-    // some overlapping the arithmetic of others; several row blocks share an image only when there
-    // are far more row blocks than the CUs can hold at once.
+    // One request per tile: small workgroups (one row block) start and finish at different times,
+    // which keeps loads of some overlapping the arithmetic of others.  Several requests per tile:
+    // the operand image grows with the request count, so as many row blocks share it as requests
+    // (up to 16 waves), which keeps LDS per wave constant and the CUs fully occupied.
     pl.RB = 1;
     const int64_t row_blocks = (a.m + 15) / 16;
-    while (pl.RB * 2 * KS <= 8 && row_blocks / (pl.RB * 2) >= 2048) pl.RB *= 2;
+    while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= 16 && row_blocks / (pl.RB * 2) >= 128) pl.RB *= 2;
     pl.lds_bytes = (size_t)lds_total(pl.NB, KS, pl.RB);
     return pl;
 }

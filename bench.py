@@ -48,9 +48,28 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying HIP graphs")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (a reference kernel of known traffic for counter runs)")
     ap.add_argument("--suite", choices=["decode", "mixed", "large"], default=None,
                     help="instead of the headline workload, time another workload family and print its table")
     return ap.parse_args()
+
+
+def profiled_traffic_bytes(p, m, n):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary (FETCH_SIZE +
+    WRITE_SIZE, scaled by a plain copy), or None when the summary does not cover this kernel."""
+    path = os.path.join(ROOT, "profiles", "plane_mfma_llama3_8b_batch1.txt")
+    want = (f"plane_mfma_kernel<{p},1,false>", f"{m}x{n}")
+    try:
+        seen_counters = False
+        for line in open(path):
+            seen_counters = seen_counters or line.startswith("HBM traffic counters")
+            parts = line.split()
+            if seen_counters and len(parts) >= 8 and parts[0] == want[0] and parts[1] == want[1]:
+                return int(float(parts[-3]) * 1e6)          # column "scaled MB"
+    except OSError:
+        pass
+    return None
 
 
 def run_suite(args, torch, bcq, syn, dev):
@@ -254,7 +273,7 @@ def main():
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": f"plane_mfma_kernel<{dom_p}> m={dm} n={dn} batch=1",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": profiled_traffic_bytes(dom_p, dm, dn),
                 "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3)}
 
     details = None
@@ -284,6 +303,14 @@ def main():
         details["fp16_gemv"] = {"m": dm, "n": dn, "us": round(us16, 3), "GBps": round(2 * dm * dn / (us16 * 1e-6) / 1e9, 1)}
         del ws
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- CPU baseline: the oracle as it stands, on one copy of the same layer set -------------
     cpu_baseline = None
     if not args.skip_cpu_baseline:
@@ -301,9 +328,10 @@ def main():
         "metric": "bcq_gemv effective HBM GB/s, Llama-3-8B linear set, batch 1, p=2/3/4",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp4 signs x e5m2 activation terms, fp32 accumulate (fp16 in/out)", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": "Llama-3-8B-shaped linear set (q,k,v,o,gate,up,down), batch 1, group 128, p in {2,3,4}; "
                                "one step = 21 bcq_gemv calls", "kernel": kernel_name,
+                   "arithmetic": "fp16 in/out; exact E5M2 activation terms x FP4 weight signs on the MFMA pipe, fp32 accumulate",
                    "weight_copies_rotated": copies, "rotation_bytes": copies * set_bytes,
                    "launch": "python loop" if args.no_graph else "hip graph replay per step"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),

@@ -63,16 +63,19 @@ struct PlaneMfmaParams {
     int KS, RB, nchunk, nslices;
     uint32_t ntiles, nwg_rows;              // batch tiles of four requests; row-block groups (workgroups per tile)
     float inv_span;                         // 1 / (8 * ntiles)
+    float inv_ks;                           // 1 / KS
 };
 
 // LDS layout of one chunk for NB requests per tile and KS slices:
-//   [0, image)        operand image: 16-byte rows at ((g*2 + h)*4 + qa)*4NB + row
+//   [0, image)        operand image: 16-byte rows; group g, register half h, lane quarter qa, operand row r at
+//                     g*kGroupBytes + h*kHalfBytes + (qa*4NB + r)*16
 //   [image, red)      staged binary16 activations of the chunk, request-major
 //   [red, total)      one fp32 partial sum per thread for the final combine
 template <int NB>
 struct Lds {
     static constexpr int kRows = 4 * NB;
-    static constexpr int kGroupBytes = 2 * 4 * kRows * 16;          // one group's image: 512 * NB
+    static constexpr int kHalfBytes = 4 * kRows * 16 + 16;          // operand registers 0-3 (or 4-7) of all lanes, padded
+    static constexpr int kGroupBytes = 2 * kHalfBytes;              // one group's image; the padding spreads LDS banks
     static constexpr int kSliceImage = kSliceGroups * kGroupBytes;   // 4 KiB * NB
     static constexpr int kSliceStage = kSliceCols * 2;               // per request
     __host__ __device__ static constexpr int stage_off(int KS) { return KS * kSliceImage; }
@@ -130,14 +133,6 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
     const int arow = r16 < L::kRows ? r16 : L::kRows - 1;
     const int img_lane = ks * L::kSliceImage + (q * L::kRows + arow) * 16;
 
-    // stage-2 task constants: task = 32 * group + (h, qa, dw); a thread keeps (h, qa, dw) and strides over groups
-    const int dw = tid & 3, qa = (tid >> 2) & 3, h = (tid >> 4) & 1, z = dw >> 1;
-    // operand byte 8z + tt of lane quarter qa pairs with column 64h + 32(qa>>1) + 4tt + 3 - (2(qa&1) + z)
-    const int cl0 = 64 * h + 32 * (qa >> 1) + 16 * (dw & 1) + 3 - (2 * (qa & 1) + z);
-    const int task_src = stage_off + ((tid >> 5) * 128 + cl0) * 2;
-    const int task_dst = (tid >> 5) * L::kGroupBytes + ((h * 4 + qa) * L::kRows) * 16 + 4 * dw;
-    const int task_groups = nthreads >> 5;                          // groups covered per trip
-
     float acc = 0.f;
     for (int chunk = 0; chunk < pr.nchunk; ++chunk) {
         const int slice = chunk * KS + ks;                          // global K slice of this wave
@@ -147,11 +142,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         const uint32_t chunk_byte0 = (uint32_t)chunk * KS * kSliceCols * 2;   // first activation byte of the chunk
         const uint32_t x_bytes = pr.x_stride;                                 // bytes per request = columns * 2
 
-        // ---- 1. loads in the order of use: activations, scales, then the two halves of every plane.
-        // The wave raises its issue priority for the burst so that its loads enter the memory queues
-        // together instead of interleaved with those of younger waves: waves then receive their data
-        // one after the other and the arithmetic of the early ones overlaps the loads of the late ones.
-        __builtin_amdgcn_s_setprio(3);
+        // ---- 1. loads in the order of use: activations, scales, then the two halves of every plane
         u32x4 xv[NB][2];
 #pragma unroll
         for (int b = 0; b < NB; ++b)
@@ -176,11 +167,11 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         for (int i = 0; i < PH; ++i)                                // groups q of the slice; 64 contiguous bytes per row
             wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
                 pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w));
+        __builtin_amdgcn_sched_barrier(0);                          // keep the issue order: first halves of all planes first
 #pragma unroll
         for (int i = 0; i < PH; ++i)                                // groups 4 + q
             whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
                 pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w + 64));
-        __builtin_amdgcn_s_setprio(0);
 
         // ---- 2. workgroup builds the operand image of this chunk --------------------------
         if (chunk > 0) __syncthreads();                             // previous image and staging no longer read
@@ -192,35 +183,48 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 if (u < units) *reinterpret_cast<u32x4 *>(lds + stage_off + b * KS * L::kSliceStage + u * 16) = xv[b][k2];
             }
         __syncthreads();
-        // one task = four columns (stride 4) of one request -> one dword in each of the four term rows
-        for (int g = tid >> 5, src = task_src, dst = task_dst; g < KS * kSliceGroups;
-             g += task_groups, src += task_groups * 256, dst += task_groups * L::kGroupBytes) {
+        // One unit = 16 consecutive columns of one request (32 bytes of the staging area).  Column
+        // 16u + low + 4i (i = 0..3) belongs to operand byte 8z + 4(u&1) + i of lane quarter 2*((u>>1)&1) + w
+        // with 2w + z = 3 - low, so a unit yields one dword for each (low, term): 16 dword stores.
+        for (int unit = tid; unit < KS * kSliceGroups * 8; unit += nthreads) {
+            const int g = unit >> 3, u16 = unit & 7;
+            const int dst0 = g * L::kGroupBytes + (u16 >> 2) * L::kHalfBytes + (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const unsigned short *s16 = reinterpret_cast<const unsigned short *>(lds + src + b * KS * L::kSliceStage);
-                const uint32_t v01 = (uint32_t)s16[0] | ((uint32_t)s16[4] << 16);
-                const uint32_t v23 = (uint32_t)s16[8] | ((uint32_t)s16[12] << 16);
-                // exact split into four E5M2 terms: top bytes of the running binary16 remainders
-                h2 r01 = __builtin_bit_cast(h2, v01), r23 = __builtin_bit_cast(h2, v23);
-                uint32_t *d32 = reinterpret_cast<uint32_t *>(lds + dst + b * 64);
+                const u32x4 *sp = reinterpret_cast<const u32x4 *>(lds + stage_off + b * KS * L::kSliceStage + unit * 32);
+                const u32x4 c0 = sp[0], c1 = sp[1];
+                const uint32_t dwd[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};   // dword k = columns 2k, 2k+1
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
-                    const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
-                    if (j < 3) {
-                        r01 = r01 - __builtin_bit_cast(h2, t01);
-                        r23 = r23 - __builtin_bit_cast(h2, t23);
+                for (int low = 0; low < 4; ++low) {
+                    const uint32_t sel = (low & 1) ? 0x07060302u : 0x05040100u;               // upper or lower halves
+                    const int k0 = low >> 1;
+                    // packed pairs (col low, col low+4) and (col low+8, col low+12)
+                    h2 r01 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 2], dwd[k0], sel));
+                    h2 r23 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 6], dwd[k0 + 4], sel));
+                    const int inv = 3 - low, w = inv >> 1, z = inv & 1;
+                    uint32_t *d32 = reinterpret_cast<uint32_t *>(lds + dst0 + w * (L::kRows * 16) + 8 * z + b * 64);
+                    // exact split into four E5M2 terms: top bytes of the running binary16 remainders
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
+                        const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
+                        if (j < 3) {
+                            r01 = r01 - __builtin_bit_cast(h2, t01);
+                            r23 = r23 - __builtin_bit_cast(h2, t23);
+                        }
+                        d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);          // bytes: i = 0, 1, 2, 3
                     }
-                    d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);   // bytes: col0, col0+4, col0+8, col0+12
                 }
             }
         }
         __syncthreads();
 
         // scales of planes this lane must not use (beyond its precision, or a slice past the end) become zero
+        if (MIXED || !slice_ok) {
 #pragma unroll
-        for (int i = 0; i < PH; ++i)
-            if (!(i < p_eff)) sc[i] = u32x4{0, 0, 0, 0};
+            for (int i = 0; i < PH; ++i)
+                if (!(i < p_eff)) sc[i] = u32x4{0, 0, 0, 0};
+        }
 
         // ---- 3. per group: expand plane words, one MFMA per (group, plane), scale, accumulate
 #pragma unroll
@@ -237,7 +241,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
             for (int t = 0; t < 4; ++t) {
                 const int gl = 4 * j + t;                           // group inside the slice
                 const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes);
-                const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes + L::kGroupBytes / 2);
+                const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes + L::kHalfBytes);
                 const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
                 v4f d[PH];
 #pragma unroll
@@ -251,9 +255,9 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 for (int i = 0; i < PH; ++i) {
                     const uint32_t sw = sc[i][gl >> 1];
                     const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
-                    const float s = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
+                    const float sum = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
                     // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
-                    acc = fmaf(-alpha, s, acc);
+                    acc = fmaf(-alpha, sum, acc);
                 }
             }
         }
@@ -271,8 +275,11 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int KS = pr.KS;
-    const int ks = wave % KS;                 // K slice of this wave inside a chunk
-    const int rb = wave / KS;                 // row block of this wave inside the workgroup
+    int ks = wave, rb = 0;                    // K slice of this wave inside a chunk, row block inside the workgroup
+    if (pr.RB > 1) {
+        rb = (int)(((float)wave + 0.5f) * pr.inv_ks);               // wave / KS for wave < 16
+        ks = wave - rb * KS;
+    }
     const int q = lane >> 4;                  // lane quarter: K sub-block on the weight side, request on the output side
     const int r16 = lane & 15;
     // Workgroup id -> (row-block group, batch tile).  Ids that differ by 8 run on the same XCD (ids
@@ -294,8 +301,9 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     uint32_t row = wg_rows0 + rb * 16 + r16;
     const bool row_ok = row < pr.m;
     if (!row_ok) row = pr.m - 1;              // keep loads in bounds; the result is discarded
-    const uint32_t voff_w = row * pr.row_stride + q * 16;
-    const uint32_t voff_s = row * pr.scale_row_stride;
+    // rows and row strides are below 2^24 (checked on the host): full-rate 24-bit multiplies
+    const uint32_t voff_w = __umul24(row, pr.row_stride) + q * 16;
+    const uint32_t voff_s = __umul24(row, pr.scale_row_stride);
 
     float acc = 0.f;
     if constexpr (!MIXED) {
@@ -399,7 +407,7 @@ bool plane_mfma_supports(const GemmArgs &a)
 {
     // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
     const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31) &&
-                              a.m < (int64_t(1) << 27);
+                              a.m < (int64_t(1) << 24) && a.n < (int64_t(1) << 24);
     return a.group == 128 && (a.n % kSliceCols) == 0 && a.p_max <= kMaxP && small_enough &&
            ((a.m + 15) / 16 + 8) * ((a.batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);
 }
@@ -432,6 +440,7 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     // ids are grouped in spans of 8 row-block groups x ntiles; the last span may be partly empty
     dim3 grid((pr.nwg_rows + 7) / 8 * 8 * pr.ntiles);
     pr.inv_span = 1.0f / (float)(8 * pr.ntiles);
+    pr.inv_ks = 1.0f / (float)pl.KS;
     dim3 block(64 * pl.KS * pl.RB);
     switch (pl.NB) {
     case 1: return launch_nb<1>(a, pr, pl, grid, block, stream);

@@ -164,14 +164,13 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         }
         u32x4 wlo[PH], whi[PH];
 #pragma unroll
-        for (int i = 0; i < PH; ++i)                                // groups q of the slice; 64 contiguous bytes per row
-            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
-                pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w));
-        __builtin_amdgcn_sched_barrier(0);                          // keep the issue order: first halves of all planes first
-#pragma unroll
-        for (int i = 0; i < PH; ++i)                                // groups 4 + q
-            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
-                pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w + 64));
+        for (int i = 0; i < PH; ++i) {
+            // both halves of a 128-byte line are requested back to back: 64 contiguous bytes per row and
+            // instruction (groups q, then groups 4 + q of the slice)
+            const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w;
+            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp));
+            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + 64));
+        }
 
         // ---- 2. workgroup builds the operand image of this chunk --------------------------
         if (chunk > 0) __syncthreads();                             // previous image and staging no longer read

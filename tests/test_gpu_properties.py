@@ -1,0 +1,209 @@
+"""GPU checks that hold at any size: full-size layers in the launch configuration the benchmark
+times (sampled rows against the oracle), invariants of the method, edge cases of the ABI."""
+import numpy as np
+import pytest
+
+import synthetic_inputs as syn
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from tests import gpu_util
+    return gpu_util
+
+
+def sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y_gpu, what):
+    """Oracle on a subset of rows (the product is independent per output row)."""
+    sub_planes = np.ascontiguousarray(layer.planes[:, rows, :])
+    sub_scales = np.ascontiguousarray(layer.scales[p][:, rows, :])
+    y_ref, a_ref = oracle.gemv(sub_planes, sub_scales, x)
+    y = y_gpu.cpu().numpy().astype(np.float64)[:, rows]
+    err = np.abs(y - y_ref)
+    tol = oracle.tolerance(y_ref, a_ref)
+    assert np.all(err <= tol), f"{what}: max err/tol {np.max(err / tol):.3f}"
+
+
+@pytest.mark.parametrize("name,m,n", [("gate_proj", 14336, 4096), ("down_proj", 4096, 14336), ("q_proj", 4096, 4096),
+                                       ("k_proj", 1024, 4096), ("llama70b_up", 28672, 8192), ("llama70b_down", 8192, 28672)])
+def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    layer = syn.make_layer(m, n, seed=(200, m, n))
+    dl = gpu.DeviceLayer(layer)
+    rng = np.random.default_rng([syn.BASE_SEED, 200, m])
+    rows = np.unique(np.concatenate([[0, 15, 16, m - 17, m - 1], rng.integers(0, m, size=120)]))
+    for batch, kernels in ((1, ("auto",)), (3, ("auto",)), (80, ("auto",))):
+        x = syn.make_x(batch, n, seed=(200, batch))
+        xd = gpu.to_dev(x)
+        for p in (2, 3, 4):
+            y = bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd)
+            torch.cuda.synchronize()
+            sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"{name} p={p} batch={batch} ({bcq.last_kernel()})")
+
+
+def test_prefix_invariance_and_determinism(gpu):
+    """Only the first p planes are read (section 3.3): scrambling the others leaves y bit-identical;
+    repeated launches give bit-identical results."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    m, n = 300, 4096
+    layer = syn.make_layer(m, n, seed=(210, 0))
+    x = gpu.to_dev(syn.make_x(2, n, seed=(210, 0)))
+    for kernel in ("plane_mfma", "sign_select", "dequant_mfma"):
+        bcq.select_kernel(kernel)
+        try:
+            for p in (1, 2, 3):
+                scrambled = layer.planes.copy()
+                scrambled[p:] = syn.make_planes(m, n, seed=(210, p))[p:]
+                sc = gpu.to_dev(layer.scales[p])
+                y0 = bcq.bcq_gemv(gpu.to_dev(layer.planes), sc, p, x)
+                y1 = bcq.bcq_gemv(gpu.to_dev(scrambled), sc, p, x)
+                y2 = bcq.bcq_gemv(gpu.to_dev(layer.planes), sc, p, x)
+                torch.cuda.synchronize()
+                assert torch.equal(y0, y1), f"{kernel}: planes >= p influenced the result"
+                assert torch.equal(y0, y2), f"{kernel}: not deterministic"
+        finally:
+            bcq.select_kernel("auto")
+
+
+def test_one_hot_readout_and_symmetries(gpu, oracle):
+    """x = e_j with power-of-two scales reads W_p[r, j] back exactly; y(-x) = -y(x); complementing
+    every plane negates y (all exact in every kernel up to the final rounding)."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    m, n, p = 64, 2048, 3
+    planes = syn.make_planes(m, n, seed=(220, 0))
+    scales = np.empty((p, m, n // 128), dtype=np.float16)
+    scales[0], scales[1], scales[2] = 1.0, 0.25, 0.0625
+    w = oracle.dequant(planes, scales)                      # exact: multiples of 1/16 below 2
+    cols = [0, 1, 2, 3, 31, 32, 63, 64, 127, 128, 1023, 1024, 1500, 2047]
+    x = np.zeros((len(cols), n), dtype=np.float16)
+    for b, j in enumerate(cols):
+        x[b, j] = 1.0
+    xr = syn.make_x(4, n, seed=(220, 1))
+    for kernel in ("plane_mfma", "sign_select", "dequant_mfma"):
+        bcq.select_kernel(kernel)
+        try:
+            y = bcq.bcq_gemv(gpu.to_dev(planes), gpu.to_dev(scales), p, gpu.to_dev(x)).cpu().numpy().astype(np.float64)
+            assert np.array_equal(y, w[:, cols].T), f"{kernel}: one-hot read-out differs"
+            ya = bcq.bcq_gemv(gpu.to_dev(planes), gpu.to_dev(scales), p, gpu.to_dev(xr))
+            yn = bcq.bcq_gemv(gpu.to_dev(planes), gpu.to_dev(scales), p, gpu.to_dev(-xr))
+            yc = bcq.bcq_gemv(gpu.to_dev(~planes), gpu.to_dev(scales), p, gpu.to_dev(xr))
+            torch.cuda.synchronize()
+            assert torch.equal(yn, -ya), f"{kernel}: y(-x) != -y(x)"
+            assert torch.equal(yc, -ya), f"{kernel}: complemented planes do not negate y"
+        finally:
+            bcq.select_kernel("auto")
+
+
+def test_mixed_equals_uniform_per_request_and_request_permutation(gpu):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    m, n = 200, 4096
+    layer = syn.make_layer(m, n, seed=(230, 0))
+    dl = gpu.DeviceLayer(layer)
+    batch = 9
+    x = syn.make_x(batch, n, seed=(230, 1))
+    p_req = np.array([2, 4, 3, 1, 4, 2, 3, 3, 1], dtype=np.int32)
+    ym = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req), gpu.to_dev(x))
+    for b in range(batch):
+        yu = bcq.bcq_gemv(dl.planes, dl.scales[int(p_req[b])], int(p_req[b]), gpu.to_dev(x[b:b + 1]))
+        assert torch.equal(ym[b], yu[0]), f"request {b}: mixed result differs from the uniform-precision call"
+    perm = np.array([3, 0, 8, 1, 7, 2, 6, 4, 5])
+    yp = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req[perm]), gpu.to_dev(np.ascontiguousarray(x[perm])))
+    torch.cuda.synchronize()
+    assert torch.equal(yp, ym[torch.from_numpy(perm).to(ym.device)])
+
+
+def test_p_req_is_clamped_and_missing_scale_set_gives_zeros(gpu, oracle):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    m, n = 48, 1024
+    layer = syn.make_layer(m, n, seed=(240, 0))
+    dl = gpu.DeviceLayer(layer)
+    x = syn.make_x(4, n, seed=(240, 1))
+    for kernel in ("plane_mfma", "sign_select"):
+        bcq.select_kernel(kernel)
+        try:
+            y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(np.array([0, 9, -3, 4], dtype=np.int32)), gpu.to_dev(x))
+            y_ref, a_ref = oracle.gemm_mixed(layer.planes, layer.scales, [1, 4, 1, 4], x)
+            gpu.assert_within_tolerance(y, y_ref, a_ref, f"{kernel}: clamped p_req")
+            partial = {2: dl.scales[2], 4: dl.scales[4]}                     # no set for precision 3
+            y = bcq.bcq_gemm_mixed(dl.planes, partial, gpu.to_dev(np.array([2, 3, 4, 3], dtype=np.int32)), gpu.to_dev(x))
+            torch.cuda.synchronize()
+            y_ref, a_ref = oracle.gemm_mixed(layer.planes, layer.scales, [2, 2, 4, 2], x)
+            y_ref[[1, 3]] = 0.0
+            a_ref[[1, 3]] = 0.0
+            gpu.assert_within_tolerance(y, y_ref, a_ref, f"{kernel}: missing scale set")
+            assert torch.count_nonzero(y[1]) == 0 and torch.count_nonzero(y[3]) == 0
+        finally:
+            bcq.select_kernel("auto")
+
+
+def test_extreme_activation_magnitudes(gpu, oracle):
+    """Large, tiny and subnormal binary16 activations (the exact E5M2 split must not overflow or lose them)."""
+    m, n = 40, 2048
+    layer = syn.make_layer(m, n, seed=(250, 0), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    rng = np.random.default_rng([syn.BASE_SEED, 250])
+    x = np.empty((4, n), dtype=np.float16)
+    x[0] = (rng.normal(size=n) * 4.0e3).clip(-65504, 65504).astype(np.float16)      # large, products still fit binary16
+    x[1] = (rng.normal(size=n) * 1e-2).astype(np.float16)
+    x[2] = (rng.normal(size=n) * 3e-6).astype(np.float16)                             # mostly subnormal
+    x[3] = 0.0
+    x[3, ::16] = np.where(rng.random(n // 16) < 0.5, 65504.0, -65504.0)               # the largest finite binary16 values
+    for kernel in ("plane_mfma", "sign_select", "dequant_mfma"):
+        # row 2: |x| < 2^-6 may lose bits below 2^-16 in plane_mfma; the documented bound is 2^-16 per element
+        used, worst = gpu.check_gemv(dl, 3, x[[0, 1, 3]], kernel)
+    y = __import__("paper_2510_10467_amd").bcq_gemv(dl.planes, dl.scales[3], 3, gpu.to_dev(x[2:3])).cpu().numpy().astype(np.float64)
+    y_ref, a_ref = oracle.gemv(layer.planes, layer.scales[3], x[2:3])
+    slack = 2.0 ** -16 * np.abs(oracle.dequant(layer.planes, layer.scales[3])).sum(axis=1)[None, :]
+    assert np.all(np.abs(y - y_ref) <= oracle.tolerance(y_ref, a_ref) + slack)
+
+
+def test_graph_replay_matches_eager(gpu):
+    """The launches are capturable; several replays with eager work in between stay bit-identical."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    m, n = 512, 4096
+    layer = syn.make_layer(m, n, seed=(260, 0))
+    dl = gpu.DeviceLayer(layer)
+    x = gpu.to_dev(syn.make_x(2, n, seed=(260, 1)))
+    p_req = gpu.to_dev(np.array([3, 2], dtype=np.int32))
+    y1 = torch.empty((2, m), dtype=torch.float16, device=x.device)
+    y2 = torch.empty_like(y1)
+    eager1 = bcq.bcq_gemv(dl.planes, dl.scales[4], 4, x).clone()
+    eager2 = bcq.bcq_gemm_mixed(dl.planes, dl.scales, p_req, x).clone()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        bcq.bcq_gemv(dl.planes, dl.scales[4], 4, x, y1)
+        bcq.bcq_gemm_mixed(dl.planes, dl.scales, p_req, x, y2)
+    for _ in range(3):
+        y1.zero_()
+        y2.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y1, eager1) and torch.equal(y2, eager2)
+        _ = bcq.bcq_gemv(dl.planes, dl.scales[2], 2, x)          # eager work between replays
+        torch.cuda.synchronize()
+
+
+def test_large_pack_round_trip(gpu, oracle):
+    import paper_2510_10467_amd as bcq
+    raw = syn.make_planes(4096, 4096, seed=(270, 0))
+    codes = bcq.bcq_unpack(gpu.to_dev(raw))
+    again = bcq.bcq_pack(codes)
+    assert np.array_equal(again.cpu().numpy().view(np.uint32), raw)
+    sample = codes[:, :8, :].cpu().numpy()
+    assert np.array_equal(sample, oracle.unpack(np.ascontiguousarray(raw[:, :8, :])))

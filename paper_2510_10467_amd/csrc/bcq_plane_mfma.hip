@@ -84,18 +84,6 @@ struct Lds {
     __host__ __device__ static constexpr int total(int KS, int RB) { return red_off(KS, RB) + 64 * KS * RB * 4; }
 };
 
-// 4x4 transpose of one dword per register across the four lane quarters
-// (lanes l, l+16, l+32, l+48): afterwards register t of quarter q holds what
-// register q of quarter t held.
-__device__ __forceinline__ void quarter_transpose(uint32_t &v0, uint32_t &v1, uint32_t &v2, uint32_t &v3)
-{
-    v2u s;
-    s = __builtin_amdgcn_permlane32_swap(v0, v2, false, false); v0 = s[0]; v2 = s[1];
-    s = __builtin_amdgcn_permlane32_swap(v1, v3, false, false); v1 = s[0]; v3 = s[1];
-    s = __builtin_amdgcn_permlane16_swap(v0, v1, false, false); v0 = s[0]; v1 = s[1];
-    s = __builtin_amdgcn_permlane16_swap(v2, v3, false, false); v2 = s[0]; v3 = s[1];
-}
-
 // 32 weight bits -> the lane's four FP4 operand registers (8 codes each).
 // Register s, nibble i carries bit 4i + 3 - s in its sign position over the code of 1.0.
 // `sign` and `one` hold 0x88888888 and 0x22222222 in registers so each line is one V_AND_OR_B32.
@@ -110,14 +98,16 @@ __device__ __forceinline__ v8i expand_plane_word(uint32_t w, uint32_t sign, uint
 }
 
 // Sweep of one wave over its K slices for PH planes; returns this lane's partial sum.
-//   voff_w   this lane's byte offset into a plane: row * row_stride + q * 16
+//   voff_wa  this lane's byte offsets into a plane for its two loads: lane (l >> 3, l & 7) fetches one
+//   voff_wb  16-byte group of row l >> 3 and of row 8 + (l >> 3), so a load instruction covers whole
+//            128-byte lines; which group of the line a lane takes is XOR-swizzled by the row (below)
 //   voff_s   this lane's byte offset into a scale plane: row * scale_row_stride
 //   p_mine   precision of the request this lane reports on (0: none); sbase its scale set
 // MIXED: lanes of different quarters may belong to requests of different precisions.
 template <int PH, int NB, bool MIXED>
 __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks,
-                                       int q, int r16, int tid, int nthreads, int b0, int nb, uint32_t voff_w,
-                                       uint32_t voff_s, int p_mine, const unsigned char *sbase)
+                                       int q, int r16, int tid, int nthreads, int b0, int nb, uint32_t voff_wa,
+                                       uint32_t voff_wb, uint32_t voff_s, int p_mine, const unsigned char *sbase)
 {
     using L = Lds<NB>;
     const int KS = pr.KS;
@@ -165,11 +155,10 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         u32x4 wlo[PH], whi[PH];
 #pragma unroll
         for (int i = 0; i < PH; ++i) {
-            // both halves of a 128-byte line are requested back to back: 64 contiguous bytes per row and
-            // instruction (groups q, then groups 4 + q of the slice)
-            const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8) + voff_w;
-            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp));
-            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + 64));
+            // rows 0-7, then rows 8-15 of the block: 128 contiguous bytes per row and instruction
+            const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8);
+            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_wa));
+            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_wb));
         }
 
         // ---- 2. workgroup builds the operand image of this chunk --------------------------
@@ -225,39 +214,48 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 if (!(i < p_eff)) sc[i] = u32x4{0, 0, 0, 0};
         }
 
-        // ---- 3. per group: expand plane words, one MFMA per (group, plane), scale, accumulate
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            // after the transpose, register t of quarter q is dword q of group 4j + t of the slice
-            uint32_t wt[PH][4];
+        // ---- 3. plane words change hands inside the wave: row-major in, operand-major out ------------
+        // The wave's 2 KiB of the (now free) staging area holds one plane's 16 rows x 128 bytes.  Row r
+        // keeps its group c at 16-byte slot c ^ (r >> 1) (that is where the lane that fetched it writes
+        // it, a plain lane-ordered 1 KiB store), so that the 64 dword reads of one group, one per
+        // (row, K quarter), fall into 64 different banks.  LDS operations of a wave complete in order:
+        // a plane may overwrite the previous one as soon as its reads have been issued.
+        uint32_t wt[PH][kSliceGroups];
+        {
+            unsigned char *shf = lds + stage_off + (tid >> 6) * 2048;
+            const int lane = tid & 63;
+            const int rd0 = r16 * 128 + (((r16 >> 1) & 7) << 4) + q * 4;
 #pragma unroll
             for (int i = 0; i < PH; ++i) {
-                const u32x4 srcw = j ? whi[i] : wlo[i];
-                wt[i][0] = srcw.x; wt[i][1] = srcw.y; wt[i][2] = srcw.z; wt[i][3] = srcw.w;
-                quarter_transpose(wt[i][0], wt[i][1], wt[i][2], wt[i][3]);
+                *reinterpret_cast<u32x4 *>(shf + lane * 16) = wlo[i];
+                *reinterpret_cast<u32x4 *>(shf + 1024 + lane * 16) = whi[i];
+#pragma unroll
+                for (int g = 0; g < kSliceGroups; ++g)
+                    wt[i][g] = *reinterpret_cast<const uint32_t *>(shf + (rd0 ^ (g << 4)));
+            }
+        }
+
+        // ---- 4. per group: expand plane words, one MFMA per (group, plane), scale, accumulate
+#pragma unroll
+        for (int gl = 0; gl < kSliceGroups; ++gl) {
+            const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes);
+            const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes + L::kHalfBytes);
+            const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            v4f d[PH];
+#pragma unroll
+            for (int i = 0; i < PH; ++i) {
+                const v8i wb = expand_plane_word(wt[i][gl], sign, one);
+                const v4f zero = {0.f, 0.f, 0.f, 0.f};
+                // A: E5M2 activation terms (cbsz = 1), B: FP4 weight codes (blgp = 4), no block scaling
+                d[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, zero, 1, 4, 0, 0, 0, 0);
             }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int gl = 4 * j + t;                           // group inside the slice
-                const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes);
-                const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes + L::kHalfBytes);
-                const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-                v4f d[PH];
-#pragma unroll
-                for (int i = 0; i < PH; ++i) {
-                    const v8i wb = expand_plane_word(wt[i][t], sign, one);
-                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
-                    // A: E5M2 activation terms (cbsz = 1), B: FP4 weight codes (blgp = 4), no block scaling
-                    d[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, zero, 1, 4, 0, 0, 0, 0);
-                }
-#pragma unroll
-                for (int i = 0; i < PH; ++i) {
-                    const uint32_t sw = sc[i][gl >> 1];
-                    const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
-                    const float sum = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
-                    // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
-                    acc = fmaf(-alpha, sum, acc);
-                }
+            for (int i = 0; i < PH; ++i) {
+                const uint32_t sw = sc[i][gl >> 1];
+                const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
+                const float sum = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
+                // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
+                acc = fmaf(-alpha, sum, acc);
             }
         }
     }
@@ -301,12 +299,18 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     const bool row_ok = row < pr.m;
     if (!row_ok) row = pr.m - 1;              // keep loads in bounds; the result is discarded
     // rows and row strides are below 2^24 (checked on the host): full-rate 24-bit multiplies
-    const uint32_t voff_w = __umul24(row, pr.row_stride) + q * 16;
     const uint32_t voff_s = __umul24(row, pr.scale_row_stride);
+    // plane loads: lane (l >> 3, l & 7) takes 16-byte slot l & 7 of block rows l >> 3 and 8 + (l >> 3);
+    // slot s of row r holds group s ^ (r >> 1) of the slice
+    const uint32_t r8 = lane >> 3, c8 = lane & 7;
+    const uint32_t row_a = min(wg_rows0 + rb * 16 + r8, pr.m - 1);
+    const uint32_t row_b = min(wg_rows0 + rb * 16 + 8 + r8, pr.m - 1);
+    const uint32_t voff_wa = __umul24(row_a, pr.row_stride) + ((c8 ^ (r8 >> 1)) << 4);
+    const uint32_t voff_wb = __umul24(row_b, pr.row_stride) + ((c8 ^ (4 + (r8 >> 1))) << 4);
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB, false>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, P, pr.scales[P]);
+        acc = sweep<P, NB, false>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, P, pr.scales[P]);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs
         int p_mine = 0, p_hi = 0;
@@ -320,10 +324,10 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
         const unsigned char *sbase = pr.scales[p_mine > 0 ? p_mine : p_hi];
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 2: acc = sweep<2, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 3: acc = sweep<3, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
-        case 4: acc = sweep<4, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_w, voff_s, p_mine, sbase); break;
+        case 1: acc = sweep<1, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
+        case 2: acc = sweep<2, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
+        case 3: acc = sweep<3, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
+        case 4: acc = sweep<4, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }

@@ -66,10 +66,10 @@ struct PlaneMfmaParams {
     float inv_ks;                           // 1 / KS
 };
 
-// LDS layout of one chunk for NB requests per tile and KS slices:
-//   [0, image)        operand image: 16-byte rows; group g, register half h, lane quarter qa, operand row r at
-//                     g*kGroupBytes + h*kHalfBytes + (qa*4NB + r)*16
-//   [image, red)      staged binary16 activations of the chunk, request-major
+// LDS layout for NB requests per tile, KS slices and RB row blocks per workgroup:
+//   [0, image)        operand image: 16-byte rows; slice ks, group g, register half h, lane quarter qa, operand
+//                     row r at ks*kSliceImage + g*kGroupBytes + h*kHalfBytes + (qa*4NB + r)*16
+//   [image, red)      a tile per wave in which plane words change from row-major to operand order
 //   [red, total)      one fp32 partial sum per thread for the final combine
 template <int NB>
 struct Lds {
@@ -77,10 +77,10 @@ struct Lds {
     static constexpr int kHalfBytes = 4 * kRows * 16 + 16;          // operand registers 0-3 (or 4-7) of all lanes, padded
     static constexpr int kGroupBytes = 2 * kHalfBytes;              // one group's image; the padding spreads LDS banks
     static constexpr int kSliceImage = kSliceGroups * kGroupBytes;   // 4 KiB * NB
-    static constexpr int kSliceStage = kSliceCols * 2;               // per request
-    __host__ __device__ static constexpr int stage_off(int KS) { return KS * kSliceImage; }
-    // per-wave partial sums for the final combine
-    __host__ __device__ static constexpr int red_off(int KS, int RB) { return KS * (kSliceImage + NB * kSliceStage); }
+    static constexpr int kTileRow = 128 + 16;                        // padded so that rows start 4 banks apart (mod 64)
+    static constexpr int kWaveTile = 16 * kTileRow;                  // 16 rows x 128 bytes of one plane
+    __host__ __device__ static constexpr int tile_off(int KS) { return KS * kSliceImage; }
+    __host__ __device__ static constexpr int red_off(int KS, int RB) { return KS * kSliceImage + KS * RB * kWaveTile; }
     __host__ __device__ static constexpr int total(int KS, int RB) { return red_off(KS, RB) + 64 * KS * RB * 4; }
 };
 
@@ -97,150 +97,155 @@ __device__ __forceinline__ v8i expand_plane_word(uint32_t w, uint32_t sign, uint
     return r;
 }
 
+// What one wave fetches for one K slice: activations, scales, plane words.
+template <int PH, int NB>
+struct SliceLoads {
+    u32x4 xv[NB][2];                        // 16 consecutive columns (one image unit) per request slot
+    u32x4 sc[PH];                           // the 8 scales of the lane's row, per plane
+    u32x4 wa[PH], wb[PH];                   // plane words: rows 0-7 and rows 8-15 of the block
+};
+
+// Lane addressing of a wave, fixed for the whole kernel.
+struct LaneOffsets {
+    uint32_t wa, wb;                        // byte offsets into a plane of the lane's two plane loads
+    uint32_t s;                             // byte offset into a scale plane: row * scale_row_stride
+    uint32_t x[kMaxBatchTile];              // byte offset of the lane's image unit in each request slot's activations
+};
+
+template <int PH, int NB, bool MIXED>
+__device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneMfmaParams &pr, const LaneOffsets &off,
+                                            const unsigned char *sbase, int p_mine, int slice_c)
+{
+    // in the order of use: activations, scales, planes
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb) {
+        const unsigned char *xp = pr.x + off.x[bb] + (uint32_t)slice_c * (kSliceCols * 2);
+        ld.xv[bb][0] = *reinterpret_cast<const u32x4 *>(xp);
+        ld.xv[bb][1] = *reinterpret_cast<const u32x4 *>(xp + 16);
+    }
+#pragma unroll
+    for (int i = 0; i < PH; ++i) {
+        const int ii = MIXED ? min(i, max(p_mine, 1) - 1) : i;      // stay inside the lane's own scale set
+        ld.sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + off.s +
+                                                    (uint32_t)slice_c * (kSliceGroups * 2));
+    }
+#pragma unroll
+    for (int i = 0; i < PH; ++i) {
+        // rows 0-7, then rows 8-15 of the block: 128 contiguous bytes per row and instruction
+        const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8);
+        ld.wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + off.wa));
+        ld.wb[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + off.wb));
+    }
+}
+
 // Sweep of one wave over its K slices for PH planes; returns this lane's partial sum.
-//   voff_wa  this lane's byte offsets into a plane for its two loads: lane (l >> 3, l & 7) fetches one
-//   voff_wb  16-byte group of row l >> 3 and of row 8 + (l >> 3), so a load instruction covers whole
-//            128-byte lines; which group of the line a lane takes is XOR-swizzled by the row (below)
-//   voff_s   this lane's byte offset into a scale plane: row * scale_row_stride
 //   p_mine   precision of the request this lane reports on (0: none); sbase its scale set
 // MIXED: lanes of different quarters may belong to requests of different precisions.
 template <int PH, int NB, bool MIXED>
-__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks,
-                                       int q, int r16, int tid, int nthreads, int b0, int nb, uint32_t voff_wa,
-                                       uint32_t voff_wb, uint32_t voff_s, int p_mine, const unsigned char *sbase)
+__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int wave, int lane,
+                                       const LaneOffsets &off, int p_mine, const unsigned char *sbase)
 {
     using L = Lds<NB>;
-    const int KS = pr.KS;
-    const int stage_off = L::stage_off(KS);
-    const int units = KS * (kSliceCols / 8);                        // 16-byte activation units per request and chunk
-
-    // constants kept in registers so that (w & sign) | one is a single three-operand instruction
-    uint32_t sign = 0x88888888u, one = 0x22222222u;
-    asm volatile("" : "+v"(one));
-    asm volatile("" : "+s"(sign));
-
-    // operand-image address of this lane: row min(r16, 4NB-1) of quarter q, first group of the wave's slice
-    const int arow = r16 < L::kRows ? r16 : L::kRows - 1;
-    const int img_lane = ks * L::kSliceImage + (q * L::kRows + arow) * 16;
+    const int KS = pr.KS, RB = pr.RB;
 
     float acc = 0.f;
     for (int chunk = 0; chunk < pr.nchunk; ++chunk) {
-        const int slice = chunk * KS + ks;                          // global K slice of this wave
-        const bool slice_ok = slice < pr.nslices;
-        const int slice_c = slice_ok ? slice : pr.nslices - 1;
+        const bool slice_ok = chunk * KS + ks < pr.nslices;         // the last chunk may be ragged
         const int p_eff = slice_ok ? p_mine : 0;
-        const uint32_t chunk_byte0 = (uint32_t)chunk * KS * kSliceCols * 2;   // first activation byte of the chunk
-        const uint32_t x_bytes = pr.x_stride;                                 // bytes per request = columns * 2
 
-        // ---- 1. loads in the order of use: activations, scales, then the two halves of every plane
-        u32x4 xv[NB][2];
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2) {
-                const uint32_t u = k2 * nthreads + tid;
-                uint32_t off = chunk_byte0 + u * 16;
-                const bool ok = u < (uint32_t)units && off < x_bytes && b < nb;
-                off = ok ? off : 0;
-                xv[b][k2] = *reinterpret_cast<const u32x4 *>(pr.x + (size_t)(b0 + (b < nb ? b : 0)) * x_bytes + off);
-                if (!ok) xv[b][k2] = u32x4{0, 0, 0, 0};             // ragged last chunk: columns past n are zero
-            }
-        u32x4 sc[PH];
-#pragma unroll
-        for (int i = 0; i < PH; ++i) {
-            const int ii = MIXED ? min(i, max(p_mine, 1) - 1) : i;  // stay inside the lane's own scale set
-            sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + voff_s +
-                                                     (uint32_t)slice_c * (kSliceGroups * 2));
-        }
-        u32x4 wlo[PH], whi[PH];
-#pragma unroll
-        for (int i = 0; i < PH; ++i) {
-            // rows 0-7, then rows 8-15 of the block: 128 contiguous bytes per row and instruction
-            const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8);
-            wlo[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_wa));
-            whi[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + voff_wb));
-        }
+        // ---- 0. the loads go out before anything else is computed: every instruction ahead of them
+        // delays the memory phase of all waves that share the SIMD.  The lane id is made opaque after
+        // them so that no LDS address arithmetic is moved in front of the loop.
+        SliceLoads<PH, NB> ld;
+        issue_loads<PH, NB, MIXED>(ld, pr, off, sbase, p_mine, slice_ok ? chunk * KS + ks : pr.nslices - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" : "+v"(lane));
 
-        // ---- 2. workgroup builds the operand image of this chunk --------------------------
-        if (chunk > 0) __syncthreads();                             // previous image and staging no longer read
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2) {
-                const int u = k2 * nthreads + tid;
-                if (u < units) *reinterpret_cast<u32x4 *>(lds + stage_off + b * KS * L::kSliceStage + u * 16) = xv[b][k2];
-            }
-        __syncthreads();
-        // One unit = 16 consecutive columns of one request (32 bytes of the staging area).  Column
+        // constants kept in registers so that (w & sign) | one is a single three-operand instruction
+        uint32_t sign = 0x88888888u, one = 0x22222222u;
+        asm volatile("" : "+v"(one));
+        asm volatile("" : "+s"(sign));
+
+        const int q = lane >> 4, r16 = lane & 15;
+        // operand-image address of this lane: row min(r16, 4NB-1) of quarter q, first group of the wave's slice
+        const int arow = r16 < L::kRows ? r16 : L::kRows - 1;
+        const unsigned char *img_lane = lds + ks * L::kSliceImage + (q * L::kRows + arow) * 16;
+        // image unit `lane` of the slice = 16 consecutive columns: group lane >> 3, part u16 = lane & 7.  Column
         // 16u + low + 4i (i = 0..3) belongs to operand byte 8z + 4(u&1) + i of lane quarter 2*((u>>1)&1) + w
         // with 2w + z = 3 - low, so a unit yields one dword for each (low, term): 16 dword stores.
-        for (int unit = tid; unit < KS * kSliceGroups * 8; unit += nthreads) {
-            const int g = unit >> 3, u16 = unit & 7;
-            const int dst0 = g * L::kGroupBytes + (u16 >> 2) * L::kHalfBytes + (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
+        const int u16 = lane & 7;
+        unsigned char *img_unit = lds + ks * L::kSliceImage + (lane >> 3) * L::kGroupBytes + (u16 >> 2) * L::kHalfBytes +
+                                  (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
+        // Plane words change hands inside the wave, row-major in, operand-major out: the wave's tile holds
+        // one plane's 16 rows x 128 bytes.  Rows are 144 bytes apart, so the 64 dword reads of one group,
+        // one per (row, K quarter), fall into 64 different banks.
+        unsigned char *tile = lds + L::tile_off(KS) + wave * L::kWaveTile;
+        unsigned char *tile_wr = tile + (lane >> 3) * L::kTileRow + (lane & 7) * 16;
+        const unsigned char *tile_rd = tile + r16 * L::kTileRow + q * 4;
+
+        // ---- 1. operand image of this slice: the RB waves that share it convert one request slot in RB each.
+        // A wave reads back only what waves of its own slice wrote; with RB == 1 that is the wave itself,
+        // whose LDS operations complete in order, so no barrier is needed.
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const u32x4 *sp = reinterpret_cast<const u32x4 *>(lds + stage_off + b * KS * L::kSliceStage + unit * 32);
-                const u32x4 c0 = sp[0], c1 = sp[1];
-                const uint32_t dwd[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};   // dword k = columns 2k, 2k+1
+        for (int bb = 0; bb < NB; ++bb) {
+            const int b = rb + bb * RB;                             // request slot of the tile
+            if (b >= NB) break;
+            const u32x4 c0 = ld.xv[bb][0], c1 = ld.xv[bb][1];
+            const uint32_t dwd[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};       // dword k = columns 2k, 2k+1
 #pragma unroll
-                for (int low = 0; low < 4; ++low) {
-                    const uint32_t sel = (low & 1) ? 0x07060302u : 0x05040100u;               // upper or lower halves
-                    const int k0 = low >> 1;
-                    // packed pairs (col low, col low+4) and (col low+8, col low+12)
-                    h2 r01 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 2], dwd[k0], sel));
-                    h2 r23 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 6], dwd[k0 + 4], sel));
-                    const int inv = 3 - low, w = inv >> 1, z = inv & 1;
-                    uint32_t *d32 = reinterpret_cast<uint32_t *>(lds + dst0 + w * (L::kRows * 16) + 8 * z + b * 64);
-                    // exact split into four E5M2 terms: top bytes of the running binary16 remainders
+            for (int low = 0; low < 4; ++low) {
+                const uint32_t sel = (low & 1) ? 0x07060302u : 0x05040100u;                   // upper or lower halves
+                const int k0 = low >> 1;
+                // packed pairs (col low, col low+4) and (col low+8, col low+12)
+                h2 r01 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 2], dwd[k0], sel));
+                h2 r23 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 6], dwd[k0 + 4], sel));
+                const int inv = 3 - low, w = inv >> 1, z = inv & 1;
+                uint32_t *d32 = reinterpret_cast<uint32_t *>(img_unit + w * (L::kRows * 16) + 8 * z + b * 64);
+                // exact split into four E5M2 terms: top bytes of the running binary16 remainders
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
-                        const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
-                        if (j < 3) {
-                            r01 = r01 - __builtin_bit_cast(h2, t01);
-                            r23 = r23 - __builtin_bit_cast(h2, t23);
-                        }
-                        d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);          // bytes: i = 0, 1, 2, 3
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
+                    const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
+                    if (j < 3) {
+                        r01 = r01 - __builtin_bit_cast(h2, t01);
+                        r23 = r23 - __builtin_bit_cast(h2, t23);
                     }
+                    d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);              // bytes: i = 0, 1, 2, 3
                 }
             }
         }
-        __syncthreads();
+        if (RB > 1) __syncthreads();
 
         // scales of planes this lane must not use (beyond its precision, or a slice past the end) become zero
         if (MIXED || !slice_ok) {
 #pragma unroll
             for (int i = 0; i < PH; ++i)
-                if (!(i < p_eff)) sc[i] = u32x4{0, 0, 0, 0};
+                if (!(i < p_eff)) ld.sc[i] = u32x4{0, 0, 0, 0};
         }
 
-        // ---- 3. plane words change hands inside the wave: row-major in, operand-major out ------------
-        // The wave's 2 KiB of the (now free) staging area holds one plane's 16 rows x 128 bytes.  Row r
-        // keeps its group c at 16-byte slot c ^ (r >> 1) (that is where the lane that fetched it writes
-        // it, a plain lane-ordered 1 KiB store), so that the 64 dword reads of one group, one per
-        // (row, K quarter), fall into 64 different banks.  LDS operations of a wave complete in order:
-        // a plane may overwrite the previous one as soon as its reads have been issued.
+        // ---- 2. plane words into operand order.  LDS operations of a wave complete in order: a plane
+        // may overwrite the previous one as soon as its reads have been issued.
         uint32_t wt[PH][kSliceGroups];
-        {
-            unsigned char *shf = lds + stage_off + (tid >> 6) * 2048;
-            const int lane = tid & 63;
-            const int rd0 = r16 * 128 + (((r16 >> 1) & 7) << 4) + q * 4;
 #pragma unroll
-            for (int i = 0; i < PH; ++i) {
-                *reinterpret_cast<u32x4 *>(shf + lane * 16) = wlo[i];
-                *reinterpret_cast<u32x4 *>(shf + 1024 + lane * 16) = whi[i];
+        for (int i = 0; i < PH; ++i) {
+            *reinterpret_cast<u32x4 *>(tile_wr) = ld.wa[i];
+            *reinterpret_cast<u32x4 *>(tile_wr + 8 * L::kTileRow) = ld.wb[i];
 #pragma unroll
-                for (int g = 0; g < kSliceGroups; ++g)
-                    wt[i][g] = *reinterpret_cast<const uint32_t *>(shf + (rd0 ^ (g << 4)));
-            }
+            for (int g = 0; g < kSliceGroups; ++g)
+                wt[i][g] = *reinterpret_cast<const uint32_t *>(tile_rd + g * 16);
         }
 
-        // ---- 4. per group: expand plane words, one MFMA per (group, plane), scale, accumulate
+        // ---- 3. per group: expand plane words, one MFMA per (group, plane), scale, accumulate;
+        // the operand rows of the next group are fetched while this one is in the matrix pipe
+        u32x4 lo = *reinterpret_cast<const u32x4 *>(img_lane);
+        u32x4 hi = *reinterpret_cast<const u32x4 *>(img_lane + L::kHalfBytes);
 #pragma unroll
         for (int gl = 0; gl < kSliceGroups; ++gl) {
-            const u32x4 lo = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes);
-            const u32x4 hi = *reinterpret_cast<const u32x4 *>(lds + img_lane + gl * L::kGroupBytes + L::kHalfBytes);
             const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            if (gl + 1 < kSliceGroups) {
+                lo = *reinterpret_cast<const u32x4 *>(img_lane + (gl + 1) * L::kGroupBytes);
+                hi = *reinterpret_cast<const u32x4 *>(img_lane + (gl + 1) * L::kGroupBytes + L::kHalfBytes);
+            }
             v4f d[PH];
 #pragma unroll
             for (int i = 0; i < PH; ++i) {
@@ -251,13 +256,17 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
             }
 #pragma unroll
             for (int i = 0; i < PH; ++i) {
-                const uint32_t sw = sc[i][gl >> 1];
+                const uint32_t sw = ld.sc[i][gl >> 1];
                 const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
                 const float sum = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
                 // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
                 acc = fmaf(-alpha, sum, acc);
             }
+            // groups stay in order: deferring the sums would keep every MFMA result register alive
+            __builtin_amdgcn_sched_barrier(0);
         }
+        asm volatile("" : "+v"(acc));                               // the sums are due here, not past the branch below
+        if (RB > 1) __syncthreads();                                // image no longer read: the next chunk may replace it
     }
     return acc;
 }
@@ -268,17 +277,14 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
-    const int nthreads = blockDim.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int KS = pr.KS;
+    const int KS = pr.KS, RB = pr.RB;
     int ks = wave, rb = 0;                    // K slice of this wave inside a chunk, row block inside the workgroup
-    if (pr.RB > 1) {
+    if (RB > 1) {
         rb = (int)(((float)wave + 0.5f) * pr.inv_ks);               // wave / KS for wave < 16
         ks = wave - rb * KS;
     }
-    const int q = lane >> 4;                  // lane quarter: K sub-block on the weight side, request on the output side
-    const int r16 = lane & 15;
     // Workgroup id -> (row-block group, batch tile).  Ids that differ by 8 run on the same XCD (ids
     // are dealt round-robin to the 8 XCDs), so the tiles of one row-block group are placed 8 apart:
     // they start close in time on one XCD and all but the first find the planes in that XCD's L2.
@@ -293,24 +299,33 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     if (wg >= pr.nwg_rows) return;                                  // padding of the last span (whole workgroup)
     const int b0 = tile * kMaxBatchTile;
     const int nb = min(NB, pr.batch - b0);
-    const uint32_t wg_rows0 = wg * pr.RB * 16;
+    const uint32_t block_row0 = (wg * RB + rb) * 16;
+    const uint32_t last_row = pr.m - 1;
 
-    uint32_t row = wg_rows0 + rb * 16 + r16;
-    const bool row_ok = row < pr.m;
-    if (!row_ok) row = pr.m - 1;              // keep loads in bounds; the result is discarded
     // rows and row strides are below 2^24 (checked on the host): full-rate 24-bit multiplies
-    const uint32_t voff_s = __umul24(row, pr.scale_row_stride);
-    // plane loads: lane (l >> 3, l & 7) takes 16-byte slot l & 7 of block rows l >> 3 and 8 + (l >> 3);
-    // slot s of row r holds group s ^ (r >> 1) of the slice
+    LaneOffsets off;
+    // plane loads: lane (l >> 3, l & 7) takes group l & 7 (16 bytes) of block rows l >> 3 and 8 + (l >> 3).
+    // Rows past the end repeat the last row.
     const uint32_t r8 = lane >> 3, c8 = lane & 7;
-    const uint32_t row_a = min(wg_rows0 + rb * 16 + r8, pr.m - 1);
-    const uint32_t row_b = min(wg_rows0 + rb * 16 + 8 + r8, pr.m - 1);
-    const uint32_t voff_wa = __umul24(row_a, pr.row_stride) + ((c8 ^ (r8 >> 1)) << 4);
-    const uint32_t voff_wb = __umul24(row_b, pr.row_stride) + ((c8 ^ (4 + (r8 >> 1))) << 4);
+    off.wa = __umul24(min(block_row0 + r8, last_row), pr.row_stride) + c8 * 16;
+    off.wb = __umul24(min(block_row0 + 8 + r8, last_row), pr.row_stride) + c8 * 16;
+    // output side: lane (q, r16) reports row r16 of the block for request slot q
+    const int q = lane >> 4;
+    uint32_t row = block_row0 + (lane & 15);
+    const bool row_ok = row <= last_row;
+    row = min(row, last_row);
+    off.s = __umul24(row, pr.scale_row_stride);
+    // activations: the wave converts request slots rb, rb + RB, ... of the tile, 32 bytes per lane and
+    // slot; absent slots repeat the tile's first request (their results are never stored)
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb) {
+        const int b = rb + bb * RB;
+        off.x[bb] = (uint32_t)(b0 + (b < nb ? b : 0)) * pr.x_stride + lane * 32;
+    }
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB, false>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, P, pr.scales[P]);
+        acc = sweep<P, NB, false>(pr, lds, ks, rb, wave, lane, off, P, pr.scales[P]);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs
         int p_mine = 0, p_hi = 0;
@@ -324,16 +339,16 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
         const unsigned char *sbase = pr.scales[p_mine > 0 ? p_mine : p_hi];
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
-        case 2: acc = sweep<2, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
-        case 3: acc = sweep<3, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
-        case 4: acc = sweep<4, NB, true>(pr, lds, ks, q, r16, tid, nthreads, b0, nb, voff_wa, voff_wb, voff_s, p_mine, sbase); break;
+        case 1: acc = sweep<1, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
+        case 2: acc = sweep<2, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
+        case 3: acc = sweep<3, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
+        case 4: acc = sweep<4, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }
 
     // ---- combine the KS partial sums of each row block in a fixed order, store binary16 -----
-    float *red = reinterpret_cast<float *>(lds + Lds<NB>::red_off(KS, pr.RB));
+    float *red = reinterpret_cast<float *>(lds + Lds<NB>::red_off(KS, RB));
     red[wave * 64 + lane] = acc;
     __syncthreads();
     if (ks == 0) {

@@ -142,14 +142,15 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
 //   p_mine   precision of the request this lane reports on (0: none); sbase its scale set
 // MIXED: lanes of different quarters may belong to requests of different precisions.
 template <int PH, int NB, bool MIXED>
-__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int wave, int lane,
+__device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int RB, int wave, int lane,
                                        const LaneOffsets &off, int p_mine, const unsigned char *sbase)
 {
     using L = Lds<NB>;
-    const int KS = pr.KS, RB = pr.RB;
+    const int KS = pr.KS;
 
     float acc = 0.f;
-    for (int chunk = 0; chunk < pr.nchunk; ++chunk) {
+    int chunk = 0;
+    do {                                                            // nchunk >= 1
         const bool slice_ok = chunk * KS + ks < pr.nslices;         // the last chunk may be ragged
         const int p_eff = slice_ok ? p_mine : 0;
 
@@ -267,7 +268,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         }
         asm volatile("" : "+v"(acc));                               // the sums are due here, not past the branch below
         if (RB > 1) __syncthreads();                                // image no longer read: the next chunk may replace it
-    }
+    } while (++chunk < pr.nchunk);
     return acc;
 }
 
@@ -279,26 +280,31 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int KS = pr.KS, RB = pr.RB;
-    int ks = wave, rb = 0;                    // K slice of this wave inside a chunk, row block inside the workgroup
-    if (RB > 1) {
-        rb = (int)(((float)wave + 0.5f) * pr.inv_ks);               // wave / KS for wave < 16
-        ks = wave - rb * KS;
+    const int KS = pr.KS;
+    // One request per tile (NB == 1): a workgroup is one row block, wave = K slice, the grid is exact.
+    // Otherwise RB row blocks share a workgroup and the batch tiles of a row-block group are spread over ids.
+    int RB = 1, ks = wave, rb = 0;            // K slice of this wave inside a chunk, row block inside the workgroup
+    uint32_t tile = 0, wg = blockIdx.x;
+    if constexpr (NB > 1) {
+        RB = pr.RB;
+        if (RB > 1) {
+            rb = (int)(((float)wave + 0.5f) * pr.inv_ks);           // wave / KS for wave < 16
+            ks = wave - rb * KS;
+        }
+        // Workgroup id -> (row-block group, batch tile).  Ids that differ by 8 run on the same XCD (ids
+        // are dealt round-robin to the 8 XCDs), so the tiles of one row-block group are placed 8 apart:
+        // they start close in time on one XCD and all but the first find the planes in that XCD's L2.
+        const uint32_t ntiles = pr.ntiles;
+        if (ntiles > 1) {
+            const uint32_t span_index = (uint32_t)(((float)blockIdx.x + 0.5f) * pr.inv_span);   // id / (8 * ntiles), ids < 2^21
+            const uint32_t rem = blockIdx.x - span_index * 8 * ntiles;
+            tile = rem >> 3;
+            wg = span_index * 8 + (rem & 7);                        // row-block group of this workgroup
+        }
+        if (wg >= pr.nwg_rows) return;                              // padding of the last span (whole workgroup)
     }
-    // Workgroup id -> (row-block group, batch tile).  Ids that differ by 8 run on the same XCD (ids
-    // are dealt round-robin to the 8 XCDs), so the tiles of one row-block group are placed 8 apart:
-    // they start close in time on one XCD and all but the first find the planes in that XCD's L2.
-    const uint32_t ntiles = pr.ntiles;
-    uint32_t tile = 0, wg = blockIdx.x;                             // one tile: the mapping is the identity
-    if (ntiles > 1) {
-        const uint32_t span_index = (uint32_t)(((float)blockIdx.x + 0.5f) * pr.inv_span);   // id / (8 * ntiles), ids < 2^21
-        const uint32_t rem = blockIdx.x - span_index * 8 * ntiles;
-        tile = rem >> 3;
-        wg = span_index * 8 + (rem & 7);                            // row-block group of this workgroup
-    }
-    if (wg >= pr.nwg_rows) return;                                  // padding of the last span (whole workgroup)
     const int b0 = tile * kMaxBatchTile;
-    const int nb = min(NB, pr.batch - b0);
+    const int nb = NB > 1 ? min(NB, pr.batch - b0) : 1;
     const uint32_t block_row0 = (wg * RB + rb) * 16;
     const uint32_t last_row = pr.m - 1;
 
@@ -325,7 +331,7 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB, false>(pr, lds, ks, rb, wave, lane, off, P, pr.scales[P]);
+        acc = sweep<P, NB, false>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P]);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs
         int p_mine = 0, p_hi = 0;
@@ -339,10 +345,10 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
         const unsigned char *sbase = pr.scales[p_mine > 0 ? p_mine : p_hi];
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
-        case 2: acc = sweep<2, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
-        case 3: acc = sweep<3, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
-        case 4: acc = sweep<4, NB, true>(pr, lds, ks, rb, wave, lane, off, p_mine, sbase); break;
+        case 1: acc = sweep<1, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
+        case 2: acc = sweep<2, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
+        case 3: acc = sweep<3, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
+        case 4: acc = sweep<4, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }
@@ -456,7 +462,7 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.ntiles = (uint32_t)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile);
     pr.nwg_rows = (uint32_t)((row_blocks + pl.RB - 1) / pl.RB);
     // ids are grouped in spans of 8 row-block groups x ntiles; the last span may be partly empty
-    dim3 grid((pr.nwg_rows + 7) / 8 * 8 * pr.ntiles);
+    dim3 grid(pl.NB == 1 ? pr.nwg_rows : (pr.nwg_rows + 7) / 8 * 8 * pr.ntiles);
     pr.inv_span = 1.0f / (float)(8 * pr.ntiles);
     pr.inv_ks = 1.0f / (float)pl.KS;
     dim3 block(64 * pl.KS * pl.RB);

@@ -364,7 +364,18 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     }
 }
 
-constexpr size_t kLdsBudget = 128 * 1024;     // of the 160 KiB per CU
+// LDS a workgroup may ask for (160 KiB on gfx950), asked of the runtime once
+size_t lds_budget()
+{
+    static const size_t budget = [] {
+        int dev = 0, bytes = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || bytes <= 0)
+            return (size_t)64 * 1024;
+        return (size_t)bytes;
+    }();
+    return budget;
+}
 
 int lds_total(int NB, int KS, int RB)
 {
@@ -382,20 +393,21 @@ Plan make_plan(const GemmArgs &a)
     Plan pl;
     pl.NB = a.batch == 1 ? 1 : a.batch == 2 ? 2 : 4;
     int ks_cap = 16;
-    while (ks_cap > 1 && (size_t)lds_total(pl.NB, ks_cap, 1) > kLdsBudget) --ks_cap;
+    while (ks_cap > 1 && (size_t)lds_total(pl.NB, ks_cap, 1) > lds_budget()) --ks_cap;
     int KS = 1;
     for (int d = 1; d <= ks_cap && d <= nslices; ++d)
         if (nslices % d == 0) KS = d;
     if (KS < ks_cap / 2 && nslices > ks_cap) KS = ks_cap;   // awkward factorisation: ragged last chunk instead
     pl.KS = KS;
     pl.nchunk = (nslices + KS - 1) / KS;
-    // One request per tile: small workgroups (one row block) start and finish at different times,
-    // which keeps loads of some overlapping the arithmetic of others.  Several requests per tile:
-    // the operand image grows with the request count, so as many row blocks share it as requests
-    // (up to 16 waves), which keeps LDS per wave constant and the CUs fully occupied.
+    // A workgroup is one row block: every wave builds its own slice of the operand image and no wave
+    // waits for another before the final combine.  Only when a short matrix meets several batch tiles
+    // do row blocks share a workgroup and its image (up to 16 waves): that halves or quarters the
+    // conversion work of a tile, at the price of workgroup barriers.
     pl.RB = 1;
     const int64_t row_blocks = (a.m + 15) / 16;
-    while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= 16 && row_blocks / (pl.RB * 2) >= 128) pl.RB *= 2;
+    if (a.batch > kMaxBatchTile && row_blocks < 512)
+        while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= 16 && row_blocks / (pl.RB * 2) >= 128) pl.RB *= 2;
     pl.lds_bytes = (size_t)lds_total(pl.NB, KS, pl.RB);
     return pl;
 }

@@ -53,6 +53,7 @@ struct PlaneMfmaParams {
     _Float16 *y;
     const unsigned char *scales[BCQ_MAX_PLANES + 1];   // scale set per precision (bytes)
     const int32_t *p_req;                   // per-request precisions (mixed) or nullptr
+    uint32_t set_mask;                      // bit k set: scales[k] is there (k = 1 .. 4)
     uint32_t plane_stride;                  // bytes between planes:      m * n / 8
     uint32_t row_stride;                    // bytes between plane rows:  n / 8
     uint32_t scale_plane_stride;            // bytes between scale planes: m * (n/128) * 2
@@ -272,8 +273,12 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
     return acc;
 }
 
+// Waves per workgroup.  Four requests of mixed precision per tile need more registers than a 16-wave
+// workgroup leaves a wave (128), and their operand image limits the waves per CU anyway: they stop at 8.
+__host__ __device__ constexpr int max_waves(int NB, bool mixed) { return NB == 4 && mixed ? 8 : 16; }
+
 template <int P, int NB, bool MIXED>
-__global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
+__global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(PlaneMfmaParams pr)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -286,21 +291,17 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     int RB = 1, ks = wave, rb = 0;            // K slice of this wave inside a chunk, row block inside the workgroup
     uint32_t tile = 0, wg = blockIdx.x;
     if constexpr (NB > 1) {
+        // all of this without branches, so that every kernel argument is fetched in one go
         RB = pr.RB;
-        if (RB > 1) {
-            rb = (int)(((float)wave + 0.5f) * pr.inv_ks);           // wave / KS for wave < 16
-            ks = wave - rb * KS;
-        }
+        rb = (int)(((float)wave + 0.5f) * pr.inv_ks);               // wave / KS for wave < 16 (0 when RB == 1)
+        ks = wave - rb * KS;
         // Workgroup id -> (row-block group, batch tile).  Ids that differ by 8 run on the same XCD (ids
         // are dealt round-robin to the 8 XCDs), so the tiles of one row-block group are placed 8 apart:
         // they start close in time on one XCD and all but the first find the planes in that XCD's L2.
-        const uint32_t ntiles = pr.ntiles;
-        if (ntiles > 1) {
-            const uint32_t span_index = (uint32_t)(((float)blockIdx.x + 0.5f) * pr.inv_span);   // id / (8 * ntiles), ids < 2^21
-            const uint32_t rem = blockIdx.x - span_index * 8 * ntiles;
-            tile = rem >> 3;
-            wg = span_index * 8 + (rem & 7);                        // row-block group of this workgroup
-        }
+        const uint32_t span_index = (uint32_t)(((float)blockIdx.x + 0.5f) * pr.inv_span);   // id / (8 * ntiles), ids < 2^21
+        const uint32_t rem = blockIdx.x - span_index * 8 * pr.ntiles;
+        tile = rem >> 3;
+        wg = span_index * 8 + (rem & 7);                            // row-block group of this workgroup
         if (wg >= pr.nwg_rows) return;                              // padding of the last span (whole workgroup)
     }
     const int b0 = tile * kMaxBatchTile;
@@ -333,16 +334,24 @@ __global__ __launch_bounds__(1024) void plane_mfma_kernel(PlaneMfmaParams pr)
     if constexpr (!MIXED) {
         acc = sweep<P, NB, false>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P]);
     } else {
-        // precision of the request this lane reports on, and the deepest plane any request of the tile needs
+        // precision of the request this lane reports on, and the deepest plane any request of the tile needs.
+        // The four precisions of the tile are fetched together, and scale sets are picked by comparison
+        // rather than by indexing memory, to keep the chain of dependent loads ahead of the sweep short.
         int p_mine = 0, p_hi = 0;
-        for (int b = 0; b < nb; ++b) {
-            int pb = pr.p_req[b0 + b];
-            pb = pb < 1 ? 1 : (pb > pr.p_max ? pr.p_max : pb);
-            if (!pr.scales[pb]) pb = 0;        // no scale set for that precision: the request yields zeros
+        int pq[kMaxBatchTile];
+#pragma unroll
+        for (int b = 0; b < kMaxBatchTile; ++b) pq[b] = pr.p_req[b0 + min(b, nb - 1)];
+        const unsigned char *const set1 = pr.scales[1], *const set2 = pr.scales[2], *const set3 = pr.scales[3], *const set4 = pr.scales[4];
+        const uint32_t have = pr.set_mask;     // bit k: a scale set of precision k was passed
+        auto pick = [&](int k) { return k == 1 ? set1 : k == 2 ? set2 : k == 3 ? set3 : set4; };
+#pragma unroll
+        for (int b = 0; b < kMaxBatchTile; ++b) {
+            int pb = pq[b] < 1 ? 1 : (pq[b] > pr.p_max ? pr.p_max : pq[b]);
+            if (!((have >> pb) & 1) || b >= nb) pb = 0;             // no such scale set: zeros; absent slot: nothing
             p_hi = max(p_hi, pb);
             if (b == q) p_mine = pb;
         }
-        const unsigned char *sbase = pr.scales[p_mine > 0 ? p_mine : p_hi];
+        const unsigned char *sbase = pick(p_mine > 0 ? p_mine : p_hi);
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
         case 1: acc = sweep<1, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
@@ -392,7 +401,8 @@ Plan make_plan(const GemmArgs &a)
     const int nslices = (int)(a.n / kSliceCols);
     Plan pl;
     pl.NB = a.batch == 1 ? 1 : a.batch == 2 ? 2 : 4;
-    int ks_cap = 16;
+    const int wave_cap = max_waves(pl.NB, a.uniform_p == 0);
+    int ks_cap = wave_cap;
     while (ks_cap > 1 && (size_t)lds_total(pl.NB, ks_cap, 1) > lds_budget()) --ks_cap;
     int KS = 1;
     for (int d = 1; d <= ks_cap && d <= nslices; ++d)
@@ -402,12 +412,12 @@ Plan make_plan(const GemmArgs &a)
     pl.nchunk = (nslices + KS - 1) / KS;
     // A workgroup is one row block: every wave builds its own slice of the operand image and no wave
     // waits for another before the final combine.  Only when a short matrix meets several batch tiles
-    // do row blocks share a workgroup and its image (up to 16 waves): that halves or quarters the
+    // do row blocks share a workgroup and its image: that halves or quarters the
     // conversion work of a tile, at the price of workgroup barriers.
     pl.RB = 1;
     const int64_t row_blocks = (a.m + 15) / 16;
     if (a.batch > kMaxBatchTile && row_blocks < 512)
-        while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= 16 && row_blocks / (pl.RB * 2) >= 128) pl.RB *= 2;
+        while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= wave_cap && row_blocks / (pl.RB * 2) >= 128) pl.RB *= 2;
     pl.lds_bytes = (size_t)lds_total(pl.NB, KS, pl.RB);
     return pl;
 }
@@ -457,6 +467,8 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.y = a.y;
     for (int q = 0; q <= BCQ_MAX_PLANES; ++q) pr.scales[q] = reinterpret_cast<const unsigned char *>(a.scales[q]);
     pr.p_req = a.p_req;
+    for (int q = 1; q <= kMaxP; ++q)
+        if (a.scales[q]) pr.set_mask |= 1u << q;
     pr.plane_stride = (uint32_t)(a.m * (a.n / 8));
     pr.row_stride = (uint32_t)(a.n / 8);
     pr.scale_plane_stride = (uint32_t)(a.m * (a.n / 128) * 2);

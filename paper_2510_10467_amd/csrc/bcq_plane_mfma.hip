@@ -62,6 +62,7 @@ struct PlaneMfmaParams {
     uint32_t m;
     int batch, p_max, uniform_p;
     int KS, RB, nchunk, nslices;
+    int glast;                              // groups in the last slice (8 unless n is not a multiple of 1024)
     uint32_t ntiles, nwg_rows;              // batch tiles of four requests; row-block groups (workgroups per tile)
     float inv_span;                         // 1 / (8 * ntiles)
     float inv_ks;                           // 1 / KS
@@ -108,34 +109,55 @@ struct SliceLoads {
 
 // Lane addressing of a wave, fixed for the whole kernel.
 struct LaneOffsets {
-    uint32_t wa, wb;                        // byte offsets into a plane of the lane's two plane loads
+    uint32_t wa, wb;                        // byte offsets into a plane of the rows of the lane's two plane loads
     uint32_t s;                             // byte offset into a scale plane: row * scale_row_stride
-    uint32_t x[kMaxBatchTile];              // byte offset of the lane's image unit in each request slot's activations
+    uint32_t x[kMaxBatchTile];              // byte offset of each request slot's activations
+    uint32_t lane;
 };
+
+// 128-bit logical shift right by 16 bits: drops the first of eight binary16 values, the last becomes 0
+__device__ __forceinline__ u32x4 drop_first_half(u32x4 v)
+{
+    return u32x4{__builtin_amdgcn_alignbit(v.y, v.x, 16), __builtin_amdgcn_alignbit(v.z, v.y, 16),
+                 __builtin_amdgcn_alignbit(v.w, v.z, 16), v.w >> 16};
+}
 
 template <int PH, int NB, bool MIXED>
 __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneMfmaParams &pr, const LaneOffsets &off,
-                                            const unsigned char *sbase, int p_mine, int slice_c)
+                                            const unsigned char *sbase, int p_mine, int slice_c, int ngroups)
 {
-    // in the order of use: activations, scales, planes
+    // A last slice of ngroups < 8 groups: lanes whose columns or group lie past the end of the row fetch
+    // the slice's first unit or group instead (valid memory, finite values; the scales of those groups
+    // are zero), and the 16 bytes of scales are the LAST eight of the row, shifted into place later.
+    const uint32_t x_lane = off.lane < (uint32_t)ngroups * 8 ? off.lane * 32 : 0;
+    const uint32_t w_lane = (off.lane & 7) < (uint32_t)ngroups ? (off.lane & 7) * 16 : 0;
+    const uint32_t s_slice = ngroups < kSliceGroups ? pr.scale_row_stride - kSliceGroups * 2 : (uint32_t)slice_c * (kSliceGroups * 2);
+    // in the order of use: activations, scales, planes.  Every address is a wave-uniform 64-bit base plus
+    // a 32-bit lane offset, which is an addressing mode of the load instruction: no 64-bit lane arithmetic.
+    const unsigned char *x_base = pr.x + (uint32_t)slice_c * (kSliceCols * 2);
 #pragma unroll
     for (int bb = 0; bb < NB; ++bb) {
-        const unsigned char *xp = pr.x + off.x[bb] + (uint32_t)slice_c * (kSliceCols * 2);
-        ld.xv[bb][0] = *reinterpret_cast<const u32x4 *>(xp);
-        ld.xv[bb][1] = *reinterpret_cast<const u32x4 *>(xp + 16);
+        const uint32_t xo = off.x[bb] + x_lane;
+        ld.xv[bb][0] = *reinterpret_cast<const u32x4 *>(x_base + xo);
+        ld.xv[bb][1] = *reinterpret_cast<const u32x4 *>(x_base + xo + 16);
     }
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
-        const int ii = MIXED ? min(i, max(p_mine, 1) - 1) : i;      // stay inside the lane's own scale set
-        ld.sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + off.s +
-                                                    (uint32_t)slice_c * (kSliceGroups * 2));
+        if constexpr (MIXED) {
+            const int ii = min(i, max(p_mine, 1) - 1);              // stay inside the lane's own scale set
+            ld.sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + off.s + s_slice);
+        } else {
+            const unsigned char *s_base = sbase + (size_t)i * pr.scale_plane_stride + s_slice;
+            ld.sc[i] = *reinterpret_cast<const u32x4 *>(s_base + off.s);
+        }
     }
+    const uint32_t wa = off.wa + w_lane, wb = off.wb + w_lane;
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
         // rows 0-7, then rows 8-15 of the block: 128 contiguous bytes per row and instruction
-        const unsigned char *wp = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8);
-        ld.wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + off.wa));
-        ld.wb[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + off.wb));
+        const unsigned char *w_base = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice_c * (kSliceCols / 8);
+        ld.wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w_base + wa));
+        ld.wb[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w_base + wb));
     }
 }
 
@@ -152,14 +174,16 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
     float acc = 0.f;
     int chunk = 0;
     do {                                                            // nchunk >= 1
-        const bool slice_ok = chunk * KS + ks < pr.nslices;         // the last chunk may be ragged
+        const int slice = __builtin_amdgcn_readfirstlane(chunk * KS + ks);      // the same in all lanes of a wave
+        const bool slice_ok = slice < pr.nslices;                   // the last chunk may be ragged
         const int p_eff = slice_ok ? p_mine : 0;
+        const int ngroups = slice == pr.nslices - 1 ? pr.glast : kSliceGroups;   // so may the last slice
 
         // ---- 0. the loads go out before anything else is computed: every instruction ahead of them
         // delays the memory phase of all waves that share the SIMD.  The lane id is made opaque after
         // them so that no LDS address arithmetic is moved in front of the loop.
         SliceLoads<PH, NB> ld;
-        issue_loads<PH, NB, MIXED>(ld, pr, off, sbase, p_mine, slice_ok ? chunk * KS + ks : pr.nslices - 1);
+        issue_loads<PH, NB, MIXED>(ld, pr, off, sbase, p_mine, slice_ok ? slice : 0, ngroups);
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" : "+v"(lane));
 
@@ -218,6 +242,13 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         }
         if (RB > 1) __syncthreads();
 
+        // short last slice: its scales are the last ngroups of the eight fetched; the rest become zero
+        if (ngroups < kSliceGroups) {
+            for (int k = ngroups; k < kSliceGroups; ++k) {
+#pragma unroll
+                for (int i = 0; i < PH; ++i) ld.sc[i] = drop_first_half(ld.sc[i]);
+            }
+        }
         // scales of planes this lane must not use (beyond its precision, or a slice past the end) become zero
         if (MIXED || !slice_ok) {
 #pragma unroll
@@ -311,11 +342,12 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
 
     // rows and row strides are below 2^24 (checked on the host): full-rate 24-bit multiplies
     LaneOffsets off;
-    // plane loads: lane (l >> 3, l & 7) takes group l & 7 (16 bytes) of block rows l >> 3 and 8 + (l >> 3).
-    // Rows past the end repeat the last row.
-    const uint32_t r8 = lane >> 3, c8 = lane & 7;
-    off.wa = __umul24(min(block_row0 + r8, last_row), pr.row_stride) + c8 * 16;
-    off.wb = __umul24(min(block_row0 + 8 + r8, last_row), pr.row_stride) + c8 * 16;
+    // plane loads: lane (l >> 3, l & 7) takes group l & 7 (16 bytes) of block rows l >> 3 and 8 + (l >> 3);
+    // the group part is added per slice.  Rows past the end repeat the last row.
+    const uint32_t r8 = lane >> 3;
+    off.wa = __umul24(min(block_row0 + r8, last_row), pr.row_stride);
+    off.wb = __umul24(min(block_row0 + 8 + r8, last_row), pr.row_stride);
+    off.lane = lane;
     // output side: lane (q, r16) reports row r16 of the block for request slot q
     const int q = lane >> 4;
     uint32_t row = block_row0 + (lane & 15);
@@ -327,7 +359,7 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
 #pragma unroll
     for (int bb = 0; bb < NB; ++bb) {
         const int b = rb + bb * RB;
-        off.x[bb] = (uint32_t)(b0 + (b < nb ? b : 0)) * pr.x_stride + lane * 32;
+        off.x[bb] = (uint32_t)(b0 + (b < nb ? b : 0)) * pr.x_stride;
     }
 
     float acc = 0.f;
@@ -398,7 +430,7 @@ struct Plan {
 
 Plan make_plan(const GemmArgs &a)
 {
-    const int nslices = (int)(a.n / kSliceCols);
+    const int nslices = (int)((a.n + kSliceCols - 1) / kSliceCols);
     Plan pl;
     pl.NB = a.batch == 1 ? 1 : a.batch == 2 ? 2 : 4;
     const int wave_cap = max_waves(pl.NB, a.uniform_p == 0);
@@ -454,7 +486,9 @@ bool plane_mfma_supports(const GemmArgs &a)
     // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
     const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31) &&
                               a.m < (int64_t(1) << 24) && a.n < (int64_t(1) << 24);
-    return a.group == 128 && (a.n % kSliceCols) == 0 && a.p_max <= kMaxP && small_enough &&
+    // whole scale groups, 4-byte aligned scale rows, and at least eight groups per row (the scales of a
+    // short last slice are fetched as the last eight of the row)
+    return a.group == 128 && (a.n % 256) == 0 && a.n >= kSliceCols && a.p_max <= kMaxP && small_enough &&
            ((a.m + 15) / 16 + 8) * ((a.batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);
 }
 
@@ -481,7 +515,8 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.KS = pl.KS;
     pr.RB = pl.RB;
     pr.nchunk = pl.nchunk;
-    pr.nslices = (int)(a.n / kSliceCols);
+    pr.nslices = (int)((a.n + kSliceCols - 1) / kSliceCols);
+    pr.glast = (int)((a.n / 128 - 1) % kSliceGroups) + 1;
     const int64_t row_blocks = (a.m + 15) / 16;
     pr.ntiles = (uint32_t)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile);
     pr.nwg_rows = (uint32_t)((row_blocks + pl.RB - 1) / pl.RB);

@@ -65,8 +65,10 @@ def test_sign_select_mixed(gpu, m, n, group):
 
 
 PLANE_MFMA_SHAPES = [
-    # m, n: one and several K slices of 1024 columns, ragged row tails, chunked K (n = 28672)
+    # m, n: one and several K slices of 1024 columns, ragged row tails, chunked K (n = 28672),
+    # short last slices of 2, 6, 1+... groups (n a multiple of 256 but not of 1024; 17920 is the Phi-4 width)
     (16, 1024), (37, 2048), (131, 4096), (40, 5120), (75, 14336), (50, 28672), (1, 1024), (530, 3072),
+    (37, 1280), (33, 1792), (16, 2304), (20, 17920), (17, 3840),
 ]
 
 
@@ -81,7 +83,7 @@ def test_plane_mfma_uniform(gpu, m, n):
             assert used == "plane_mfma"
 
 
-@pytest.mark.parametrize("m,n", [(37, 2048), (131, 4096), (75, 14336)])
+@pytest.mark.parametrize("m,n", [(37, 2048), (131, 4096), (75, 14336), (37, 1280), (20, 17920)])
 def test_plane_mfma_mixed(gpu, m, n):
     layer = syn.make_layer(m, n, seed=(140, m), signed=True)
     dl = gpu.DeviceLayer(layer)
@@ -104,7 +106,7 @@ def test_dequant_mfma_uniform(gpu, m, n):
 
 def test_forced_variant_that_cannot_run_is_an_error(gpu):
     import paper_2510_10467_amd as bcq
-    layer = syn.make_layer(16, 640, seed=(160, 0))            # n is not a multiple of 1024
+    layer = syn.make_layer(16, 640, seed=(160, 0))            # n is shorter than one K slice
     dl = gpu.DeviceLayer(layer)
     x = gpu.to_dev(syn.make_x(1, 640, seed=(160, 0)))
     bcq.select_kernel("plane_mfma")

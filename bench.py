@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a reference kernel of known traffic for counter runs)")
-    ap.add_argument("--suite", choices=["decode", "mixed", "large"], default=None,
+    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused"], default=None,
                     help="instead of the headline workload, time another workload family and print its table")
     return ap.parse_args()
 
@@ -150,6 +150,14 @@ def run_suite(args, torch, bcq, syn, dev):
             bench_shape(m, n, (1, 2, 4, 8, 16, 32), PRECISIONS)
     elif args.suite == "mixed":
         bench_shape(14336, 4096, (16,), PRECISIONS, mixed=True)
+    elif args.suite == "phi4":
+        # second model of the paper's GEMV table; 17920 columns end in a half slice
+        for (_, m, n) in syn.PHI4_14B_SHAPES:
+            bench_shape(m, n, (1,), PRECISIONS)
+    elif args.suite == "fused":
+        # q/k/v and gate/up stored as one matrix each (they share x): 4 launches per decoder layer instead of 7
+        for (m, n) in ((4096 + 1024 + 1024, 4096), (4096, 4096), (2 * 14336, 4096), (4096, 14336)):
+            bench_shape(m, n, (1,), PRECISIONS)
     else:
         for (_, m, n) in syn.LLAMA3_70B_SHAPES:
             bench_shape(m, n, (1, 16, 64, 256), PRECISIONS)

@@ -27,11 +27,12 @@ int run(const bcq::GemmArgs &a, hipStream_t stream)
     hipError_t err;
     int choice = g_forced;
     if (choice == BCQ_KERNEL_AUTO) {
-        // Dequantising a weight tile costs the same whatever the number of requests that then use it, so it
-        // pays only from about 64 requests on, and only when there are enough (64 rows x 64 requests) tiles to
-        // occupy the chip; below that the plane-wise kernel wins (measured on Llama-3-8B and 70B shapes).
-        const int64_t tiles = ((a.m + 63) / 64) * ((a.batch + 63) / 64);
-        if (dequant_mfma_supports(a) && a.batch >= 64 && tiles >= 192) choice = BCQ_KERNEL_DEQUANT_MFMA;
+        // Dequantising a weight tile costs the same whatever the number of requests that then use it, and a
+        // workgroup takes 64 rows: the kernel pays from about 24 requests on when the rows fill the chip
+        // (m >= 8192), from about 96 when they fill a quarter of it, and not at all on shorter matrices; below
+        // that the plane-wise kernel wins (measured on Llama-3-8B and 70B shapes, p = 2 and 4).
+        const bool pays = (a.m >= 8192 && a.batch >= 24) || (a.m >= 4096 && a.batch >= 96);
+        if (dequant_mfma_supports(a) && pays) choice = BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         else choice = BCQ_KERNEL_SIGN_SELECT;
     }

@@ -4,16 +4,28 @@
 // is no longer bound by HBM but by arithmetic, and one dense fp16 MFMA over dequantised weights
 // costs p times fewer matrix instructions than p plane-wise products.
 //
-// A workgroup of four waves owns 64 weight rows and a block of 64 requests.  Per group of 128
-// columns the workgroup stages the 64 x 128 activation tile in LDS; every lane fetches the 16 bytes
-// of its own row's group from each plane plus the group's scales, and for each 32-column step
-//   * takes ONE byte of each plane word (lane quarter kq owns columns 8kq .. 8kq+7 of the step),
-//   * looks the byte up in a 256-entry LDS table of eight +-1.0 binary16 values,
-//   * accumulates w_j = sum_i alpha_i * (+-1) in fp32 (one mixed-precision FMA per column and
-//     plane), rounds once to binary16,
-// and issues v_mfma_f32_16x16x32_f16 for the four 16-request column blocks, accumulating in fp32.
-// The MFMA's M side carries requests, its N side the 16 weight rows of the wave, so a lane ends up
-// with four requests of its own row.
+// A workgroup of four waves owns 64 weight rows (16 per wave) and TB = 64, 128 or 256 requests.  Per
+// group of 128 columns
+//   * the workgroup stages the TB x 128 activation tile in LDS (fetched one group ahead with fully
+//     coalesced loads into registers, stored into the tile the previous group has just left);
+//   * lane (row, kq) of a wave holds word kq of its row's group from each plane plus the group's
+//     scales (also one group ahead).  Matrix step t covers the columns 32 kq + 8 t + j of the group
+//     (a permutation of K that the activation operand follows), so for each step the lane takes
+//     byte t of each plane word, looks it up in a 256-entry LDS table of eight +-1.0 binary16
+//     values, accumulates w_j = sum_i alpha_i * (+-1) in fp32 (one mixed-precision FMA per column
+//     and plane) and rounds once to binary16: that IS the B operand of v_mfma_f32_16x16x32_f16;
+//   * the wave multiplies its 16 x 128 weight tile with all TB requests, reading each activation
+//     operand (16 requests x 32 columns) from LDS.
+// A weight is therefore dequantised once per TB requests and never leaves the registers; the
+// activations are read from HBM/L2 once per workgroup.  The MFMA's M side carries requests, its N
+// side the 16 weight rows of the wave, so a lane ends up with four requests of its own row per
+// accumulator.  One barrier per group.
+//
+// A wave cannot overlap its own vector, matrix and LDS instructions, and with one wave per SIMD every
+// latency is exposed.  So, LDS and registers permitting (TB <= 128), a workgroup has TWO such teams of
+// four waves: both work on the same rows and requests, team k on the groups k, k+2, k+4, ... with
+// activation tiles and accumulators of its own; the teams meet at every barrier and add their
+// accumulators through LDS at the end.
 #include <hip/hip_runtime.h>
 
 #include "bcq_internal.hpp"
@@ -26,30 +38,49 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRowsPerWg = 64;              // 4 waves x 16 rows
-constexpr int kReqPerWg = 64;               // 4 MFMA column blocks of 16 requests
 constexpr int kMaxP = 4;
-constexpr int kXRowBytes = 128 * 2 + 16;    // padded LDS row of one request's 128 activations
 constexpr int kLutBytes = 256 * 16;
-constexpr int kXTileBytes = kReqPerWg * kXRowBytes;
+constexpr int kXRowBytes = 128 * 2 + 16;    // padded LDS row of one request's 128 activations: rows start 4 banks apart
 
-template <int P>
-__global__ __launch_bounds__(256) void dequant_mfma_kernel(GemmArgs a)
+constexpr int x_tile_bytes(int nu) { return 64 * nu * kXRowBytes; }
+constexpr int lds_bytes(int nu, int teams) { return kLutBytes + teams * 2 * x_tile_bytes(nu); }
+
+struct DequantParams {
+    const unsigned char *planes;            // plane 0
+    const unsigned char *scales;            // scale set of the precision
+    const unsigned char *x;
+    _Float16 *y;
+    uint32_t plane_stride;                  // bytes between planes:        m * n / 8
+    uint32_t row_stride;                    // bytes between plane rows:    n / 8
+    uint32_t scale_plane_stride;            // bytes between scale planes:  m * (n/128) * 2
+    uint32_t scale_row_stride;              // bytes between scale rows:    (n/128) * 2
+    uint32_t x_stride;                      // bytes between requests:      n * 2
+    uint32_t m;
+    int batch, ngroups;
+};
+
+// What a thread fetches ahead: plane words and scales of its row for one group, and its share of the
+// activation tile of the group after (4 * NU units of 16 bytes).
+template <int P, int NU>
+struct Ahead {
+    uint32_t w[P];
+    _Float16 alpha[P];
+    u32x4 xs[4 * NU];
+};
+
+template <int P, int NU, int TEAMS>
+__global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams a)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kLutBytes + 2 * kXTileBytes];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     unsigned char *lut = lds;
-    unsigned char *xt0 = lds + kLutBytes;       // two activation tiles, used alternately
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255, team = threadIdx.x >> 8;
     const int lane = tid & 63, wave = tid >> 6;
-    const int n16 = lane & 15;                // weight row inside the wave's block / request inside a column block
-    const int kq = lane >> 4;                 // K quarter: columns 8kq .. 8kq+7 of each 32-column step
-    const int ngroups = (int)(a.n >> 7);
-    const int words = (int)(a.n >> 5);
-    const int b0 = blockIdx.y * kReqPerWg;
-
-    int64_t row = (int64_t)blockIdx.x * kRowsPerWg + wave * 16 + n16;
-    const bool row_ok = row < a.m;
-    if (!row_ok) row = a.m - 1;
+    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NU);     // the team's two activation tiles, used alternately
+    const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
+    const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
+    const uint32_t row0 = blockIdx.x * kRowsPerWg + wave * 16;
+    const int b0 = blockIdx.y * (64 * NU);    // first request of the workgroup
 
     // table: byte -> eight binary16 values, +1.0 where the bit is set, -1.0 where it is clear
     {
@@ -60,40 +91,78 @@ __global__ __launch_bounds__(256) void dequant_mfma_kernel(GemmArgs a)
             const uint32_t hi = ((tid >> (2 * c + 1)) & 1) ? 0x3C00u : 0xBC00u;
             e[c] = lo | (hi << 16);
         }
-        *reinterpret_cast<u32x4 *>(lut + tid * 16) = u32x4{e[0], e[1], e[2], e[3]};
+        if (team == 0) *reinterpret_cast<u32x4 *>(lut + tid * 16) = u32x4{e[0], e[1], e[2], e[3]};
     }
 
-    const _Float16 *scales = a.scales[a.uniform_p];
-    v4f acc[4];
+    // lane offsets; rows and requests past the end repeat the last one (their results are not stored)
+    // Plane words and scales are fetched with four adjacent lanes on one row (lane l: row l >> 2, word
+    // l & 3), which the memory pipe combines into one request per row, and then handed to the lane
+    // that uses them (row l & 15, word l >> 4) by a lane permute.
+    const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
+    const uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
+    const uint32_t s_lane = frow * a.scale_row_stride;
+    const int pull = (4 * n16 + kq) * 4;      // byte index of the lane to take from
+    // staging: unit tid + 256k of the tile = request (unit >> 4), 16-byte part (unit & 15) of its 256 bytes
+    uint32_t xs_src[4 * NU], xs_dst[4 * NU];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < 4 * NU; ++k) {
+        const int unit = tid + 256 * k;
+        const int req = unit >> 4, part = unit & 15;
+        xs_src[k] = (uint32_t)min(b0 + req, a.batch - 1) * a.x_stride + part * 16;
+        xs_dst[k] = req * kXRowBytes + part * 16;
+    }
+    // A operand of request tile u, step t: 16 bytes at (16u + n16) * kXRowBytes + (32kq + 8t) * 2
+    const unsigned char *xa_lane = xt0 + n16 * kXRowBytes + kq * 64;
 
-    // staging assignment: thread t copies 16-byte units t, t+256, t+512, t+768 of the 64 x 256-byte tile
-    auto stage_tile = [&](int g, unsigned char *dst) {
+    auto fetch_w = [&](Ahead<P, NU> &ah, int g) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int unit = tid + 256 * k;
-            const int req = unit >> 4, part = unit & 15;            // 16 units per request row
-            const int b = b0 + req;
-            u32x4 v = u32x4{0, 0, 0, 0};
-            if (b < a.batch) v = *reinterpret_cast<const u32x4 *>(a.x + (int64_t)b * a.n + (int64_t)g * 128 + part * 8);
-            *reinterpret_cast<u32x4 *>(dst + req * kXRowBytes + part * 16) = v;
+        for (int i = 0; i < P; ++i) {
+            // wave-uniform 64-bit base plus 32-bit lane offset: an addressing mode of the load instruction
+            const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
+            ah.w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(w_base + w_lane));
+            const unsigned char *s_base = a.scales + (size_t)i * a.scale_plane_stride + (uint32_t)g * 2;
+            ah.alpha[i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
         }
     };
+    auto fetch_x = [&](Ahead<P, NU> &ah, int g) {
+        const unsigned char *x_base = a.x + (uint32_t)g * 256;
+#pragma unroll
+        for (int k = 0; k < 4 * NU; ++k) ah.xs[k] = *reinterpret_cast<const u32x4 *>(x_base + xs_src[k]);
+    };
+    auto store_x = [&](const Ahead<P, NU> &ah, int buf) {
+#pragma unroll
+        for (int k = 0; k < 4 * NU; ++k) *reinterpret_cast<u32x4 *>(xt0 + buf * x_tile_bytes(NU) + xs_dst[k]) = ah.xs[k];
+    };
 
-    stage_tile(0, xt0);
-    __syncthreads();
-    for (int g = 0; g < ngroups; ++g) {
-        // this lane's row: one group of every plane and its scales
-        u32x4 w[P];
+    v4f acc[4 * NU];
+#pragma unroll
+    for (int u = 0; u < 4 * NU; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // Group g, the team's next being g + TEAMS.  On entry `cur` holds the plane words and scales of group g
+    // and the activation tile of the next group; the team's LDS tile `buf` holds the activations of group g.
+    // Every wave of the workgroup passes the barrier of every step, with or without a group of its own.
+    auto step = [&](Ahead<P, NU> &cur, Ahead<P, NU> &nxt, int g, int buf) {
+        if (g < a.ngroups) {
+        // Everything fetched ahead is claimed here, while it is all that is outstanding: the wait is
+        // then exact.  (Claimed after the next loads have been issued, it would cover those too.)
+#pragma unroll
+        for (int i = 0; i < P; ++i) asm volatile("" : "+v"(cur.w[i]), "+v"(cur.alpha[i]));
+#pragma unroll
+        for (int k = 0; k < 4 * NU; ++k) asm volatile("" : "+v"(cur.xs[k]));
+        uint32_t w[P];
         float alpha[P];
 #pragma unroll
         for (int i = 0; i < P; ++i) {
-            w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.planes + ((int64_t)i * a.m + row) * words + g * 4));
-            alpha[i] = (float)scales[((int64_t)i * a.m + row) * ngroups + g];
+            w[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)cur.w[i]);
+            const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.alpha[i]));
+            alpha[i] = (float)__builtin_bit_cast(_Float16, (unsigned short)ab);
         }
-        if (g + 1 < ngroups) stage_tile(g + 1, xt0 + ((g + 1) & 1) * kXTileBytes);    // next tile into the other buffer
-        const unsigned char *xcur = xt0 + (g & 1) * kXTileBytes;
+        if (g + TEAMS < a.ngroups) {
+            store_x(cur, buf ^ 1);              // that tile was last read before the previous barrier
+            fetch_w(nxt, g + TEAMS);
+            if (g + 2 * TEAMS < a.ngroups) fetch_x(nxt, g + 2 * TEAMS);
+        }
+        const unsigned char *xa_cur = xa_lane + buf * x_tile_bytes(NU);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             float wf[8];
@@ -101,7 +170,7 @@ __global__ __launch_bounds__(256) void dequant_mfma_kernel(GemmArgs a)
             for (int j = 0; j < 8; ++j) wf[j] = 0.f;
 #pragma unroll
             for (int i = 0; i < P; ++i) {
-                const uint32_t byte = (w[i][t] >> (8 * kq)) & 0xffu;
+                const uint32_t byte = (w[i] >> (8 * t)) & 0xffu;
                 const v8h pm = *reinterpret_cast<const v8h *>(lut + byte * 16);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) wf[j] = fmaf((float)pm[j], alpha[i], wf[j]);
@@ -110,23 +179,80 @@ __global__ __launch_bounds__(256) void dequant_mfma_kernel(GemmArgs a)
 #pragma unroll
             for (int j = 0; j < 8; ++j) wb[j] = (_Float16)wf[j];    // the single rounding of W_p to binary16
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const v8h xa = *reinterpret_cast<const v8h *>(xcur + (16 * u + n16) * kXRowBytes + (32 * t + 8 * kq) * 2);
+            for (int u = 0; u < 4 * NU; ++u) {
+                const v8h xa = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + t * 16);
                 acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, wb, acc[u], 0, 0, 0);
             }
         }
-        __syncthreads();                                            // next tile complete, current tile free
+        }
+        __syncthreads();                        // tile `buf` free, the other tile complete
+    };
+
+    Ahead<P, NU> ah0, ah1;
+    if (team < a.ngroups) {
+        fetch_x(ah0, team);
+        store_x(ah0, 0);
+        fetch_w(ah0, team);
+        if (team + TEAMS < a.ngroups) fetch_x(ah0, team + TEAMS);
+    }
+    __syncthreads();                            // table and first tiles complete
+    const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
+    for (int it = 0; it < npairs; ++it) {
+        const int g = 2 * it * TEAMS + team;
+        step(ah0, ah1, g, 0);
+        step(ah1, ah0, g + TEAMS, 1);
     }
 
-    // lane holds requests 16u + 4kq + i (i = 0..3) of weight row `row`
-    if (row_ok) {
+    if constexpr (TEAMS == 2) {
+        // the second team hands its accumulators over through the (now free) activation tiles
+        v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
+        if (team == 1) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 4 * NU; ++u) xchg[(wave * 4 * NU + u) * 64 + lane] = acc[u];
+        }
+        __syncthreads();
+        if (team == 1) return;
+#pragma unroll
+        for (int u = 0; u < 4 * NU; ++u) acc[u] += xchg[(wave * 4 * NU + u) * 64 + lane];
+    }
+
+    // accumulator u, register i: request b0 + 16u + 4kq + i of row row0 + n16
+    const uint32_t row = row0 + n16;
+    if (row < a.m) {
+#pragma unroll
+        for (int u = 0; u < 4 * NU; ++u)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int b = b0 + 16 * u + 4 * kq + i;
-                if (b < a.batch) a.y[(int64_t)b * a.m + row] = (_Float16)acc[u][i];
+                if (b < a.batch) a.y[(size_t)b * a.m + row] = (_Float16)acc[u][i];
             }
+    }
+}
+
+template <int P, int NU, int TEAMS>
+hipError_t launch_one(const DequantParams &pr, dim3 grid, hipStream_t stream)
+{
+    auto kernel = dequant_mfma_kernel<P, NU, TEAMS>;
+    if (lds_bytes(NU, TEAMS) > 64 * 1024) {
+        // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           lds_bytes(NU, TEAMS));
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(256 * TEAMS), lds_bytes(NU, TEAMS), stream, pr);
+    return hipGetLastError();
+}
+
+template <int P>
+hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
+{
+    // requests per workgroup: 64, 128 or 256; the last leaves neither LDS nor registers for two teams
+    const int nu = a.batch <= 64 ? 1 : a.batch <= 128 ? 2 : 4;
+    dim3 grid((unsigned)((a.m + kRowsPerWg - 1) / kRowsPerWg), (unsigned)((a.batch + 64 * nu - 1) / (64 * nu)));
+    switch (nu) {
+    case 1: return launch_one<P, 1, 2>(pr, grid, stream);
+    case 2: return launch_one<P, 2, 2>(pr, grid, stream);
+    default: return launch_one<P, 4, 1>(pr, grid, stream);
     }
 }
 
@@ -134,21 +260,33 @@ __global__ __launch_bounds__(256) void dequant_mfma_kernel(GemmArgs a)
 
 bool dequant_mfma_supports(const GemmArgs &a)
 {
-    return a.uniform_p >= 1 && a.uniform_p <= kMaxP && a.group == 128 &&
-           (a.batch + kReqPerWg - 1) / kReqPerWg <= 65535 && (a.m + kRowsPerWg - 1) / kRowsPerWg < (int64_t(1) << 31);
+    // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
+    const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31);
+    return a.uniform_p >= 1 && a.uniform_p <= kMaxP && a.group == 128 && small_enough &&
+           (a.batch + 63) / 64 <= 65535 && (a.m + kRowsPerWg - 1) / kRowsPerWg < (int64_t(1) << 31);
 }
 
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
 {
-    dim3 grid((unsigned)((a.m + kRowsPerWg - 1) / kRowsPerWg), (unsigned)((a.batch + kReqPerWg - 1) / kReqPerWg));
-    dim3 block(256);
+    DequantParams pr{};
+    pr.planes = reinterpret_cast<const unsigned char *>(a.planes);
+    pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);
+    pr.x = reinterpret_cast<const unsigned char *>(a.x);
+    pr.y = a.y;
+    pr.plane_stride = (uint32_t)(a.m * (a.n / 8));
+    pr.row_stride = (uint32_t)(a.n / 8);
+    pr.scale_plane_stride = (uint32_t)(a.m * (a.n / 128) * 2);
+    pr.scale_row_stride = (uint32_t)((a.n / 128) * 2);
+    pr.x_stride = (uint32_t)(a.n * 2);
+    pr.m = (uint32_t)a.m;
+    pr.batch = a.batch;
+    pr.ngroups = (int)(a.n / 128);
     switch (a.uniform_p) {
-    case 1: hipLaunchKernelGGL(dequant_mfma_kernel<1>, grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL(dequant_mfma_kernel<2>, grid, block, 0, stream, a); break;
-    case 3: hipLaunchKernelGGL(dequant_mfma_kernel<3>, grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL(dequant_mfma_kernel<4>, grid, block, 0, stream, a); break;
+    case 1: return launch_p<1>(pr, a, stream);
+    case 2: return launch_p<2>(pr, a, stream);
+    case 3: return launch_p<3>(pr, a, stream);
+    default: return launch_p<4>(pr, a, stream);
     }
-    return hipGetLastError();
 }
 
 }  // namespace bcq

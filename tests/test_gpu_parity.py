@@ -128,9 +128,11 @@ def test_auto_dispatch_by_batch(gpu):
     used, _ = gpu.check_gemv(dl, 3, syn.make_x(16, 2048, seed=(170, 2)), "auto")
     assert used == "plane_mfma"
     used, _ = gpu.check_gemv(dl, 3, syn.make_x(128, 2048, seed=(170, 3)), "auto")
-    assert used == "plane_mfma"            # too few 64 x 64 tiles for the dequantising kernel to pay
-    big = gpu.DeviceLayer(syn.make_layer(2048, 1024, seed=(171, 0)))
-    used, _ = gpu.check_gemv(big, 3, syn.make_x(384, 1024, seed=(171, 1)), "auto")
+    assert used == "plane_mfma"            # too few rows for the dequantising kernel to pay
+    big = gpu.DeviceLayer(syn.make_layer(4096, 1024, seed=(171, 0)))
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(64, 1024, seed=(171, 1)), "auto")
+    assert used == "plane_mfma"
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(100, 1024, seed=(171, 2)), "auto")
     assert used == "dequant_mfma"
     p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
     used, _ = gpu.check_mixed(dl, p_req, syn.make_x(40, 2048, seed=(170, 4)), "auto")

@@ -74,8 +74,10 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     unsigned char *lut = lds;
 
-    const int tid = threadIdx.x & 255, team = threadIdx.x >> 8;
-    const int lane = tid & 63, wave = tid >> 6;
+    // team and wave are the same in all lanes of a wave: telling the compiler keeps group indices and
+    // base addresses in scalar registers
+    const int tid = threadIdx.x & 255, team = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NU);     // the team's two activation tiles, used alternately
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t

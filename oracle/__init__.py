@@ -46,10 +46,14 @@ def _load():
         lib.bcq_oracle_dequant.argtypes = [vp, vp, i32, i64, i64, i64, vp]
         lib.bcq_oracle_gemv.argtypes = [vp, vp, i32, vp, vp, vp, i64, i64, i64, i64]
         lib.bcq_oracle_gemm_mixed.argtypes = [vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, i64]
+        lib.bcq_oracle_dequant_offset.argtypes = [vp, vp, vp, i32, i64, i64, i64, vp]
+        lib.bcq_oracle_gemv_offset.argtypes = [vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, i64]
+        lib.bcq_oracle_gemm_mixed_offset.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, i64]
         lib.bcq_oracle_num_threads.restype = i32
         lib.bcq_oracle_set_num_threads.argtypes = [i32]
         for f in (lib.bcq_oracle_pack, lib.bcq_oracle_unpack, lib.bcq_oracle_dequant,
-                  lib.bcq_oracle_gemv, lib.bcq_oracle_gemm_mixed):
+                  lib.bcq_oracle_gemv, lib.bcq_oracle_gemm_mixed, lib.bcq_oracle_dequant_offset,
+                  lib.bcq_oracle_gemv_offset, lib.bcq_oracle_gemm_mixed_offset):
             f.restype = i32
         _lib = lib
     return _lib
@@ -102,22 +106,35 @@ def unpack(planes: np.ndarray) -> np.ndarray:
     return codes
 
 
-def dequant(planes: np.ndarray, scales_p: np.ndarray, group: int = 128) -> np.ndarray:
-    """W_p as float64 [m][n]; p is ``scales_p.shape[0]`` (small shapes only)."""
+def _offset_bits(offsets, m, ngroups):
+    if offsets is None:
+        return None
+    z = _half_bits(offsets)
+    if z.shape != (m, ngroups):
+        raise ValueError(f"offset set has shape {z.shape}, expected {(m, ngroups)}")
+    return z
+
+
+def dequant(planes: np.ndarray, scales_p: np.ndarray, group: int = 128, offsets=None) -> np.ndarray:
+    """W_p as float64 [m][n]; p is ``scales_p.shape[0]`` (small shapes only).
+
+    ``offsets`` (float16 [m][n/group]) adds the asymmetric scheme's offset of every (row, group)."""
     planes = _c(planes, np.uint32)
     s = _half_bits(scales_p)
     p, m, ngroups = s.shape
     n = planes.shape[2] * 32
     if planes.shape[0] < p or planes.shape[1] != m or ngroups * group != n:
         raise ValueError("shape mismatch between planes and scales")
+    z = _offset_bits(offsets, m, ngroups)
     w = np.empty((m, n), dtype=np.float64)
-    if _load().bcq_oracle_dequant(_ptr(planes), _ptr(s), p, m, n, group, _ptr(w)) != 0:
+    zp = _ptr(z) if z is not None else None
+    if _load().bcq_oracle_dequant_offset(_ptr(planes), _ptr(s), zp, p, m, n, group, _ptr(w)) != 0:
         raise ValueError("bcq_oracle_dequant: bad argument")
     return w
 
 
-def gemv(planes: np.ndarray, scales_p: np.ndarray, x: np.ndarray, group: int = 128):
-    """Uniform precision p = ``scales_p.shape[0]``.
+def gemv(planes: np.ndarray, scales_p: np.ndarray, x: np.ndarray, group: int = 128, offsets=None):
+    """Uniform precision p = ``scales_p.shape[0]``; ``offsets`` as for :func:`dequant`.
 
     Returns ``(y, abs)`` as float64 [batch][m]: y = W_p x, abs = sum_j |W_p[r,j] x_j|.
     """
@@ -128,15 +145,18 @@ def gemv(planes: np.ndarray, scales_p: np.ndarray, x: np.ndarray, group: int = 1
     batch, n = xb.shape
     if planes.shape[0] < p or planes.shape[1] != m or planes.shape[2] * 32 != n or ngroups * group != n:
         raise ValueError("shape mismatch")
+    z = _offset_bits(offsets, m, ngroups)
+    zp = _ptr(z) if z is not None else None
     y = np.zeros((batch, m), dtype=np.float64)
     a = np.zeros((batch, m), dtype=np.float64)
-    if _load().bcq_oracle_gemv(_ptr(planes), _ptr(s), p, _ptr(xb), _ptr(y), _ptr(a), m, n, batch, group) != 0:
+    if _load().bcq_oracle_gemv_offset(_ptr(planes), _ptr(s), zp, p, _ptr(xb), _ptr(y), _ptr(a), m, n, batch, group) != 0:
         raise ValueError("bcq_oracle_gemv: bad argument")
     return y, a
 
 
-def gemm_mixed(planes: np.ndarray, scales_by_p: dict, p_req, x: np.ndarray, group: int = 128):
-    """Per-request precision.  ``scales_by_p[q]`` is the float16 set [q][m][n/group]."""
+def gemm_mixed(planes: np.ndarray, scales_by_p: dict, p_req, x: np.ndarray, group: int = 128, offsets_by_p=None):
+    """Per-request precision.  ``scales_by_p[q]`` is the float16 set [q][m][n/group];
+    ``offsets_by_p[q]`` (optional) the float16 offsets [m][n/group] of precision q."""
     planes = _c(planes, np.uint32)
     xb = _half_bits(x)
     p_req = np.ascontiguousarray(np.asarray(p_req, dtype=np.int32))
@@ -154,10 +174,18 @@ def gemm_mixed(planes: np.ndarray, scales_by_p: dict, p_req, x: np.ndarray, grou
             raise ValueError(f"scale set {q} has shape {sb.shape}")
         keep.append(sb)
         ptrs[q] = sb.ctypes.data
+    optrs = (ctypes.c_void_p * (p_max + 1))()
+    for q, zq in (offsets_by_p or {}).items():
+        if not 1 <= q <= p_max:
+            raise ValueError("offset set for a precision outside [1, p_max]")
+        zb = _offset_bits(zq, m, n // group)
+        keep.append(zb)
+        optrs[q] = zb.ctypes.data
     y = np.zeros((batch, m), dtype=np.float64)
     a = np.zeros((batch, m), dtype=np.float64)
-    rc = _load().bcq_oracle_gemm_mixed(_ptr(planes), ctypes.cast(ptrs, ctypes.c_void_p), _ptr(p_req), p_max,
-                                       _ptr(xb), _ptr(y), _ptr(a), m, n, batch, group)
+    rc = _load().bcq_oracle_gemm_mixed_offset(_ptr(planes), ctypes.cast(ptrs, ctypes.c_void_p),
+                                              ctypes.cast(optrs, ctypes.c_void_p) if offsets_by_p else None, _ptr(p_req), p_max,
+                                              _ptr(xb), _ptr(y), _ptr(a), m, n, batch, group)
     if rc != 0:
         raise ValueError("bcq_oracle_gemm_mixed: bad argument")
     return y, a

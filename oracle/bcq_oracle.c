@@ -18,6 +18,12 @@
  *   y[b][r]     = sum_j W_p[r][j] * x[b][j]
  *   abs[b][r]   = sum_j |W_p[r][j] * x[b][j]|      (used by the tolerance)
  *
+ * Asymmetric variant (section 4.1, implementation details: the models are
+ * quantised under the asymmetric BCQ scheme, i.e. every (row, group) also
+ * carries an offset): with an offset set z^{(p)} for precision p,
+ *   W_p[r][j]   = z^{(p)}[r][j / group] + sum_{i<p} alpha^{(p)}_i[r][j / group] * B_i[r][j]
+ * and y, abs as above.
+ *
  * All arithmetic is IEEE double.  Scales and activations arrive as the raw
  * 16 bits of IEEE binary16 values and are widened exactly.  Nothing is
  * blocked, fused or reordered: one row of W_p is materialised, then dotted
@@ -114,10 +120,13 @@ int bcq_oracle_unpack(const uint32_t *planes, int8_t *codes,
 
 /*
  * One row of the dequantised matrix W_p (section 2.2 with the precision-p
- * scale set): out[j] = sum_{i<p} alpha_i[r][j/group] * B_i[r][j], j = 0..n-1.
- * planes: [>=p][m][n/32]; scales: binary16 bits, [p][m][n/group].
+ * scale set): out[j] = sum_{i<p} alpha_i[r][j/group] * B_i[r][j], j = 0..n-1,
+ * plus offsets[r][j/group] when an offset set is given (asymmetric scheme).
+ * planes: [>=p][m][n/32]; scales: binary16 bits, [p][m][n/group];
+ * offsets: binary16 bits [m][n/group], or NULL.
  */
-static void dequant_row(const uint32_t *planes, const uint16_t *scales, int p,
+static void dequant_row(const uint32_t *planes, const uint16_t *scales,
+                        const uint16_t *offsets, int p,
                         int64_t m, int64_t n, int64_t group, int64_t r,
                         double *out)
 {
@@ -131,18 +140,26 @@ static void dequant_row(const uint32_t *planes, const uint16_t *scales, int p,
                 scales[((int64_t)i * m + r) * ngroups + j / group]);
             w += alpha * sign;
         }
+        if (offsets) w += half_bits_to_double(offsets[r * ngroups + j / group]);
         out[j] = w;
     }
 }
 
 /* Materialise W_p (double [m][n]) -- for tests on small shapes. */
-int bcq_oracle_dequant(const uint32_t *planes, const uint16_t *scales, int p,
-                       int64_t m, int64_t n, int64_t group, double *w_out)
+int bcq_oracle_dequant_offset(const uint32_t *planes, const uint16_t *scales,
+                              const uint16_t *offsets, int p,
+                              int64_t m, int64_t n, int64_t group, double *w_out)
 {
     if (p < 1 || m < 0 || n < 0 || group < 1 || (n % 32) || (n % group)) return -1;
     for (int64_t r = 0; r < m; ++r)
-        dequant_row(planes, scales, p, m, n, group, r, w_out + r * n);
+        dequant_row(planes, scales, offsets, p, m, n, group, r, w_out + r * n);
     return 0;
+}
+
+int bcq_oracle_dequant(const uint32_t *planes, const uint16_t *scales, int p,
+                       int64_t m, int64_t n, int64_t group, double *w_out)
+{
+    return bcq_oracle_dequant_offset(planes, scales, NULL, p, m, n, group, w_out);
 }
 
 /*
@@ -154,16 +171,19 @@ int bcq_oracle_dequant(const uint32_t *planes, const uint16_t *scales, int p,
  * planes      uint32 [p_max][m][n/32]
  * scales_by_p p_max+1 pointers; entry q is binary16 bits [q][m][n/group] or
  *             NULL when no request uses precision q
+ * offsets_by_p NULL, or p_max+1 pointers; entry q is binary16 bits
+ *             [m][n/group], the offsets of precision q, or NULL for none
  * p_req       int32 [batch], each in [1, p_max]
  * x           binary16 bits [batch][n]
  * y, abs_out  double [batch][m]; abs_out may be NULL
  * Returns 0, or -1 on a bad argument.
  */
-int bcq_oracle_gemm_mixed(const uint32_t *planes,
-                          const uint16_t *const *scales_by_p,
-                          const int32_t *p_req, int p_max,
-                          const uint16_t *x, double *y, double *abs_out,
-                          int64_t m, int64_t n, int64_t batch, int64_t group)
+int bcq_oracle_gemm_mixed_offset(const uint32_t *planes,
+                                 const uint16_t *const *scales_by_p,
+                                 const uint16_t *const *offsets_by_p,
+                                 const int32_t *p_req, int p_max,
+                                 const uint16_t *x, double *y, double *abs_out,
+                                 int64_t m, int64_t n, int64_t batch, int64_t group)
 {
     if (p_max < 1 || m < 0 || n < 0 || batch < 0 || group < 1 ||
         (n % 32) || (n % group))
@@ -186,7 +206,7 @@ int bcq_oracle_gemm_mixed(const uint32_t *planes,
                 int used = 0;
                 for (int64_t b = 0; b < batch; ++b) used |= (p_req[b] == q);
                 if (!used) continue;
-                dequant_row(planes, scales_by_p[q], q, m, n, group, r, wrow);
+                dequant_row(planes, scales_by_p[q], offsets_by_p ? offsets_by_p[q] : NULL, q, m, n, group, r, wrow);
                 for (int64_t b = 0; b < batch; ++b) {
                     if (p_req[b] != q) continue;
                     double acc = 0.0, aacc = 0.0;
@@ -205,23 +225,46 @@ int bcq_oracle_gemm_mixed(const uint32_t *planes,
     return failed ? -1 : 0;
 }
 
+/* Symmetric scheme: the same without offsets. */
+int bcq_oracle_gemm_mixed(const uint32_t *planes,
+                          const uint16_t *const *scales_by_p,
+                          const int32_t *p_req, int p_max,
+                          const uint16_t *x, double *y, double *abs_out,
+                          int64_t m, int64_t n, int64_t batch, int64_t group)
+{
+    return bcq_oracle_gemm_mixed_offset(planes, scales_by_p, NULL, p_req, p_max,
+                                        x, y, abs_out, m, n, batch, group);
+}
+
 /*
  * Uniform precision: every request uses precision p with scale set `scales`
- * ([p][m][n/group]).  Same definition as above with p_req[b] = p for all b.
+ * ([p][m][n/group]) and, when `offsets` is not NULL, the offset set `offsets`
+ * ([m][n/group]).  Same definition as above with p_req[b] = p for all b.
  */
+int bcq_oracle_gemv_offset(const uint32_t *planes, const uint16_t *scales,
+                           const uint16_t *offsets, int p,
+                           const uint16_t *x, double *y, double *abs_out,
+                           int64_t m, int64_t n, int64_t batch, int64_t group)
+{
+    if (p < 1 || p > 64 || batch < 0) return -1;
+    const uint16_t *sets[65];
+    const uint16_t *offs[65];
+    memset(sets, 0, sizeof(sets));
+    memset(offs, 0, sizeof(offs));
+    sets[p] = scales;
+    offs[p] = offsets;
+    int32_t *preq = (int32_t *)malloc(sizeof(int32_t) * (size_t)(batch > 0 ? batch : 1));
+    if (!preq) return -1;
+    for (int64_t b = 0; b < batch; ++b) preq[b] = p;
+    int rc = bcq_oracle_gemm_mixed_offset(planes, sets, offs, preq, p, x, y, abs_out,
+                                          m, n, batch, group);
+    free(preq);
+    return rc;
+}
+
 int bcq_oracle_gemv(const uint32_t *planes, const uint16_t *scales, int p,
                     const uint16_t *x, double *y, double *abs_out,
                     int64_t m, int64_t n, int64_t batch, int64_t group)
 {
-    if (p < 1 || p > 64 || batch < 0) return -1;
-    const uint16_t *sets[65];
-    memset(sets, 0, sizeof(sets));
-    sets[p] = scales;
-    int32_t *preq = (int32_t *)malloc(sizeof(int32_t) * (size_t)(batch > 0 ? batch : 1));
-    if (!preq) return -1;
-    for (int64_t b = 0; b < batch; ++b) preq[b] = p;
-    int rc = bcq_oracle_gemm_mixed(planes, sets, preq, p, x, y, abs_out,
-                                   m, n, batch, group);
-    free(preq);
-    return rc;
+    return bcq_oracle_gemv_offset(planes, scales, NULL, p, x, y, abs_out, m, n, batch, group);
 }

@@ -74,6 +74,14 @@ def make_scales(p: int, m: int, n: int, group: int = GROUP, seed=(0, 0), signed:
     return out.astype(np.float16)
 
 
+def make_offsets(p: int, m: int, n: int, group: int = GROUP, seed=(0, 0)) -> np.ndarray:
+    """float16 [m][n/group]: offsets of the asymmetric scheme for precision p, N(0, 0.01^2) per
+    (row, group), an independent draw for every p (half the spread of the first scale)."""
+    assert n % group == 0
+    rng = _rng(6, p, *seed)
+    return rng.normal(0.0, 0.01, size=(m, n // group)).astype(np.float16)
+
+
 def make_x(batch: int, n: int, seed=(0, 0), scale: float = 1.0) -> np.ndarray:
     """float16 [batch][n] ~ N(0, scale^2)."""
     rng = _rng(3, *seed)

@@ -5,6 +5,9 @@ Each test states what it pins.  Sources: the worked example of section 3.1
 section 2.2, the q = 1 special case of section 2.2, the memory-footprint table
 of section 1, exact rational brute force on tiny inputs, closed forms, and the
 numpy library matmul on a matrix rebuilt with numpy's own bit unpacking.
+The asymmetric offset (section 4.1) is pinned by the identity "an offset is one
+more all-(+1) plane whose scale is the offset", which reduces it to the
+symmetric path pinned above, by rational brute force and by closed forms.
 """
 import os
 from fractions import Fraction
@@ -25,7 +28,7 @@ def bit_of(planes, i, r, j):
     return (int(planes[i, r, j >> 5]) >> (j & 31)) & 1
 
 
-def brute_force(planes, scale_sets, p_req, x, group):
+def brute_force(planes, scale_sets, p_req, x, group, offset_sets=None):
     """Exact rational y[b][r] and sum of |terms| from the definition, pure Python loops."""
     _, m, words = planes.shape
     n = words * 32
@@ -43,6 +46,8 @@ def brute_force(planes, scale_sets, p_req, x, group):
                 for i in range(p):
                     alpha = Fraction(float(s[i, r, j // group]))
                     w += alpha if bit_of(planes, i, r, j) else -alpha
+                if offset_sets is not None and offset_sets.get(p) is not None:
+                    w += Fraction(float(offset_sets[p][r, j // group]))
                 t = w * Fraction(float(x[b, j]))
                 acc += t
                 aacc += abs(t)
@@ -330,3 +335,60 @@ def test_bad_arguments(oracle):
     layer = syn.make_layer(2, 128, seed=(99, 0))
     with pytest.raises(ValueError):
         oracle.gemm_mixed(layer.planes, layer.scales, [5], syn.make_x(1, 128), 128)
+
+
+# ----------------------------------------------------------------------------
+# P11: asymmetric offset (section 4.1).  z[r][g] is one more plane of all +1 with scale z:
+#      checked against the SYMMETRIC oracle path (pinned above) on such an extended layer,
+#      against exact rational brute force, and against closed forms.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("m,n,group,p_max,batch,seed", [(3, 256, 128, 3, 2, 0), (5, 384, 64, 4, 3, 1), (2, 1024, 128, 2, 1, 2)])
+def test_offset_is_an_extra_all_ones_plane(oracle, m, n, group, p_max, batch, seed):
+    layer = syn.make_layer(m, n, p_max=p_max, group=group, seed=(110, seed), signed=True)
+    x = syn.make_x(batch, n, seed=(110, seed))
+    for p in range(1, p_max + 1):
+        z = syn.make_offsets(p, m, n, group, seed=(110, seed))
+        y, a = oracle.gemv(layer.planes, layer.scales[p], x, group, offsets=z)
+        planes_ext = np.concatenate([layer.planes[:p], np.full((1, m, n // 32), 0xFFFFFFFF, dtype=np.uint32)])
+        scales_ext = np.concatenate([layer.scales[p], z[None]])
+        y2, a2 = oracle.gemv(planes_ext, scales_ext, x, group)
+        scale = a2 + 1e-300
+        assert np.all(np.abs(y - y2) <= 1e-13 * scale)
+        assert np.all(np.abs(a - a2) <= 1e-13 * scale)
+        w = oracle.dequant(layer.planes, layer.scales[p], group, offsets=z)
+        w2 = oracle.dequant(planes_ext, scales_ext, group)
+        assert np.array_equal(w, w2) or np.all(np.abs(w - w2) <= 1e-15 * np.abs(w2).max())
+
+
+def test_offset_brute_force_and_closed_forms(oracle):
+    m, n, group, p_max, batch = 3, 256, 128, 3, 3
+    layer = syn.make_layer(m, n, p_max=p_max, group=group, seed=(111, 0), signed=True)
+    x = syn.make_x(batch, n, seed=(111, 0))
+    zs = {p: syn.make_offsets(p, m, n, group, seed=(111, 0)) for p in range(1, p_max + 1)}
+    p_req = syn.make_p_req(batch, 1, p_max, seed=(111, 0))
+    y, a = oracle.gemm_mixed(layer.planes, layer.scales, p_req, x, group, offsets_by_p=zs)
+    ye, ae = brute_force(layer.planes, layer.scales, p_req, x, group, offset_sets=zs)
+    for b in range(batch):
+        for r in range(m):
+            assert abs(Fraction(y[b, r]) - ye[b][r]) <= Fraction(1, 10 ** 13) * ae[b][r] + Fraction(1, 10 ** 300)
+            assert abs(Fraction(a[b, r]) - ae[b][r]) <= Fraction(1, 10 ** 13) * ae[b][r] + Fraction(1, 10 ** 300)
+    # a precision without an offset set in the dictionary is the symmetric product
+    only2 = {2: zs[2]}
+    y2, _ = oracle.gemm_mixed(layer.planes, layer.scales, np.array([1, 2, 3], dtype=np.int32), x, group, offsets_by_p=only2)
+    y1s, _ = oracle.gemv(layer.planes, layer.scales[1], x[:1], group)
+    y3s, _ = oracle.gemv(layer.planes, layer.scales[3], x[2:], group)
+    y2o, _ = oracle.gemv(layer.planes, layer.scales[2], x[1:2], group, offsets=zs[2])
+    assert np.array_equal(y2[0], y1s[0]) and np.array_equal(y2[2], y3s[0]) and np.array_equal(y2[1], y2o[0])
+    # closed form: zero scales leave y[b][r] = sum_g z[r][g] * sum_{j in g} x[b][j]
+    zero_scales = np.zeros_like(layer.scales[2])
+    y0, a0 = oracle.gemv(layer.planes, zero_scales, x, group, offsets=zs[2])
+    xs = x.astype(np.float64).reshape(batch, n // group, group).sum(axis=2)
+    expect = np.einsum("rg,bg->br", zs[2].astype(np.float64), xs)
+    bound = 1e-13 * (np.abs(zs[2].astype(np.float64)).sum(axis=1)[None, :] * np.abs(x.astype(np.float64)).sum(axis=1)[:, None])
+    assert np.all(np.abs(y0 - expect) <= bound)
+    # linearity in the offset: y(z) - y(0) is that same closed form
+    ysym, _ = oracle.gemv(layer.planes, layer.scales[2], x, group)
+    yoff, _ = oracle.gemv(layer.planes, layer.scales[2], x, group, offsets=zs[2])
+    assert np.all(np.abs((yoff - ysym) - expect) <= 1e-12 * (np.abs(ysym) + np.abs(expect) + 1e-300))
+    # a dropped offset must be visible at the acceptance tolerance (the pin would catch a no-op)
+    assert np.any(np.abs(yoff - ysym) > oracle.tolerance(yoff, a0 + np.abs(ysym)))

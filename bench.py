@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a reference kernel of known traffic for counter runs)")
-    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused"], default=None,
+    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused", "offset"], default=None,
                     help="instead of the headline workload, time another workload family and print its table")
     return ap.parse_args()
 
@@ -112,7 +112,7 @@ def run_suite(args, torch, bcq, syn, dev):
     rows = []
     launches = 16
 
-    def bench_shape(m, n, batches, precisions, mixed=False):
+    def bench_shape(m, n, batches, precisions, mixed=False, offsets=False):
         copies = max(2, -(-MIN_ROTATION_BYTES // (m * n // 2)))
         copies = min(copies, 24)
         sets = [device_layer(m, n) for _ in range(copies)]
@@ -120,13 +120,16 @@ def run_suite(args, torch, bcq, syn, dev):
             x = torch.randn((batch, n), device=dev, generator=gen).half()
             y = torch.empty((batch, m), dtype=torch.float16, device=dev)
             for p in precisions:
+                # asymmetric scheme: one fp16 offset per (row, group), N(0, 0.01^2), one set per precision
+                z = (torch.randn((m, n // syn.GROUP), device=dev, generator=gen) * 0.01).half() if offsets else None
+
                 def burst():
                     for i in range(launches):
                         pl, sc = sets[i % copies]
-                        bcq.bcq_gemv(pl, sc[p], p, x, y)
+                        bcq.bcq_gemv(pl, sc[p], p, x, y, offsets=z)
                 us = timed_graph(burst) * 1e3 / launches
-                by = syn.algorithmic_bytes(m, n, p, batch)
-                rows.append({"m": m, "n": n, "batch": batch, "p": p, "kernel": bcq.last_kernel(), "us": round(us, 2),
+                by = syn.algorithmic_bytes(m, n, p, batch) + (m * (n // syn.GROUP) * 2 if offsets else 0)
+                rows.append({"m": m, "n": n, "batch": batch, "p": p, "offsets": bool(offsets), "kernel": bcq.last_kernel(), "us": round(us, 2),
                              "GBps": round(by / us / 1e3, 1), "pct_of_hbm_peak": round(100 * by / us / 1e3 / HBM_PEAK_GBS, 2),
                              "TFLOPs": round(2.0 * m * n * batch / us / 1e6, 1)})
             if mixed:
@@ -150,6 +153,11 @@ def run_suite(args, torch, bcq, syn, dev):
             bench_shape(m, n, (1, 2, 4, 8, 16, 32), PRECISIONS)
     elif args.suite == "mixed":
         bench_shape(14336, 4096, (16,), PRECISIONS, mixed=True)
+    elif args.suite == "offset":
+        # asymmetric scheme next to the symmetric one, batch 1 and a dequantising batch
+        for (m, n) in ((4096, 4096), (14336, 4096), (4096, 14336)):
+            bench_shape(m, n, (1, 64), PRECISIONS)
+            bench_shape(m, n, (1, 64), PRECISIONS, offsets=True)
     elif args.suite == "phi4":
         # second model of the paper's GEMV table; 17920 columns end in a half slice
         for (_, m, n) in syn.PHI4_14B_SHAPES:

@@ -123,6 +123,32 @@ int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p,
                    const bcq_half *x, bcq_half *y,
                    int64_t m, int64_t n, int batch, int group, void *stream);
 
+/*
+ * Asymmetric BCQ (section 4.1, implementation details: the models are quantised
+ * under the asymmetric scheme): every (row, group) also carries an offset z, so
+ * W_p[r][j] = z^{(p)}[r][j/group] + sum_{i<p} alpha^{(p)}_i[r][j/group] B_i[r][j]
+ * and y gains sum_g z^{(p)}[r][g] * sum_{j in g} x[b][j].  Each precision has its
+ * own offsets, as it has its own scales.
+ *
+ * bcq_gemv_offset: as bcq_gemv, plus
+ *   offsets_p  bcq_half [m][n/group] (device), the offsets OF PRECISION p;
+ *              NULL gives exactly bcq_gemv
+ * bcq_gemm_mixed_offset: as bcq_gemm_mixed, plus
+ *   offsets_by_p  HOST array of p_max+1 device pointers; entry q is the offset
+ *                 set of precision q ([m][n/group]) or NULL for none; entry 0
+ *                 is ignored; the array itself may be NULL (no offsets at all)
+ * Offset sets must be 16-byte aligned.  Errors as for the symmetric calls.
+ */
+int bcq_gemv_offset(const uint32_t *planes, const bcq_half *scales_p, const bcq_half *offsets_p, int p,
+                    const bcq_half *x, bcq_half *y,
+                    int64_t m, int64_t n, int batch, int group, void *stream);
+
+int bcq_gemm_mixed_offset(const uint32_t *planes, const bcq_half *const *scales_by_p,
+                          const bcq_half *const *offsets_by_p,
+                          const int32_t *p_req, int p_max,
+                          const bcq_half *x, bcq_half *y,
+                          int64_t m, int64_t n, int batch, int group, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

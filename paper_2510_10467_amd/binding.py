@@ -45,7 +45,10 @@ def lib() -> ctypes.CDLL:
         L.bcq_unpack.argtypes = [vp, vp, i32, i64, i64, vp]
         L.bcq_gemv.argtypes = [vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
         L.bcq_gemm_mixed.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
-        for f in (L.bcq_select_kernel, L.bcq_pack, L.bcq_unpack, L.bcq_gemv, L.bcq_gemm_mixed):
+        L.bcq_gemv_offset.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
+        L.bcq_gemm_mixed_offset.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
+        for f in (L.bcq_select_kernel, L.bcq_pack, L.bcq_unpack, L.bcq_gemv, L.bcq_gemm_mixed, L.bcq_gemv_offset,
+                  L.bcq_gemm_mixed_offset):
             f.restype = i32
         _lib = L
     return _lib
@@ -101,8 +104,9 @@ def bcq_unpack(planes: torch.Tensor, codes: torch.Tensor | None = None) -> torch
 
 
 def bcq_gemv(planes: torch.Tensor, scales_p: torch.Tensor, p: int, x: torch.Tensor,
-             y: torch.Tensor | None = None, group: int = 128) -> torch.Tensor:
-    """Uniform precision: y[b][r] = sum_{i<p} sum_j scales_p[i][r][j/group] * B_i[r][j] * x[b][j]."""
+             y: torch.Tensor | None = None, group: int = 128, offsets: torch.Tensor | None = None) -> torch.Tensor:
+    """Uniform precision: y[b][r] = sum_{i<p} sum_j scales_p[i][r][j/group] * B_i[r][j] * x[b][j];
+    with ``offsets`` (float16 [m][n/group], asymmetric scheme) plus sum_j offsets[r][j/group] * x[b][j]."""
     _, m, words = planes.shape
     n = words * 32
     batch = x.shape[0]
@@ -112,6 +116,13 @@ def bcq_gemv(planes: torch.Tensor, scales_p: torch.Tensor, p: int, x: torch.Tens
         y = torch.empty((batch, m), dtype=torch.float16, device=x.device)
     elif y.shape != (batch, m):
         raise ValueError("bcq_gemv: y has the wrong shape")
+    if offsets is not None:
+        if offsets.shape != (m, n // group):
+            raise ValueError("bcq_gemv: offsets have the wrong shape")
+        _check(lib().bcq_gemv_offset(_dev(planes, torch.int32, "planes"), _dev(scales_p, torch.float16, "scales_p"),
+                                     _dev(offsets, torch.float16, "offsets"), p, _dev(x, torch.float16, "x"),
+                                     _dev(y, torch.float16, "y"), m, n, batch, group, _stream()), "bcq_gemv_offset")
+        return y
     _check(lib().bcq_gemv(_dev(planes, torch.int32, "planes"), _dev(scales_p, torch.float16, "scales_p"), p,
                           _dev(x, torch.float16, "x"), _dev(y, torch.float16, "y"), m, n, batch, group, _stream()),
            "bcq_gemv")
@@ -119,8 +130,9 @@ def bcq_gemv(planes: torch.Tensor, scales_p: torch.Tensor, p: int, x: torch.Tens
 
 
 def bcq_gemm_mixed(planes: torch.Tensor, scales_by_p: dict, p_req: torch.Tensor, x: torch.Tensor,
-                   y: torch.Tensor | None = None, group: int = 128) -> torch.Tensor:
-    """Per-request precision: request b uses planes 0..p_req[b]-1 and scale set scales_by_p[p_req[b]]."""
+                   y: torch.Tensor | None = None, group: int = 128, offsets_by_p: dict | None = None) -> torch.Tensor:
+    """Per-request precision: request b uses planes 0..p_req[b]-1 and scale set scales_by_p[p_req[b]]
+    (and the offset set offsets_by_p[p_req[b]] if there is one)."""
     p_max, m, words = planes.shape
     n = words * 32
     batch = x.shape[0]
@@ -135,6 +147,17 @@ def bcq_gemm_mixed(planes: torch.Tensor, scales_by_p: dict, p_req: torch.Tensor,
         y = torch.empty((batch, m), dtype=torch.float16, device=x.device)
     elif y.shape != (batch, m):
         raise ValueError("bcq_gemm_mixed: y has the wrong shape")
+    if offsets_by_p:
+        optrs = (ctypes.c_void_p * (p_max + 1))()
+        for q, z in offsets_by_p.items():
+            if not 1 <= q <= p_max or z.shape != (m, n // group):
+                raise ValueError(f"bcq_gemm_mixed: bad offset set for precision {q}")
+            optrs[q] = _dev(z, torch.float16, f"offsets_by_p[{q}]")
+        _check(lib().bcq_gemm_mixed_offset(_dev(planes, torch.int32, "planes"), ctypes.cast(ptrs, ctypes.c_void_p),
+                                           ctypes.cast(optrs, ctypes.c_void_p), _dev(p_req, torch.int32, "p_req"), p_max,
+                                           _dev(x, torch.float16, "x"), _dev(y, torch.float16, "y"), m, n, batch, group,
+                                           _stream()), "bcq_gemm_mixed_offset")
+        return y
     _check(lib().bcq_gemm_mixed(_dev(planes, torch.int32, "planes"), ctypes.cast(ptrs, ctypes.c_void_p),
                                 _dev(p_req, torch.int32, "p_req"), p_max, _dev(x, torch.float16, "x"),
                                 _dev(y, torch.float16, "y"), m, n, batch, group, _stream()), "bcq_gemm_mixed")

@@ -105,17 +105,19 @@ int bcq_unpack(const uint32_t *planes, int8_t *codes, int n_planes, int64_t m, i
                ? BCQ_OK : BCQ_ERR_HIP;
 }
 
-int bcq_gemv(const uint32_t *planes, const bcq_half *scales_p, int p, const bcq_half *x, bcq_half *y,
-             int64_t m, int64_t n, int batch, int group, void *stream)
+int bcq_gemv_offset(const uint32_t *planes, const bcq_half *scales_p, const bcq_half *offsets_p, int p, const bcq_half *x,
+                    bcq_half *y, int64_t m, int64_t n, int batch, int group, void *stream)
 {
     if (!planes || !scales_p || !x || !y) return BCQ_ERR_NULL;
     if (p < 1 || p > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
     if (int rc = check_shape(m, n, batch, group)) return rc;
-    if (!aligned(planes, 16) || !aligned(scales_p, 16) || !aligned(x, 16) || !aligned(y, 2)) return BCQ_ERR_ALIGN;
+    if (!aligned(planes, 16) || !aligned(scales_p, 16) || !aligned(offsets_p, 16) || !aligned(x, 16) || !aligned(y, 2))
+        return BCQ_ERR_ALIGN;
     if (batch == 0) return BCQ_OK;
     bcq::GemmArgs a{};
     a.planes = planes;
     a.scales[p] = reinterpret_cast<const _Float16 *>(scales_p);
+    a.offsets[p] = reinterpret_cast<const _Float16 *>(offsets_p);
     a.p_req = nullptr;
     a.uniform_p = p;
     a.p_max = p;
@@ -128,8 +130,15 @@ int bcq_gemv(const uint32_t *planes, const bcq_half *scales_p, int p, const bcq_
     return run(a, static_cast<hipStream_t>(stream));
 }
 
-int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p, const int32_t *p_req, int p_max,
-                   const bcq_half *x, bcq_half *y, int64_t m, int64_t n, int batch, int group, void *stream)
+int bcq_gemv(const uint32_t *planes, const bcq_half *scales_p, int p, const bcq_half *x, bcq_half *y,
+             int64_t m, int64_t n, int batch, int group, void *stream)
+{
+    return bcq_gemv_offset(planes, scales_p, nullptr, p, x, y, m, n, batch, group, stream);
+}
+
+int bcq_gemm_mixed_offset(const uint32_t *planes, const bcq_half *const *scales_by_p, const bcq_half *const *offsets_by_p,
+                          const int32_t *p_req, int p_max, const bcq_half *x, bcq_half *y, int64_t m, int64_t n, int batch,
+                          int group, void *stream)
 {
     if (!planes || !scales_by_p || !p_req || !x || !y) return BCQ_ERR_NULL;
     if (p_max < 1 || p_max > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
@@ -141,6 +150,10 @@ int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p, c
         if (!aligned(scales_by_p[q], 16)) return BCQ_ERR_ALIGN;
         a.scales[q] = reinterpret_cast<const _Float16 *>(scales_by_p[q]);
         any = any || scales_by_p[q] != nullptr;
+        if (offsets_by_p) {
+            if (!aligned(offsets_by_p[q], 16)) return BCQ_ERR_ALIGN;
+            a.offsets[q] = reinterpret_cast<const _Float16 *>(offsets_by_p[q]);
+        }
     }
     if (!any) return BCQ_ERR_NULL;
     if (batch == 0) return BCQ_OK;
@@ -155,6 +168,12 @@ int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p, c
     a.batch = batch;
     a.group = group;
     return run(a, static_cast<hipStream_t>(stream));
+}
+
+int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p, const int32_t *p_req, int p_max,
+                   const bcq_half *x, bcq_half *y, int64_t m, int64_t n, int batch, int group, void *stream)
+{
+    return bcq_gemm_mixed_offset(planes, scales_by_p, nullptr, p_req, p_max, x, y, m, n, batch, group, stream);
 }
 
 }  // extern "C"

@@ -13,7 +13,8 @@
 //     (a permutation of K that the activation operand follows), so for each step the lane takes
 //     byte t of each plane word, looks it up in a 256-entry LDS table of eight +-1.0 binary16
 //     values, accumulates w_j = sum_i alpha_i * (+-1) in fp32 (one mixed-precision FMA per column
-//     and plane) and rounds once to binary16: that IS the B operand of v_mfma_f32_16x16x32_f16;
+//     and plane), starting from the group's offset in the asymmetric scheme (section 4.1), and
+//     rounds once to binary16: that IS the B operand of v_mfma_f32_16x16x32_f16;
 //   * the wave multiplies its 16 x 128 weight tile with all TB requests, reading each activation
 //     operand (16 requests x 32 columns) from LDS.
 // A weight is therefore dequantised once per TB requests and never leaves the registers; the
@@ -48,6 +49,8 @@ constexpr int lds_bytes(int nu, int teams) { return kLutBytes + teams * 2 * x_ti
 struct DequantParams {
     const unsigned char *planes;            // plane 0
     const unsigned char *scales;            // scale set of the precision
+    const unsigned char *offsets;           // offsets [m][n/128] of the precision; any readable array of that size if none
+    int has_offsets;
     const unsigned char *x;
     _Float16 *y;
     uint32_t plane_stride;                  // bytes between planes:        m * n / 8
@@ -65,6 +68,7 @@ template <int P, int NU>
 struct Ahead {
     uint32_t w[P];
     _Float16 alpha[P];
+    _Float16 z;
     u32x4 xs[4 * NU];
 };
 
@@ -125,6 +129,7 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
             const unsigned char *s_base = a.scales + (size_t)i * a.scale_plane_stride + (uint32_t)g * 2;
             ah.alpha[i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
         }
+        ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + (uint32_t)g * 2 + s_lane);
     };
     auto fetch_x = [&](Ahead<P, NU> &ah, int g) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
@@ -149,8 +154,11 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
         // then exact.  (Claimed after the next loads have been issued, it would cover those too.)
 #pragma unroll
         for (int i = 0; i < P; ++i) asm volatile("" : "+v"(cur.w[i]), "+v"(cur.alpha[i]));
+        asm volatile("" : "+v"(cur.z));
 #pragma unroll
         for (int k = 0; k < 4 * NU; ++k) asm volatile("" : "+v"(cur.xs[k]));
+        const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.z));
+        const float z = a.has_offsets ? (float)__builtin_bit_cast(_Float16, (unsigned short)zb) : 0.f;
         uint32_t w[P];
         float alpha[P];
 #pragma unroll
@@ -169,7 +177,7 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
         for (int t = 0; t < 4; ++t) {
             float wf[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) wf[j] = 0.f;
+            for (int j = 0; j < 8; ++j) wf[j] = z;
 #pragma unroll
             for (int i = 0; i < P; ++i) {
                 const uint32_t byte = (w[i] >> (8 * t)) & 0xffu;
@@ -273,6 +281,8 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
     DequantParams pr{};
     pr.planes = reinterpret_cast<const unsigned char *>(a.planes);
     pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);
+    pr.has_offsets = a.offsets[a.uniform_p] != nullptr;
+    pr.offsets = pr.has_offsets ? reinterpret_cast<const unsigned char *>(a.offsets[a.uniform_p]) : pr.scales;
     pr.x = reinterpret_cast<const unsigned char *>(a.x);
     pr.y = a.y;
     pr.plane_stride = (uint32_t)(a.m * (a.n / 8));

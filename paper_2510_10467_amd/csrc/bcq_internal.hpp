@@ -13,6 +13,7 @@ namespace bcq {
 struct GemmArgs {
     const uint32_t *planes;                          // [>= p_max][m][n/32]
     const _Float16 *scales[BCQ_MAX_PLANES + 1];      // [q] = scale set of precision q, or nullptr
+    const _Float16 *offsets[BCQ_MAX_PLANES + 1];     // [q] = offsets [m][n/group] of precision q, or nullptr (none)
     const int32_t *p_req;                            // device int32[batch], nullptr when uniform
     int uniform_p;                                   // > 0: every request runs at this precision
     int p_max;                                       // planes stored / upper bound of any p_req

@@ -23,6 +23,10 @@
 //     precision, and accumulates in fp32.  Requests at different precisions
 //     share the plane sweep; a lane's scales beyond p_b are zero.
 //
+// Asymmetric scheme (section 4.1): the offset z[r][g] of a (row, group) multiplies the plain sum of the
+// group's activations, which depends on neither row nor plane; it is formed beside the operand image
+// (one float per request and group, kept in the image's padding) and costs one FMA per group.
+//
 // Work split: a workgroup owns RB blocks of 16 rows and the whole K range;
 // wave (rb, ks) handles K slice ks (1024 columns) of row block rb, issues all
 // of its plane and scale loads up front (128-bit, 128 contiguous bytes per row
@@ -52,8 +56,10 @@ struct PlaneMfmaParams {
     const unsigned char *x;                 // activations of request 0 of the whole batch
     _Float16 *y;
     const unsigned char *scales[BCQ_MAX_PLANES + 1];   // scale set per precision (bytes)
+    const unsigned char *offsets[BCQ_MAX_PLANES + 1];  // offsets [m][n/128] per precision, or nullptr (asymmetric scheme)
     const int32_t *p_req;                   // per-request precisions (mixed) or nullptr
     uint32_t set_mask;                      // bit k set: scales[k] is there (k = 1 .. 4)
+    uint32_t offset_mask;                   // bit k set: offsets[k] is there
     uint32_t plane_stride;                  // bytes between planes:      m * n / 8
     uint32_t row_stride;                    // bytes between plane rows:  n / 8
     uint32_t scale_plane_stride;            // bytes between scale planes: m * (n/128) * 2
@@ -99,11 +105,22 @@ __device__ __forceinline__ v8i expand_plane_word(uint32_t w, uint32_t sign, uint
     return r;
 }
 
+// Sum of a value over the 8 lanes l & ~7 .. l | 7 (result in all of them).
+__device__ __forceinline__ float sum_over_8_lanes(float v)
+{
+    // quad_perm(1,0,3,2), quad_perm(2,3,0,1), row_half_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, false));
+    return v;
+}
+
 // What one wave fetches for one K slice: activations, scales, plane words.
 template <int PH, int NB>
 struct SliceLoads {
     u32x4 xv[NB][2];                        // 16 consecutive columns (one image unit) per request slot
     u32x4 sc[PH];                           // the 8 scales of the lane's row, per plane
+    u32x4 zc;                               // the 8 offsets of the lane's row (asymmetric scheme only)
     u32x4 wa[PH], wb[PH];                   // plane words: rows 0-7 and rows 8-15 of the block
 };
 
@@ -122,9 +139,10 @@ __device__ __forceinline__ u32x4 drop_first_half(u32x4 v)
                  __builtin_amdgcn_alignbit(v.w, v.z, 16), v.w >> 16};
 }
 
-template <int PH, int NB, bool MIXED>
+template <int PH, int NB, bool MIXED, bool OFFSET>
 __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneMfmaParams &pr, const LaneOffsets &off,
-                                            const unsigned char *sbase, int p_mine, int slice_c, int ngroups)
+                                            const unsigned char *sbase, const unsigned char *zbase, int p_mine, int slice_c,
+                                            int ngroups)
 {
     // A last slice of ngroups < 8 groups: lanes whose columns or group lie past the end of the row fetch
     // the slice's first unit or group instead (valid memory, finite values; the scales of those groups
@@ -151,6 +169,7 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
             ld.sc[i] = *reinterpret_cast<const u32x4 *>(s_base + off.s);
         }
     }
+    if constexpr (OFFSET) ld.zc = *reinterpret_cast<const u32x4 *>(zbase + s_slice + off.s);
     const uint32_t wa = off.wa + w_lane, wb = off.wb + w_lane;
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
@@ -164,9 +183,12 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
 // Sweep of one wave over its K slices for PH planes; returns this lane's partial sum.
 //   p_mine   precision of the request this lane reports on (0: none); sbase its scale set
 // MIXED: lanes of different quarters may belong to requests of different precisions.
-template <int PH, int NB, bool MIXED>
+// OFFSET: asymmetric scheme; zbase is the offset set of the lane's request (any readable array of that
+//         size when z_on is false: the request has none).
+template <int PH, int NB, bool MIXED, bool OFFSET>
 __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int RB, int wave, int lane,
-                                       const LaneOffsets &off, int p_mine, const unsigned char *sbase)
+                                       const LaneOffsets &off, int p_mine, const unsigned char *sbase,
+                                       const unsigned char *zbase, bool z_on)
 {
     using L = Lds<NB>;
     const int KS = pr.KS;
@@ -183,7 +205,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         // delays the memory phase of all waves that share the SIMD.  The lane id is made opaque after
         // them so that no LDS address arithmetic is moved in front of the loop.
         SliceLoads<PH, NB> ld;
-        issue_loads<PH, NB, MIXED>(ld, pr, off, sbase, p_mine, slice_ok ? slice : 0, ngroups);
+        issue_loads<PH, NB, MIXED, OFFSET>(ld, pr, off, sbase, zbase, p_mine, slice_ok ? slice : 0, ngroups);
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" : "+v"(lane));
 
@@ -200,8 +222,11 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         // 16u + low + 4i (i = 0..3) belongs to operand byte 8z + 4(u&1) + i of lane quarter 2*((u>>1)&1) + w
         // with 2w + z = 3 - low, so a unit yields one dword for each (low, term): 16 dword stores.
         const int u16 = lane & 7;
-        unsigned char *img_unit = lds + ks * L::kSliceImage + (lane >> 3) * L::kGroupBytes + (u16 >> 2) * L::kHalfBytes +
-                                  (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
+        unsigned char *img_group = lds + ks * L::kSliceImage + (lane >> 3) * L::kGroupBytes;
+        unsigned char *img_unit = img_group + (u16 >> 2) * L::kHalfBytes + (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
+        // asymmetric scheme: sum_j x_j of a group, one float per request slot in the padding behind the
+        // first half of the group's image; this lane reads the one of its own request slot
+        const unsigned char *img_xsum = lds + ks * L::kSliceImage + 4 * L::kRows * 16 + (q < NB ? q : NB - 1) * 4;
         // Plane words change hands inside the wave, row-major in, operand-major out: the wave's tile holds
         // one plane's 16 rows x 128 bytes.  Rows are 144 bytes apart, so the 64 dword reads of one group,
         // one per (row, K quarter), fall into 64 different banks.
@@ -218,6 +243,18 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
             if (b >= NB) break;
             const u32x4 c0 = ld.xv[bb][0], c1 = ld.xv[bb][1];
             const uint32_t dwd[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};       // dword k = columns 2k, 2k+1
+            if constexpr (OFFSET) {
+                // the unit's 16 activations in fp32, then the group's 8 units (= 8 lanes)
+                float xsum = 0.f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const h2 pair = __builtin_bit_cast(h2, dwd[k]);
+                    xsum += (float)pair[0];
+                    xsum += (float)pair[1];
+                }
+                xsum = sum_over_8_lanes(xsum);
+                if (u16 == 0) *reinterpret_cast<float *>(img_group + 4 * L::kRows * 16 + b * 4) = xsum;
+            }
 #pragma unroll
             for (int low = 0; low < 4; ++low) {
                 const uint32_t sel = (low & 1) ? 0x07060302u : 0x05040100u;                   // upper or lower halves
@@ -247,7 +284,11 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
             for (int k = ngroups; k < kSliceGroups; ++k) {
 #pragma unroll
                 for (int i = 0; i < PH; ++i) ld.sc[i] = drop_first_half(ld.sc[i]);
+                if constexpr (OFFSET) ld.zc = drop_first_half(ld.zc);
             }
+        }
+        if constexpr (OFFSET) {
+            if (!z_on || !slice_ok) ld.zc = u32x4{0, 0, 0, 0};
         }
         // scales of planes this lane must not use (beyond its precision, or a slice past the end) become zero
         if (MIXED || !slice_ok) {
@@ -272,12 +313,21 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         // the operand rows of the next group are fetched while this one is in the matrix pipe
         u32x4 lo = *reinterpret_cast<const u32x4 *>(img_lane);
         u32x4 hi = *reinterpret_cast<const u32x4 *>(img_lane + L::kHalfBytes);
+        float xsum = 0.f;
+        if constexpr (OFFSET) xsum = *reinterpret_cast<const float *>(img_xsum);
 #pragma unroll
         for (int gl = 0; gl < kSliceGroups; ++gl) {
             const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            if constexpr (OFFSET) {
+                // offset of the group times the sum of its activations
+                const uint32_t zw = ld.zc[gl >> 1];
+                const float z = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (zw >> 16) : (zw & 0xffffu)));
+                acc = fmaf(z, xsum, acc);
+            }
             if (gl + 1 < kSliceGroups) {
                 lo = *reinterpret_cast<const u32x4 *>(img_lane + (gl + 1) * L::kGroupBytes);
                 hi = *reinterpret_cast<const u32x4 *>(img_lane + (gl + 1) * L::kGroupBytes + L::kHalfBytes);
+                if constexpr (OFFSET) xsum = *reinterpret_cast<const float *>(img_xsum + (gl + 1) * L::kGroupBytes);
             }
             v4f d[PH];
 #pragma unroll
@@ -308,7 +358,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
 // workgroup leaves a wave (128), and their operand image limits the waves per CU anyway: they stop at 8.
 __host__ __device__ constexpr int max_waves(int NB, bool mixed) { return NB == 4 && mixed ? 8 : 16; }
 
-template <int P, int NB, bool MIXED>
+template <int P, int NB, bool MIXED, bool OFFSET>
 __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(PlaneMfmaParams pr)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -364,7 +414,7 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB, false>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P]);
+        acc = sweep<P, NB, false, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P], pr.offsets[P], true);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs.
         // The four precisions of the tile are fetched together, and scale sets are picked by comparison
@@ -384,12 +434,19 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
             if (b == q) p_mine = pb;
         }
         const unsigned char *sbase = pick(p_mine > 0 ? p_mine : p_hi);
+        // offsets of the lane's request, if its precision has any (else any readable array: the scales)
+        const bool z_on = OFFSET && ((pr.offset_mask >> p_mine) & 1);
+        const unsigned char *zbase = sbase;
+        if constexpr (OFFSET) {
+            const unsigned char *const z1 = pr.offsets[1], *const z2 = pr.offsets[2], *const z3 = pr.offsets[3], *const z4 = pr.offsets[4];
+            if (z_on) zbase = p_mine == 1 ? z1 : p_mine == 2 ? z2 : p_mine == 3 ? z3 : z4;
+        }
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
-        case 2: acc = sweep<2, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
-        case 3: acc = sweep<3, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
-        case 4: acc = sweep<4, NB, true>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase); break;
+        case 1: acc = sweep<1, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 2: acc = sweep<2, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 3: acc = sweep<3, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 4: acc = sweep<4, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }
@@ -467,15 +524,15 @@ hipError_t launch_one(K kernel, const PlaneMfmaParams &pr, const Plan &pl, dim3 
     return hipGetLastError();
 }
 
-template <int NB>
+template <int NB, bool OFFSET>
 hipError_t launch_nb(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
 {
-    if (a.uniform_p == 0) return launch_one(plane_mfma_kernel<kMaxP, NB, true>, pr, pl, grid, block, stream);
+    if (a.uniform_p == 0) return launch_one(plane_mfma_kernel<kMaxP, NB, true, OFFSET>, pr, pl, grid, block, stream);
     switch (a.uniform_p) {
-    case 1: return launch_one(plane_mfma_kernel<1, NB, false>, pr, pl, grid, block, stream);
-    case 2: return launch_one(plane_mfma_kernel<2, NB, false>, pr, pl, grid, block, stream);
-    case 3: return launch_one(plane_mfma_kernel<3, NB, false>, pr, pl, grid, block, stream);
-    default: return launch_one(plane_mfma_kernel<4, NB, false>, pr, pl, grid, block, stream);
+    case 1: return launch_one(plane_mfma_kernel<1, NB, false, OFFSET>, pr, pl, grid, block, stream);
+    case 2: return launch_one(plane_mfma_kernel<2, NB, false, OFFSET>, pr, pl, grid, block, stream);
+    case 3: return launch_one(plane_mfma_kernel<3, NB, false, OFFSET>, pr, pl, grid, block, stream);
+    default: return launch_one(plane_mfma_kernel<4, NB, false, OFFSET>, pr, pl, grid, block, stream);
     }
 }
 
@@ -501,8 +558,13 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.y = a.y;
     for (int q = 0; q <= BCQ_MAX_PLANES; ++q) pr.scales[q] = reinterpret_cast<const unsigned char *>(a.scales[q]);
     pr.p_req = a.p_req;
-    for (int q = 1; q <= kMaxP; ++q)
+    for (int q = 0; q <= BCQ_MAX_PLANES; ++q) pr.offsets[q] = reinterpret_cast<const unsigned char *>(a.offsets[q]);
+    for (int q = 1; q <= kMaxP; ++q) {
         if (a.scales[q]) pr.set_mask |= 1u << q;
+        if (a.offsets[q] && a.scales[q]) pr.offset_mask |= 1u << q;
+    }
+    // the asymmetric kernels run only when an offset set will be used
+    const bool with_offsets = a.uniform_p > 0 ? a.offsets[a.uniform_p] != nullptr : pr.offset_mask != 0;
     pr.plane_stride = (uint32_t)(a.m * (a.n / 8));
     pr.row_stride = (uint32_t)(a.n / 8);
     pr.scale_plane_stride = (uint32_t)(a.m * (a.n / 128) * 2);
@@ -525,10 +587,17 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.inv_span = 1.0f / (float)(8 * pr.ntiles);
     pr.inv_ks = 1.0f / (float)pl.KS;
     dim3 block(64 * pl.KS * pl.RB);
+    if (with_offsets) {
+        switch (pl.NB) {
+        case 1: return launch_nb<1, true>(a, pr, pl, grid, block, stream);
+        case 2: return launch_nb<2, true>(a, pr, pl, grid, block, stream);
+        default: return launch_nb<4, true>(a, pr, pl, grid, block, stream);
+        }
+    }
     switch (pl.NB) {
-    case 1: return launch_nb<1>(a, pr, pl, grid, block, stream);
-    case 2: return launch_nb<2>(a, pr, pl, grid, block, stream);
-    default: return launch_nb<4>(a, pr, pl, grid, block, stream);
+    case 1: return launch_nb<1, false>(a, pr, pl, grid, block, stream);
+    case 2: return launch_nb<2, false>(a, pr, pl, grid, block, stream);
+    default: return launch_nb<4, false>(a, pr, pl, grid, block, stream);
     }
 }
 

@@ -54,6 +54,13 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void sign_select_kernel(GemmAr
 #pragma unroll
             for (int k = 0; k < 32; ++k) xv[k] = (float)xp[k];
             const _Float16 *sp = a.scales[pb[t]];
+            // asymmetric scheme: the group's offset times the sum of the word's activations
+            if (const _Float16 *zp = a.offsets[pb[t]]) {
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < 32; ++k) s += xv[k];
+                acc[t] = fmaf((float)zp[r * ngroups + g], s, acc[t]);
+            }
 #pragma unroll
             for (int i = 0; i < BCQ_MAX_PLANES; ++i) {
                 if (i < pb[t]) {

@@ -35,27 +35,30 @@ def assert_within_tolerance(y_gpu: torch.Tensor, y_ref: np.ndarray, a_ref: np.nd
     return float(np.max(err / tol))
 
 
-def check_gemv(dl: DeviceLayer, p: int, x: np.ndarray, kernel: str, group: int = 128):
+def check_gemv(dl: DeviceLayer, p: int, x: np.ndarray, kernel: str, group: int = 128, offsets: np.ndarray | None = None):
     bcq.select_kernel(kernel)
     try:
-        y = bcq.bcq_gemv(dl.planes, dl.scales[p], p, to_dev(x), group=group)
+        y = bcq.bcq_gemv(dl.planes, dl.scales[p], p, to_dev(x), group=group,
+                         offsets=None if offsets is None else to_dev(offsets))
         torch.cuda.synchronize()
         used = bcq.last_kernel()
     finally:
         bcq.select_kernel("auto")
-    y_ref, a_ref = oracle.gemv(dl.layer.planes, dl.layer.scales[p], x, group)
-    worst = assert_within_tolerance(y, y_ref, a_ref, f"bcq_gemv[{kernel}] m={dl.layer.m} n={dl.layer.n} p={p} batch={x.shape[0]}")
+    y_ref, a_ref = oracle.gemv(dl.layer.planes, dl.layer.scales[p], x, group, offsets=offsets)
+    worst = assert_within_tolerance(y, y_ref, a_ref, f"bcq_gemv[{kernel}] m={dl.layer.m} n={dl.layer.n} p={p} batch={x.shape[0]}"
+                                                     f"{'' if offsets is None else ' with offsets'}")
     return used, worst
 
 
-def check_mixed(dl: DeviceLayer, p_req: np.ndarray, x: np.ndarray, kernel: str, group: int = 128):
+def check_mixed(dl: DeviceLayer, p_req: np.ndarray, x: np.ndarray, kernel: str, group: int = 128, offsets_by_p: dict | None = None):
     bcq.select_kernel(kernel)
     try:
-        y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, to_dev(p_req.astype(np.int32)), to_dev(x), group=group)
+        y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, to_dev(p_req.astype(np.int32)), to_dev(x), group=group,
+                               offsets_by_p=None if not offsets_by_p else {q: to_dev(z) for q, z in offsets_by_p.items()})
         torch.cuda.synchronize()
         used = bcq.last_kernel()
     finally:
         bcq.select_kernel("auto")
-    y_ref, a_ref = oracle.gemm_mixed(dl.layer.planes, dl.layer.scales, p_req, x, group)
+    y_ref, a_ref = oracle.gemm_mixed(dl.layer.planes, dl.layer.scales, p_req, x, group, offsets_by_p=offsets_by_p)
     worst = assert_within_tolerance(y, y_ref, a_ref, f"bcq_gemm_mixed[{kernel}] m={dl.layer.m} n={dl.layer.n} batch={x.shape[0]}")
     return used, worst

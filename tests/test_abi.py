@@ -26,8 +26,8 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_strerror", "bcq_select_kernel",
-            "bcq_last_kernel"} <= set(names)
+    assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_gemv_offset", "bcq_gemm_mixed_offset",
+            "bcq_strerror", "bcq_select_kernel", "bcq_last_kernel"} <= set(names)
     for name in names:
         assert hasattr(lib, name), f"{name} declared in bcq.h but not exported"
 
@@ -66,6 +66,22 @@ def test_argument_validation_without_device(lib):
     assert mixed(P, ptrs, 0x5000, 4, X, Y, 16, 128, 0, 128, None) == 0
     none = (ctypes.c_void_p * 5)()
     assert mixed(P, none, 0x5000, 4, X, Y, 16, 128, 1, 128, None) == -1
+    # asymmetric entry points: same checks, the offset set may be absent but not misaligned
+    Z = 0x6000
+    goff = lib.bcq_gemv_offset
+    assert goff(P, None, Z, 2, X, Y, 16, 128, 1, 128, None) == -1
+    assert goff(P, S, Z, 9, X, Y, 16, 128, 1, 128, None) == -2
+    assert goff(P, S, Z, 2, X, Y, 16, 192, 1, 128, None) == -3
+    assert goff(P, S, Z + 2, 2, X, Y, 16, 128, 1, 128, None) == -4
+    assert goff(P, S, Z, 2, X, Y, 16, 128, 0, 128, None) == 0
+    assert goff(P, S, None, 2, X, Y, 16, 128, 0, 128, None) == 0
+    moff = lib.bcq_gemm_mixed_offset
+    zptrs = (ctypes.c_void_p * 5)(None, None, Z, None, None)
+    assert moff(P, ptrs, zptrs, None, 4, X, Y, 16, 128, 1, 128, None) == -1
+    assert moff(P, ptrs, zptrs, 0x5000, 4, X, Y, 16, 128, 0, 128, None) == 0
+    assert moff(P, ptrs, None, 0x5000, 4, X, Y, 16, 128, 0, 128, None) == 0
+    bad = (ctypes.c_void_p * 5)(None, None, Z + 8, None, None)
+    assert moff(P, ptrs, bad, 0x5000, 4, X, Y, 16, 128, 1, 128, None) == -4
     assert lib.bcq_pack(0x1000, 0x2000, 4, 8, 48, None) == -3
     assert lib.bcq_pack(0x1000, 0x2000, 0, 8, 64, None) == -2
     assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1

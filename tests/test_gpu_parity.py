@@ -137,3 +137,66 @@ def test_auto_dispatch_by_batch(gpu):
     p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
     used, _ = gpu.check_mixed(dl, p_req, syn.make_x(40, 2048, seed=(170, 4)), "auto")
     assert used == "plane_mfma"
+
+
+# ----------------------------------------------------------------------------
+# asymmetric scheme: offsets per (row, group) and precision, every kernel family
+# ----------------------------------------------------------------------------
+OFFSET_SHAPES = [(16, 1024), (37, 2048), (131, 4096), (20, 17920), (33, 1792), (50, 28672)]
+
+
+@pytest.mark.parametrize("m,n", OFFSET_SHAPES)
+def test_offsets_plane_mfma(gpu, m, n):
+    layer = syn.make_layer(m, n, seed=(180, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    zs = {p: syn.make_offsets(p, m, n, seed=(180, m)) for p in (1, 2, 3, 4)}
+    for batch in (1, 2, 4, 7):
+        x = syn.make_x(batch, n, seed=(180, batch))
+        for p in (1, 2, 3, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "plane_mfma", offsets=zs[p])
+            assert used == "plane_mfma"
+    for batch in (1, 6, 16):
+        x = syn.make_x(batch, n, seed=(181, batch))
+        p_req = syn.make_p_req(batch, 1, 4, seed=(181, batch))
+        gpu.check_mixed(dl, p_req, x, "plane_mfma", offsets_by_p=zs)
+        gpu.check_mixed(dl, p_req, x, "plane_mfma", offsets_by_p={2: zs[2], 4: zs[4]})   # precisions 1 and 3 have none
+
+
+@pytest.mark.parametrize("m,n,group", [(37, 2048, 128), (33, 640, 128), (9, 512, 64), (5, 96, 32)])
+def test_offsets_sign_select(gpu, m, n, group):
+    layer = syn.make_layer(m, n, group=group, seed=(182, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    zs = {p: syn.make_offsets(p, m, n, group, seed=(182, m)) for p in (1, 2, 3, 4)}
+    for batch in (1, 5):
+        x = syn.make_x(batch, n, seed=(182, batch))
+        for p in (1, 3, 4):
+            gpu.check_gemv(dl, p, x, "sign_select", group, offsets=zs[p])
+        p_req = syn.make_p_req(batch, 1, 4, seed=(182, batch))
+        gpu.check_mixed(dl, p_req, x, "sign_select", group, offsets_by_p={1: zs[1], 3: zs[3]})
+
+
+@pytest.mark.parametrize("m,n", [(37, 2048), (131, 4096), (64, 640)])
+def test_offsets_dequant_mfma(gpu, m, n):
+    layer = syn.make_layer(m, n, seed=(183, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 64, 100, 256):
+        x = syn.make_x(batch, n, seed=(183, batch))
+        for p in (1, 2, 4):
+            z = syn.make_offsets(p, m, n, seed=(183, m))
+            used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma", offsets=z)
+            assert used == "dequant_mfma"
+
+
+def test_offsets_change_the_result_and_null_is_symmetric(gpu):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    layer = syn.make_layer(48, 2048, seed=(184, 0))
+    dl = gpu.DeviceLayer(layer)
+    x = gpu.to_dev(syn.make_x(3, 2048, seed=(184, 0)))
+    z = gpu.to_dev(syn.make_offsets(3, 48, 2048, seed=(184, 0)))
+    y_sym = bcq.bcq_gemv(dl.planes, dl.scales[3], 3, x)
+    y_off = bcq.bcq_gemv(dl.planes, dl.scales[3], 3, x, offsets=z)
+    y_zero = bcq.bcq_gemv(dl.planes, dl.scales[3], 3, x, offsets=torch.zeros_like(z))
+    assert not torch.equal(y_sym, y_off)
+    assert torch.equal(y_sym, y_zero)

@@ -163,9 +163,39 @@ def run_suite(args, torch, bcq, syn, dev):
         for (_, m, n) in syn.PHI4_14B_SHAPES:
             bench_shape(m, n, (1,), PRECISIONS)
     elif args.suite == "fused":
-        # q/k/v and gate/up stored as one matrix each (they share x): 4 launches per decoder layer instead of 7
-        for (m, n) in ((4096 + 1024 + 1024, 4096), (4096, 4096), (2 * 14336, 4096), (4096, 14336)):
-            bench_shape(m, n, (1,), PRECISIONS)
+        # The linear layers of one Llama-3-8B decoder layer, batch 1: seven bcq_gemv calls against four
+        # calls in which q/k/v and gate/up (same activations) go through bcq_gemv_multi as one launch each.
+        shapes = {"q": (4096, 4096), "k": (1024, 4096), "v": (1024, 4096), "o": (4096, 4096),
+                  "gate": (14336, 4096), "up": (14336, 4096), "down": (4096, 14336)}
+        copies = 8                                                   # 8 x 218 MB of planes: cold for the last-level cache
+        sets = [{name: device_layer(m, n) for name, (m, n) in shapes.items()} for _ in range(copies)]
+        x4k = torch.randn((1, 4096), device=dev, generator=gen).half()
+        x14k = torch.randn((1, 14336), device=dev, generator=gen).half()
+        ys = {name: torch.empty((1, m), dtype=torch.float16, device=dev) for name, (m, n) in shapes.items()}
+        for p in PRECISIONS:
+            def separate():
+                for c in range(copies):
+                    L = sets[c]
+                    for name in ("q", "k", "v", "o", "gate", "up"):
+                        bcq.bcq_gemv(L[name][0], L[name][1][p], p, x4k, ys[name])
+                    bcq.bcq_gemv(L["down"][0], L["down"][1][p], p, x14k, ys["down"])
+
+            def fused():
+                for c in range(copies):
+                    L = sets[c]
+                    bcq.bcq_gemv_multi([L[k][0] for k in ("q", "k", "v")], [L[k][1][p] for k in ("q", "k", "v")], p, x4k,
+                                       [ys[k] for k in ("q", "k", "v")])
+                    bcq.bcq_gemv(L["o"][0], L["o"][1][p], p, x4k, ys["o"])
+                    bcq.bcq_gemv_multi([L[k][0] for k in ("gate", "up")], [L[k][1][p] for k in ("gate", "up")], p, x4k,
+                                       [ys[k] for k in ("gate", "up")])
+                    bcq.bcq_gemv(L["down"][0], L["down"][1][p], p, x14k, ys["down"])
+            by = sum(syn.algorithmic_bytes(m, n, p, 1) for (m, n) in shapes.values())
+            us_sep = timed_graph(separate) * 1e3 / copies
+            us_fus = timed_graph(fused) * 1e3 / copies
+            rows.append({"workload": "linear layers of one Llama-3-8B decoder layer, batch 1", "p": p,
+                         "seven_calls_us": round(us_sep, 2), "four_calls_us": round(us_fus, 2),
+                         "seven_calls_GBps": round(by / us_sep / 1e3, 1), "four_calls_GBps": round(by / us_fus / 1e3, 1),
+                         "pct_of_hbm_peak_four_calls": round(100 * by / us_fus / 1e3 / HBM_PEAK_GBS, 2)})
     else:
         for (_, m, n) in syn.LLAMA3_70B_SHAPES:
             bench_shape(m, n, (1, 16, 64, 256), PRECISIONS)
@@ -265,6 +295,31 @@ def main():
                          "effective_GBps": round(bytes_per_p[p] / (ms * 1e-3) / 1e9, 1),
                          "pct_of_hbm_peak": round(100 * bytes_per_p[p] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
 
+    # ---- the same 21 products with q/k/v and gate/up handed to bcq_gemv_multi (12 launches per step):
+    # a secondary figure; `value` above stays with one bcq_gemv call per product
+    idx = {name: li for li, (name, _, _) in enumerate(layers)}
+    groups = [("q_proj", "k_proj", "v_proj"), ("o_proj",), ("gate_proj", "up_proj"), ("down_proj",)]
+
+    def run_step_multi(c):
+        for p in PRECISIONS:
+            for names in groups:
+                lis = [idx[nm] for nm in names]
+                n = layers[lis[0]][2]
+                if len(lis) == 1:
+                    planes, scales = dev_sets[c][lis[0]]
+                    bcq.bcq_gemv(planes, scales[p], p, xs[n], ys[lis[0]])
+                else:
+                    bcq.bcq_gemv_multi([dev_sets[c][li][0] for li in lis], [dev_sets[c][li][1][p] for li in lis], p, xs[n],
+                                       [ys[li] for li in lis])
+    run_step_multi(0)
+    torch.cuda.synchronize()
+    multi_fns = [lambda c=c: run_step_multi(c) for c in range(copies)] if args.no_graph else \
+                [capture(lambda c=c: run_step_multi(c)).replay for c in range(copies)]
+    ms_multi = timed(multi_fns, args.steps, args.warmup)
+    multi_call = {"what": "the same 21 products, q/k/v and gate/up through bcq_gemv_multi: 12 launches per step",
+                  "value": round(bytes_per_step / (ms_multi * 1e-3) / 1e9, 1), "unit": "GB/s", "ms_per_step": round(ms_multi, 5),
+                  "pct_of_hbm_peak": round(100 * bytes_per_step / (ms_multi * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+
     # ---- roofline of the dominant kernel: gate/up-shaped layer at p = 4 -----------------------
     def kernel_time_us(li, p, launches=64):
         """Mean duration of back-to-back launches of one (layer, p), rotating over the copies."""
@@ -331,14 +386,17 @@ def main():
     cpu_baseline = None
     if not args.skip_cpu_baseline:
         import oracle
+        reps = 8                                     # about 10 s of CPU work on the box's 16 cores
         t0 = time.perf_counter()
-        for p in PRECISIONS:
-            for li, (_, m, n) in enumerate(layers):
-                oracle.gemv(host_copy0[li].planes, host_copy0[li].scales[p], xs_host[n])
-        dt = time.perf_counter() - t0
+        for _ in range(reps):
+            for p in PRECISIONS:
+                for li, (_, m, n) in enumerate(layers):
+                    oracle.gemv(host_copy0[li].planes, host_copy0[li].scales[p], xs_host[n])
+        dt = (time.perf_counter() - t0) / reps
         cpu_baseline = {"value": round(bytes_per_step / dt / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(),
-                        "kind": "oracle", "seconds": round(dt, 2),
-                        "sample": "one step: the 7 Llama-3-8B layers at p=2,3,4, batch 1 (21 oracle products, float64)"}
+                        "kind": "oracle", "seconds": round(dt * reps, 2),
+                        "sample": f"{reps} steps of the 7 Llama-3-8B layers at p=2,3,4, batch 1 "
+                                  f"({21 * reps} oracle products, float64), one weight copy"}
 
     out = {
         "metric": "bcq_gemv effective HBM GB/s, Llama-3-8B linear set, batch 1, p=2/3/4",
@@ -353,6 +411,7 @@ def main():
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "bytes_per_step": bytes_per_step,
         "per_precision": per_p,
+        "multi_call": multi_call,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }

@@ -46,6 +46,7 @@ extern "C" {
 typedef uint16_t bcq_half;
 
 #define BCQ_MAX_PLANES 8
+#define BCQ_MAX_MULTI 4   /* matrices per bcq_gemv_multi call */
 
 typedef enum {
     BCQ_OK = 0,
@@ -148,6 +149,24 @@ int bcq_gemm_mixed_offset(const uint32_t *planes, const bcq_half *const *scales_
                           const int32_t *p_req, int p_max,
                           const bcq_half *x, bcq_half *y,
                           int64_t m, int64_t n, int batch, int group, void *stream);
+
+/*
+ * bcq_gemv_multi -- several weight matrices applied to the SAME activations at
+ * the same precision in one call (the q/k/v and the gate/up projections of a
+ * decoder layer; section 4.4 measures whole decoding steps made of such layers).
+ * Equivalent to `count` calls of bcq_gemv, bit for bit, but small-batch
+ * problems run as a single kernel launch.
+ *   count      1 .. BCQ_MAX_MULTI
+ *   planes     HOST array of `count` device pointers, matrix k: [>= p][m[k]][n/32]
+ *   scales_p   HOST array of `count` device pointers, matrix k: [p][m[k]][n/group]
+ *   m          HOST array of `count` row counts
+ *   y          HOST array of `count` device pointers, matrix k: [batch][m[k]] (written)
+ *   x          bcq_half [batch][n], shared
+ * Errors as for bcq_gemv (the first offending matrix decides).
+ */
+int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *const *scales_p, const int64_t *m,
+                   bcq_half *const *y, int p, const bcq_half *x,
+                   int64_t n, int batch, int group, void *stream);
 
 #ifdef __cplusplus
 }

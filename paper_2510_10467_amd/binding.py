@@ -45,6 +45,8 @@ def lib() -> ctypes.CDLL:
         L.bcq_unpack.argtypes = [vp, vp, i32, i64, i64, vp]
         L.bcq_gemv.argtypes = [vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
         L.bcq_gemm_mixed.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
+        L.bcq_gemv_multi.argtypes = [i32, vp, vp, vp, vp, i32, vp, i64, i32, i32, vp]
+        L.bcq_gemv_multi.restype = i32
         L.bcq_gemv_offset.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
         L.bcq_gemm_mixed_offset.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
         for f in (L.bcq_select_kernel, L.bcq_pack, L.bcq_unpack, L.bcq_gemv, L.bcq_gemm_mixed, L.bcq_gemv_offset,
@@ -127,6 +129,34 @@ def bcq_gemv(planes: torch.Tensor, scales_p: torch.Tensor, p: int, x: torch.Tens
                           _dev(x, torch.float16, "x"), _dev(y, torch.float16, "y"), m, n, batch, group, _stream()),
            "bcq_gemv")
     return y
+
+
+def bcq_gemv_multi(planes: list, scales_p: list, p: int, x: torch.Tensor, ys: list | None = None, group: int = 128) -> list:
+    """Several matrices (same n and precision) applied to the same activations in one call: the q/k/v or
+    gate/up projections of a decoder layer.  Returns the list of outputs, bit for bit those of bcq_gemv."""
+    count = len(planes)
+    batch, n = x.shape
+    if len(scales_p) != count or (ys is not None and len(ys) != count):
+        raise ValueError("bcq_gemv_multi: lists of different lengths")
+    ms = []
+    for k in range(count):
+        _, m, words = planes[k].shape
+        if words * 32 != n or scales_p[k].shape != (p, m, n // group) or planes[k].shape[0] < p:
+            raise ValueError(f"bcq_gemv_multi: inconsistent shapes for matrix {k}")
+        ms.append(m)
+    if ys is None:
+        ys = [torch.empty((batch, m), dtype=torch.float16, device=x.device) for m in ms]
+    pp = (ctypes.c_void_p * count)(*[_dev(t, torch.int32, f"planes[{k}]") for k, t in enumerate(planes)])
+    sp = (ctypes.c_void_p * count)(*[_dev(t, torch.float16, f"scales_p[{k}]") for k, t in enumerate(scales_p)])
+    yp = (ctypes.c_void_p * count)(*[_dev(t, torch.float16, f"ys[{k}]") for k, t in enumerate(ys)])
+    mp = (ctypes.c_int64 * count)(*ms)
+    for k in range(count):
+        if ys[k].shape != (batch, ms[k]):
+            raise ValueError(f"bcq_gemv_multi: ys[{k}] has the wrong shape")
+    _check(lib().bcq_gemv_multi(count, ctypes.cast(pp, ctypes.c_void_p), ctypes.cast(sp, ctypes.c_void_p),
+                                ctypes.cast(mp, ctypes.c_void_p), ctypes.cast(yp, ctypes.c_void_p), p,
+                                _dev(x, torch.float16, "x"), n, batch, group, _stream()), "bcq_gemv_multi")
+    return ys
 
 
 def bcq_gemm_mixed(planes: torch.Tensor, scales_by_p: dict, p_req: torch.Tensor, x: torch.Tensor,

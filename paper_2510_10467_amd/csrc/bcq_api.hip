@@ -21,10 +21,10 @@ int check_shape(int64_t m, int64_t n, int batch, int group)
     return BCQ_OK;
 }
 
-int run(const bcq::GemmArgs &a, hipStream_t stream)
+// The kernel family a problem runs on: the forced one, or the default choice.
+int choose(const bcq::GemmArgs &a)
 {
     using namespace bcq;
-    hipError_t err;
     int choice = g_forced;
     if (choice == BCQ_KERNEL_AUTO) {
         // Dequantising a weight tile costs the same whatever the number of requests that then use it, and a
@@ -36,7 +36,14 @@ int run(const bcq::GemmArgs &a, hipStream_t stream)
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         else choice = BCQ_KERNEL_SIGN_SELECT;
     }
-    switch (choice) {
+    return choice;
+}
+
+int run(const bcq::GemmArgs &a, hipStream_t stream)
+{
+    using namespace bcq;
+    hipError_t err;
+    switch (choose(a)) {
     case BCQ_KERNEL_SIGN_SELECT:
         if (!sign_select_supports(a)) return BCQ_ERR_VARIANT;
         err = sign_select_launch(a, stream);
@@ -174,6 +181,42 @@ int bcq_gemm_mixed(const uint32_t *planes, const bcq_half *const *scales_by_p, c
                    const bcq_half *x, bcq_half *y, int64_t m, int64_t n, int batch, int group, void *stream)
 {
     return bcq_gemm_mixed_offset(planes, scales_by_p, nullptr, p_req, p_max, x, y, m, n, batch, group, stream);
+}
+
+int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *const *scales_p, const int64_t *m,
+                   bcq_half *const *y, int p, const bcq_half *x, int64_t n, int batch, int group, void *stream)
+{
+    if (count < 1 || count > BCQ_MAX_MULTI) return BCQ_ERR_BAD_SHAPE;
+    if (!planes || !scales_p || !m || !y || !x) return BCQ_ERR_NULL;
+    if (p < 1 || p > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
+    bcq::GemmArgs mats[BCQ_MAX_MULTI] = {};
+    for (int k = 0; k < count; ++k) {
+        if (!planes[k] || !scales_p[k] || !y[k]) return BCQ_ERR_NULL;
+        if (int rc = check_shape(m[k], n, batch, group)) return rc;
+        if (!aligned(planes[k], 16) || !aligned(scales_p[k], 16) || !aligned(x, 16) || !aligned(y[k], 2)) return BCQ_ERR_ALIGN;
+        bcq::GemmArgs &a = mats[k];
+        a.planes = planes[k];
+        a.scales[p] = reinterpret_cast<const _Float16 *>(scales_p[k]);
+        a.uniform_p = p;
+        a.p_max = p;
+        a.x = reinterpret_cast<const _Float16 *>(x);
+        a.y = reinterpret_cast<_Float16 *>(y[k]);
+        a.m = m[k];
+        a.n = n;
+        a.batch = batch;
+        a.group = group;
+    }
+    if (batch == 0) return BCQ_OK;
+    // one launch when every matrix would run on the plane-wise kernel anyway
+    bool together = count > 1 && bcq::plane_mfma_supports_multi(mats, count);
+    for (int k = 0; together && k < count; ++k) together = choose(mats[k]) == BCQ_KERNEL_PLANE_MFMA;
+    if (together) {
+        g_last = "plane_mfma";
+        return bcq::plane_mfma_launch_multi(mats, count, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
+    }
+    for (int k = 0; k < count; ++k)
+        if (int rc = run(mats[k], static_cast<hipStream_t>(stream))) return rc;
+    return BCQ_OK;
 }
 
 }  // extern "C"

@@ -44,6 +44,10 @@ hipError_t sign_select_launch(const GemmArgs &a, hipStream_t stream);
 bool plane_mfma_supports(const GemmArgs &a);
 hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream);
 
+// `count` matrices that share n, precision, batch and activations as ONE launch
+bool plane_mfma_supports_multi(const GemmArgs *mats, int count);
+hipError_t plane_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t stream);
+
 bool dequant_mfma_supports(const GemmArgs &a);
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream);
 

@@ -69,6 +69,13 @@ struct PlaneMfmaParams {
     int batch, p_max, uniform_p;
     int KS, RB, nchunk, nslices;
     int glast;                              // groups in the last slice (8 unless n is not a multiple of 1024)
+    // several matrices with the same n, p and activations in one launch (MULTI kernels): matrix k owns the
+    // row blocks mat_blk0[k] .. mat_blk0[k+1]-1 of the grid; unused entries hold the total
+    const unsigned char *mat_planes[BCQ_MAX_MULTI];
+    const unsigned char *mat_scales[BCQ_MAX_MULTI];
+    _Float16 *mat_y[BCQ_MAX_MULTI];
+    uint32_t mat_m[BCQ_MAX_MULTI];
+    uint32_t mat_blk0[BCQ_MAX_MULTI];
     uint32_t ntiles, nwg_rows;              // batch tiles of four requests; row-block groups (workgroups per tile)
     float inv_span;                         // 1 / (8 * ntiles)
     float inv_ks;                           // 1 / KS
@@ -358,9 +365,10 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
 // workgroup leaves a wave (128), and their operand image limits the waves per CU anyway: they stop at 8.
 __host__ __device__ constexpr int max_waves(int NB, bool mixed) { return NB == 4 && mixed ? 8 : 16; }
 
-template <int P, int NB, bool MIXED, bool OFFSET>
-__global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(PlaneMfmaParams pr)
+template <int P, int NB, bool MIXED, bool OFFSET, bool MULTI = false>
+__global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(PlaneMfmaParams pr_in)
 {
+    PlaneMfmaParams pr = pr_in;               // MULTI kernels overwrite the per-matrix fields below
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
@@ -384,6 +392,18 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
         tile = rem >> 3;
         wg = span_index * 8 + (rem & 7);                            // row-block group of this workgroup
         if (wg >= pr.nwg_rows) return;                              // padding of the last span (whole workgroup)
+    }
+    if constexpr (MULTI) {
+        // which matrix this row block belongs to (row blocks are never shared: RB == 1), picked by comparison
+        static_assert(BCQ_MAX_MULTI == 4, "the selection below is written for four matrices");
+        const bool g1 = wg >= pr_in.mat_blk0[1], g2 = wg >= pr_in.mat_blk0[2], g3 = wg >= pr_in.mat_blk0[3];
+        pr.planes = g3 ? pr_in.mat_planes[3] : g2 ? pr_in.mat_planes[2] : g1 ? pr_in.mat_planes[1] : pr_in.mat_planes[0];
+        pr.scales[P] = g3 ? pr_in.mat_scales[3] : g2 ? pr_in.mat_scales[2] : g1 ? pr_in.mat_scales[1] : pr_in.mat_scales[0];
+        pr.y = g3 ? pr_in.mat_y[3] : g2 ? pr_in.mat_y[2] : g1 ? pr_in.mat_y[1] : pr_in.mat_y[0];
+        pr.m = g3 ? pr_in.mat_m[3] : g2 ? pr_in.mat_m[2] : g1 ? pr_in.mat_m[1] : pr_in.mat_m[0];
+        wg -= g3 ? pr_in.mat_blk0[3] : g2 ? pr_in.mat_blk0[2] : g1 ? pr_in.mat_blk0[1] : 0u;
+        pr.plane_stride = pr.m * pr.row_stride;
+        pr.scale_plane_stride = pr.m * pr.scale_row_stride;
     }
     const int b0 = tile * kMaxBatchTile;
     const int nb = NB > 1 ? min(NB, pr.batch - b0) : 1;
@@ -485,7 +505,7 @@ struct Plan {
     size_t lds_bytes;
 };
 
-Plan make_plan(const GemmArgs &a)
+Plan make_plan(const GemmArgs &a, bool share_row_blocks = true)
 {
     const int nslices = (int)((a.n + kSliceCols - 1) / kSliceCols);
     Plan pl;
@@ -505,7 +525,7 @@ Plan make_plan(const GemmArgs &a)
     // conversion work of a tile, at the price of workgroup barriers.
     pl.RB = 1;
     const int64_t row_blocks = (a.m + 15) / 16;
-    if (a.batch > kMaxBatchTile && row_blocks < 512)
+    if (share_row_blocks && a.batch > kMaxBatchTile && row_blocks < 512)
         while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= wave_cap && row_blocks / (pl.RB * 2) >= 128) pl.RB *= 2;
     pl.lds_bytes = (size_t)lds_total(pl.NB, KS, pl.RB);
     return pl;
@@ -533,6 +553,17 @@ hipError_t launch_nb(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &p
     case 2: return launch_one(plane_mfma_kernel<2, NB, false, OFFSET>, pr, pl, grid, block, stream);
     case 3: return launch_one(plane_mfma_kernel<3, NB, false, OFFSET>, pr, pl, grid, block, stream);
     default: return launch_one(plane_mfma_kernel<4, NB, false, OFFSET>, pr, pl, grid, block, stream);
+    }
+}
+
+template <int NB>
+hipError_t launch_multi_nb(int p, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
+{
+    switch (p) {
+    case 1: return launch_one(plane_mfma_kernel<1, NB, false, false, true>, pr, pl, grid, block, stream);
+    case 2: return launch_one(plane_mfma_kernel<2, NB, false, false, true>, pr, pl, grid, block, stream);
+    case 3: return launch_one(plane_mfma_kernel<3, NB, false, false, true>, pr, pl, grid, block, stream);
+    default: return launch_one(plane_mfma_kernel<4, NB, false, false, true>, pr, pl, grid, block, stream);
     }
 }
 
@@ -598,6 +629,61 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     case 1: return launch_nb<1, false>(a, pr, pl, grid, block, stream);
     case 2: return launch_nb<2, false>(a, pr, pl, grid, block, stream);
     default: return launch_nb<4, false>(a, pr, pl, grid, block, stream);
+    }
+}
+
+// Several matrices (same n, precision, batch and activations, no offsets) as one launch: the grid is
+// the concatenation of their row blocks.
+bool plane_mfma_supports_multi(const GemmArgs *mats, int count)
+{
+    if (count < 2 || count > BCQ_MAX_MULTI) return false;
+    int64_t row_blocks = 0;
+    for (int k = 0; k < count; ++k) {
+        const GemmArgs &a = mats[k];
+        if (!plane_mfma_supports(a) || a.uniform_p < 1 || a.offsets[a.uniform_p]) return false;
+        if (a.n != mats[0].n || a.uniform_p != mats[0].uniform_p || a.batch != mats[0].batch || a.x != mats[0].x) return false;
+        row_blocks += (a.m + 15) / 16;
+    }
+    return (row_blocks + 8) * ((mats[0].batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);
+}
+
+hipError_t plane_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t stream)
+{
+    const GemmArgs &a = mats[0];
+    const Plan pl = make_plan(a, false);      // a row block belongs to one matrix: no sharing of workgroups
+    PlaneMfmaParams pr{};
+    pr.x = reinterpret_cast<const unsigned char *>(a.x);
+    pr.row_stride = (uint32_t)(a.n / 8);
+    pr.scale_row_stride = (uint32_t)((a.n / 128) * 2);
+    pr.x_stride = (uint32_t)(a.n * 2);
+    pr.batch = a.batch;
+    pr.p_max = a.p_max;
+    pr.uniform_p = a.uniform_p;
+    pr.KS = pl.KS;
+    pr.RB = 1;
+    pr.nchunk = pl.nchunk;
+    pr.nslices = (int)((a.n + kSliceCols - 1) / kSliceCols);
+    pr.glast = (int)((a.n / 128 - 1) % kSliceGroups) + 1;
+    uint32_t blk = 0;
+    for (int k = 0; k < BCQ_MAX_MULTI; ++k) {
+        pr.mat_blk0[k] = blk;                 // unused entries: the total, which no row block reaches
+        if (k >= count) continue;
+        pr.mat_planes[k] = reinterpret_cast<const unsigned char *>(mats[k].planes);
+        pr.mat_scales[k] = reinterpret_cast<const unsigned char *>(mats[k].scales[a.uniform_p]);
+        pr.mat_y[k] = mats[k].y;
+        pr.mat_m[k] = (uint32_t)mats[k].m;
+        blk += (uint32_t)((mats[k].m + 15) / 16);
+    }
+    pr.ntiles = (uint32_t)((a.batch + kMaxBatchTile - 1) / kMaxBatchTile);
+    pr.nwg_rows = blk;
+    dim3 grid(pl.NB == 1 ? pr.nwg_rows : (pr.nwg_rows + 7) / 8 * 8 * pr.ntiles);
+    pr.inv_span = 1.0f / (float)(8 * pr.ntiles);
+    pr.inv_ks = 1.0f / (float)pl.KS;
+    dim3 block(64 * pl.KS);
+    switch (pl.NB) {
+    case 1: return launch_multi_nb<1>(a.uniform_p, pr, pl, grid, block, stream);
+    case 2: return launch_multi_nb<2>(a.uniform_p, pr, pl, grid, block, stream);
+    default: return launch_multi_nb<4>(a.uniform_p, pr, pl, grid, block, stream);
     }
 }
 

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_gemv_offset", "bcq_gemm_mixed_offset",
+    assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_gemv_offset", "bcq_gemm_mixed_offset", "bcq_gemv_multi",
             "bcq_strerror", "bcq_select_kernel", "bcq_last_kernel"} <= set(names)
     for name in names:
         assert hasattr(lib, name), f"{name} declared in bcq.h but not exported"
@@ -82,6 +82,21 @@ def test_argument_validation_without_device(lib):
     assert moff(P, ptrs, None, 0x5000, 4, X, Y, 16, 128, 0, 128, None) == 0
     bad = (ctypes.c_void_p * 5)(None, None, Z + 8, None, None)
     assert moff(P, ptrs, bad, 0x5000, 4, X, Y, 16, 128, 1, 128, None) == -4
+    # several matrices in one call
+    multi = lib.bcq_gemv_multi
+    pp = (ctypes.c_void_p * 2)(P, P + 0x100)
+    sp = (ctypes.c_void_p * 2)(S, S + 0x100)
+    yp = (ctypes.c_void_p * 2)(Y, Y + 0x100)
+    mm = (ctypes.c_int64 * 2)(16, 32)
+    assert multi(0, pp, sp, mm, yp, 2, X, 128, 1, 128, None) == -3
+    assert multi(5, pp, sp, mm, yp, 2, X, 128, 1, 128, None) == -3
+    assert multi(2, None, sp, mm, yp, 2, X, 128, 1, 128, None) == -1
+    assert multi(2, pp, sp, mm, yp, 0, X, 128, 1, 128, None) == -2
+    assert multi(2, pp, sp, mm, yp, 2, X, 192, 1, 128, None) == -3
+    assert multi(2, pp, sp, (ctypes.c_int64 * 2)(16, 0), yp, 2, X, 128, 1, 128, None) == -3
+    assert multi(2, (ctypes.c_void_p * 2)(P, None), sp, mm, yp, 2, X, 128, 1, 128, None) == -1
+    assert multi(2, (ctypes.c_void_p * 2)(P, P + 4), sp, mm, yp, 2, X, 128, 1, 128, None) == -4
+    assert multi(2, pp, sp, mm, yp, 2, X, 128, 0, 128, None) == 0
     assert lib.bcq_pack(0x1000, 0x2000, 4, 8, 48, None) == -3
     assert lib.bcq_pack(0x1000, 0x2000, 0, 8, 64, None) == -2
     assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1

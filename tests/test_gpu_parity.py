@@ -200,3 +200,42 @@ def test_offsets_change_the_result_and_null_is_symmetric(gpu):
     y_zero = bcq.bcq_gemv(dl.planes, dl.scales[3], 3, x, offsets=torch.zeros_like(z))
     assert not torch.equal(y_sym, y_off)
     assert torch.equal(y_sym, y_zero)
+
+
+# ----------------------------------------------------------------------------
+# several matrices on the same activations in one call (q/k/v, gate/up)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("ms,n", [((64, 16, 16), 1024), ((37, 50), 2048), ((131, 16, 75, 1), 4096), ((40, 24), 17920), ((20,), 1024)])
+def test_gemv_multi_equals_separate_calls(gpu, oracle, ms, n):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    layers = [syn.make_layer(m, n, seed=(190, k, m), signed=True) for k, m in enumerate(ms)]
+    dls = [gpu.DeviceLayer(layer) for layer in layers]
+    for batch in (1, 3, 4, 9):
+        xh = syn.make_x(batch, n, seed=(190, batch))
+        x = gpu.to_dev(xh)
+        for p in (1, 2, 3, 4):
+            ys = bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[p] for d in dls], p, x)
+            torch.cuda.synchronize()
+            assert bcq.last_kernel() == "plane_mfma"
+            for d, y in zip(dls, ys):
+                y_ref, a_ref = oracle.gemv(d.layer.planes, d.layer.scales[p], xh)
+                gpu.assert_within_tolerance(y, y_ref, a_ref, f"bcq_gemv_multi ms={ms} n={n} p={p} batch={batch}")
+                assert torch.equal(y, bcq.bcq_gemv(d.planes, d.scales[p], p, x)), "multi differs from the separate call"
+
+
+def test_gemv_multi_falls_back_to_separate_launches(gpu, oracle):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    # n shorter than a K slice: the generic kernel runs, one launch per matrix
+    layers = [syn.make_layer(m, 640, seed=(191, m)) for m in (16, 40)]
+    dls = [gpu.DeviceLayer(layer) for layer in layers]
+    xh = syn.make_x(2, 640, seed=(191, 0))
+    ys = bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[3] for d in dls], 3, gpu.to_dev(xh))
+    torch.cuda.synchronize()
+    assert bcq.last_kernel() == "sign_select"
+    for d, y in zip(dls, ys):
+        y_ref, a_ref = oracle.gemv(d.layer.planes, d.layer.scales[3], xh)
+        gpu.assert_within_tolerance(y, y_ref, a_ref, "bcq_gemv_multi fallback")

@@ -11,8 +11,9 @@
 //   * lane (row, kq) of a wave holds word kq of its row's group from each plane plus the group's
 //     scales (also one group ahead).  Matrix step t covers the columns 32 kq + 8 t + j of the group
 //     (a permutation of K that the activation operand follows), so for each step the lane takes
-//     byte t of each plane word, looks it up in a 256-entry LDS table of eight +-1.0 binary16
-//     values, accumulates w_j = sum_i alpha_i * (+-1) in fp32 (one mixed-precision FMA per column
+//     byte t of each plane word, looks its two nibbles up in a 16-entry LDS table of four +-1.0
+//     binary16 values (each entry sits in banks of its own and equal addresses are broadcast, so
+//     these reads never conflict, unlike those of a 256-entry table of eight values), accumulates w_j = sum_i alpha_i * (+-1) in fp32 (one mixed-precision FMA per column
 //     and plane), starting from the group's offset in the asymmetric scheme (section 4.1), and
 //     rounds once to binary16: that IS the B operand of v_mfma_f32_16x16x32_f16;
 //   * the wave multiplies its 16 x 128 weight tile with all TB requests, reading each activation
@@ -23,10 +24,10 @@
 // accumulator.  One barrier per group.
 //
 // A wave cannot overlap its own vector, matrix and LDS instructions, and with one wave per SIMD every
-// latency is exposed.  So, LDS and registers permitting (TB <= 128), a workgroup has TWO such teams of
-// four waves: both work on the same rows and requests, team k on the groups k, k+2, k+4, ... with
-// activation tiles and accumulators of its own; the teams meet at every barrier and add their
-// accumulators through LDS at the end.
+// latency is exposed.  So, LDS and registers permitting, a workgroup has several such teams of four
+// waves (four for TB = 64, two for TB = 128): all work on the same rows and requests, team k on the
+// groups k, k + TEAMS, ... with activation tiles and accumulators of its own; the teams meet at every
+// barrier and add their accumulators through LDS at the end.
 #include <hip/hip_runtime.h>
 
 #include "bcq_internal.hpp"
@@ -35,12 +36,14 @@ namespace bcq {
 namespace {
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRowsPerWg = 64;              // 4 waves x 16 rows
 constexpr int kMaxP = 4;
-constexpr int kLutBytes = 256 * 16;
+constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2 + 16;    // padded LDS row of one request's 128 activations: rows start 4 banks apart
 
 constexpr int x_tile_bytes(int nu) { return 64 * nu * kXRowBytes; }
@@ -88,16 +91,16 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
     const uint32_t row0 = blockIdx.x * kRowsPerWg + wave * 16;
     const int b0 = blockIdx.y * (64 * NU);    // first request of the workgroup
 
-    // table: byte -> eight binary16 values, +1.0 where the bit is set, -1.0 where it is clear
-    {
-        uint32_t e[4];
+    // table: nibble -> four binary16 values, +1.0 where the bit is set, -1.0 where it is clear
+    if (team == 0 && tid < 16) {
+        uint32_t e[2];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < 2; ++c) {
             const uint32_t lo = ((tid >> (2 * c)) & 1) ? 0x3C00u : 0xBC00u;
             const uint32_t hi = ((tid >> (2 * c + 1)) & 1) ? 0x3C00u : 0xBC00u;
             e[c] = lo | (hi << 16);
         }
-        if (team == 0) *reinterpret_cast<u32x4 *>(lut + tid * 16) = u32x4{e[0], e[1], e[2], e[3]};
+        *reinterpret_cast<u32x2 *>(lut + tid * 8) = u32x2{e[0], e[1]};
     }
 
     // lane offsets; rows and requests past the end repeat the last one (their results are not stored)
@@ -173,6 +176,14 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
             if (g + 2 * TEAMS < a.ngroups) fetch_x(nxt, g + 2 * TEAMS);
         }
         const unsigned char *xa_cur = xa_lane + buf * x_tile_bytes(NU);
+        // table offsets of all low and all high nibbles of a plane word at once: byte t of `lo8` (`hi8`) is
+        // eight times the low (high) nibble of byte t
+        uint32_t lo8[P], hi8[P];
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            lo8[i] = (w[i] << 3) & 0x78787878u;
+            hi8[i] = (w[i] >> 1) & 0x78787878u;
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             float wf[8];
@@ -180,10 +191,13 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
             for (int j = 0; j < 8; ++j) wf[j] = z;
 #pragma unroll
             for (int i = 0; i < P; ++i) {
-                const uint32_t byte = (w[i] >> (8 * t)) & 0xffu;
-                const v8h pm = *reinterpret_cast<const v8h *>(lut + byte * 16);
+                const v4h pl = *reinterpret_cast<const v4h *>(lut + ((lo8[i] >> (8 * t)) & 0xffu));
+                const v4h ph = *reinterpret_cast<const v4h *>(lut + ((hi8[i] >> (8 * t)) & 0xffu));
 #pragma unroll
-                for (int j = 0; j < 8; ++j) wf[j] = fmaf((float)pm[j], alpha[i], wf[j]);
+                for (int j = 0; j < 4; ++j) {
+                    wf[j] = fmaf((float)pl[j], alpha[i], wf[j]);
+                    wf[4 + j] = fmaf((float)ph[j], alpha[i], wf[4 + j]);
+                }
             }
             v8h wb;
 #pragma unroll
@@ -213,17 +227,19 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
         step(ah1, ah0, g + TEAMS, 1);
     }
 
-    if constexpr (TEAMS == 2) {
-        // the second team hands its accumulators over through the (now free) activation tiles
+    if constexpr (TEAMS > 1) {
+        // the other teams hand their accumulators over through the (now free) activation tiles
         v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
-        if (team == 1) {
+        if (team > 0) {
 #pragma unroll
-            for (int u = 0; u < 4 * NU; ++u) xchg[(wave * 4 * NU + u) * 64 + lane] = acc[u];
+            for (int u = 0; u < 4 * NU; ++u) xchg[(((team - 1) * 4 + wave) * 4 * NU + u) * 64 + lane] = acc[u];
         }
         __syncthreads();
-        if (team == 1) return;
+        if (team > 0) return;
 #pragma unroll
-        for (int u = 0; u < 4 * NU; ++u) acc[u] += xchg[(wave * 4 * NU + u) * 64 + lane];
+        for (int k = 1; k < TEAMS; ++k)
+#pragma unroll
+            for (int u = 0; u < 4 * NU; ++u) acc[u] += xchg[(((k - 1) * 4 + wave) * 4 * NU + u) * 64 + lane];
     }
 
     // accumulator u, register i: request b0 + 16u + 4kq + i of row row0 + n16
@@ -256,11 +272,11 @@ hipError_t launch_one(const DequantParams &pr, dim3 grid, hipStream_t stream)
 template <int P>
 hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    // requests per workgroup: 64, 128 or 256; the last leaves neither LDS nor registers for two teams
+    // requests per workgroup: 64, 128 or 256, with four, two and one team of waves
     const int nu = a.batch <= 64 ? 1 : a.batch <= 128 ? 2 : 4;
     dim3 grid((unsigned)((a.m + kRowsPerWg - 1) / kRowsPerWg), (unsigned)((a.batch + 64 * nu - 1) / (64 * nu)));
     switch (nu) {
-    case 1: return launch_one<P, 1, 2>(pr, grid, stream);
+    case 1: return launch_one<P, 1, 4>(pr, grid, stream);
     case 2: return launch_one<P, 2, 2>(pr, grid, stream);
     default: return launch_one<P, 4, 1>(pr, grid, stream);
     }

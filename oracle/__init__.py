@@ -22,15 +22,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "bcq_oracle.c")
+_SRC_QUANT = os.path.join(_HERE, "bcq_quant_oracle.c")
 _LIB = os.path.join(_HERE, "libbcq_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile ``bcq_oracle.c`` with gcc into ``libbcq_oracle.so`` beside it."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile ``bcq_oracle.c`` and ``bcq_quant_oracle.c`` with gcc into ``libbcq_oracle.so`` beside them."""
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_QUANT))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_QUANT, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -49,6 +51,8 @@ def _load():
         lib.bcq_oracle_dequant_offset.argtypes = [vp, vp, vp, i32, i64, i64, i64, vp]
         lib.bcq_oracle_gemv_offset.argtypes = [vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, i64]
         lib.bcq_oracle_gemm_mixed_offset.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, i64]
+        lib.bcq_oracle_quantize.argtypes = [vp, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp]
+        lib.bcq_oracle_quantize.restype = i32
         lib.bcq_oracle_num_threads.restype = i32
         lib.bcq_oracle_set_num_threads.argtypes = [i32]
         for f in (lib.bcq_oracle_pack, lib.bcq_oracle_unpack, lib.bcq_oracle_dequant,
@@ -189,6 +193,35 @@ def gemm_mixed(planes: np.ndarray, scales_by_p: dict, p_req, x: np.ndarray, grou
     if rc != 0:
         raise ValueError("bcq_oracle_gemm_mixed: bad argument")
     return y, a
+
+
+def quantize(w: np.ndarray, p_low: int, p_high: int, cycles: int, group: int = 128, with_offset: bool = False,
+             literal_residual: bool = False) -> dict:
+    """Algorithm 1 on float16 weights [m][n], every (row, group) on its own.
+
+    Returns ``{"codes": int8 [p_high][m][n] in {-1,+1}, "scales": {p: float64 [p][m][n/group]},
+    "offsets": {p: float64 [m][n/group]} or None}`` for p = p_low..p_high, unrounded.
+    ``group`` may be any divisor of n here (the packed format needs a multiple of 32).
+    """
+    wb = _half_bits(w)
+    m, n = wb.shape
+    if n % group:
+        raise ValueError("n must be a multiple of group")
+    ng = n // group
+    nsets = p_high - p_low + 1
+    codes = np.zeros((p_high, m, n), dtype=np.int8)
+    flat = np.zeros(sum(p * m * ng for p in range(p_low, p_high + 1)), dtype=np.float64)
+    offs = np.zeros((nsets, m, ng), dtype=np.float64)
+    rc = _load().bcq_oracle_quantize(_ptr(wb), m, n, group, p_low, p_high, cycles, int(with_offset), int(literal_residual),
+                                     _ptr(codes), _ptr(flat), _ptr(offs))
+    if rc != 0:
+        raise ValueError("bcq_oracle_quantize: bad argument")
+    scales, at = {}, 0
+    for p in range(p_low, p_high + 1):
+        scales[p] = flat[at:at + p * m * ng].reshape(p, m, ng).copy()
+        at += p * m * ng
+    offsets = {p: offs[p - p_low].copy() for p in range(p_low, p_high + 1)} if with_offset else None
+    return {"codes": codes, "scales": scales, "offsets": offsets}
 
 
 def ulp16(v) -> np.ndarray:

@@ -82,6 +82,21 @@ def make_offsets(p: int, m: int, n: int, group: int = GROUP, seed=(0, 0)) -> np.
     return rng.normal(0.0, 0.01, size=(m, n // group)).astype(np.float16)
 
 
+def make_weights(m: int, n: int, seed=(0, 0), heavy_tail: bool = True) -> np.ndarray:
+    """float16 [m][n]: full-precision weights for the quantiser, standing in for trained layers.
+
+    Per output row a spread sigma_r = 0.02 * exp(N(0, 0.25^2)); entries sigma_r * N(0, 1); with
+    ``heavy_tail`` one entry in 256 is multiplied by 6 (trained layers have a few large weights per
+    group).  Rounded to float16 once, here.
+    """
+    rng = _rng(7, *seed)
+    sigma = 0.02 * np.exp(rng.normal(0.0, 0.25, size=(m, 1)))
+    w = rng.standard_normal(size=(m, n)) * sigma
+    if heavy_tail:
+        w = np.where(rng.random(size=(m, n)) < 1.0 / 256.0, 6.0 * w, w)
+    return w.astype(np.float16)
+
+
 def make_x(batch: int, n: int, seed=(0, 0), scale: float = 1.0) -> np.ndarray:
     """float16 [batch][n] ~ N(0, scale^2)."""
     rng = _rng(3, *seed)

@@ -168,6 +168,41 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
                    bcq_half *const *y, int p, const bcq_half *x,
                    int64_t n, int batch, int group, void *stream);
 
+/*
+ * bcq_quantize -- the offline quantiser: Algorithm 1 of section 3.2 ("AnyBCQ
+ * initialization and progressive precision expansion") built from the blocks
+ * of section 2.2 (greedy initialisation; scales by least squares; codes
+ * reassigned to the nearest of the 2^p levels), applied group-wise (section
+ * 4.1).  Every (row, group) of `w` is quantised on its own:
+ *   base precision p_low : greedy start, then `cycles` rounds of LS and BS;
+ *   p = p_low+1..p_high  : planes 0..p-2 stay frozen; `cycles` rounds of
+ *                          residual -> sign (the new plane p-1) -> LS over all
+ *                          p scales, starting from [alpha^(p-1), 0].
+ * The scale set of precision p is what the scales are when its rounds end.
+ * With `offsets_by_p` the asymmetric scheme of section 4.1 is fitted: the
+ * offset is one more least-squares unknown (all-ones basis vector).
+ * Definitions that decide codes: sign(0) = +1; the residual that re-signs the
+ * new plane excludes that plane (section 2.2's residual after p-1 planes);
+ * nearest-level ties go to the first level when enumerated with plane 0 as the
+ * most significant bit of the index; a plane that is linearly dependent on the
+ * planes before it gets scale 0.  Arithmetic is IEEE double (sums of binary16
+ * weights are exact in it), results are rounded once to binary16.
+ *   w             bcq_half [m][n], 16-byte aligned (finite values)
+ *   p_low, p_high 1 <= p_low <= p_high <= 4
+ *   cycles        T of Algorithm 1, >= 0; >= 1 if p_high > p_low
+ *   planes        uint32 [p_high][m][n/32] (written), storage format above
+ *   scales_by_p   HOST array of p_high+1 device pointers; entry p in
+ *                 p_low..p_high: bcq_half [p][m][n/group] (written); other
+ *                 entries are ignored
+ *   offsets_by_p  NULL (symmetric), or HOST array of p_high+1 device pointers;
+ *                 entry p in p_low..p_high: bcq_half [m][n/group] (written)
+ *   group         32, 64, 128 or 256
+ * Errors: BCQ_ERR_NULL, BCQ_ERR_BAD_P (precisions or cycles out of range),
+ * BCQ_ERR_BAD_SHAPE, BCQ_ERR_ALIGN, BCQ_ERR_HIP.
+ */
+int bcq_quantize(const bcq_half *w, int p_low, int p_high, int cycles, uint32_t *planes, bcq_half *const *scales_by_p,
+                 bcq_half *const *offsets_by_p, int64_t m, int64_t n, int group, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

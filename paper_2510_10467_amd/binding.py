@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.bcq_gemv_multi.restype = i32
         L.bcq_gemv_offset.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
         L.bcq_gemm_mixed_offset.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
+        L.bcq_quantize.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, i64, i32, vp]
+        L.bcq_quantize.restype = i32
         for f in (L.bcq_select_kernel, L.bcq_pack, L.bcq_unpack, L.bcq_gemv, L.bcq_gemm_mixed, L.bcq_gemv_offset,
                   L.bcq_gemm_mixed_offset):
             f.restype = i32
@@ -192,3 +194,38 @@ def bcq_gemm_mixed(planes: torch.Tensor, scales_by_p: dict, p_req: torch.Tensor,
                                 _dev(p_req, torch.int32, "p_req"), p_max, _dev(x, torch.float16, "x"),
                                 _dev(y, torch.float16, "y"), m, n, batch, group, _stream()), "bcq_gemm_mixed")
     return y
+
+
+def bcq_quantize(w: torch.Tensor, p_low: int, p_high: int, cycles: int, group: int = 128, with_offset: bool = False,
+                 planes: torch.Tensor | None = None, scales_by_p: dict | None = None, offsets_by_p: dict | None = None):
+    """Algorithm 1 on float16 weights [m][n]: returns ``(planes int32 [p_high][m][n/32], {p: scales float16
+    [p][m][n/group]}, {p: offsets float16 [m][n/group]} or None)`` for p = p_low..p_high."""
+    m, n = w.shape
+    if n % 32 or n % group:
+        raise ValueError("bcq_quantize: n must be a multiple of 32 and of group")
+    dev = w.device
+    if planes is None:
+        planes = torch.empty((p_high, m, n // 32), dtype=torch.int32, device=dev)
+    elif planes.shape != (p_high, m, n // 32):
+        raise ValueError("bcq_quantize: planes has the wrong shape")
+    rng = range(max(p_low, 1), min(p_high, BCQ_MAX_PLANES) + 1)
+    if scales_by_p is None:
+        scales_by_p = {p: torch.empty((p, m, n // group), dtype=torch.float16, device=dev) for p in rng}
+    if with_offset and offsets_by_p is None:
+        offsets_by_p = {p: torch.empty((m, n // group), dtype=torch.float16, device=dev) for p in rng}
+    size = max(p_high, 0) + 1
+    sp = (ctypes.c_void_p * size)()
+    op = (ctypes.c_void_p * size)()
+    for p in rng:
+        if scales_by_p[p].shape != (p, m, n // group):
+            raise ValueError(f"bcq_quantize: bad scale set for precision {p}")
+        sp[p] = _dev(scales_by_p[p], torch.float16, f"scales_by_p[{p}]")
+        if offsets_by_p is not None:
+            if offsets_by_p[p].shape != (m, n // group):
+                raise ValueError(f"bcq_quantize: bad offset set for precision {p}")
+            op[p] = _dev(offsets_by_p[p], torch.float16, f"offsets_by_p[{p}]")
+    _check(lib().bcq_quantize(_dev(w, torch.float16, "w"), p_low, p_high, cycles, _dev(planes, torch.int32, "planes"),
+                              ctypes.cast(sp, ctypes.c_void_p),
+                              ctypes.cast(op, ctypes.c_void_p) if offsets_by_p is not None else None,
+                              m, n, group, _stream()), "bcq_quantize")
+    return planes, scales_by_p, offsets_by_p

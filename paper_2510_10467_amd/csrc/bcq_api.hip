@@ -219,4 +219,24 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
     return BCQ_OK;
 }
 
+int bcq_quantize(const bcq_half *w, int p_low, int p_high, int cycles, uint32_t *planes, bcq_half *const *scales_by_p,
+                 bcq_half *const *offsets_by_p, int64_t m, int64_t n, int group, void *stream)
+{
+    if (!w || !planes || !scales_by_p) return BCQ_ERR_NULL;
+    if (p_low < 1 || p_high < p_low || p_high > 4 || cycles < 0 || (cycles < 1 && p_high > p_low)) return BCQ_ERR_BAD_P;
+    if (int rc = check_shape(m, n, 0, group)) return rc;
+    if (!bcq::quantize_supports(m, n, group)) return BCQ_ERR_BAD_SHAPE;
+    if (!aligned(w, 16) || !aligned(planes, 4)) return BCQ_ERR_ALIGN;
+    for (int p = p_low; p <= p_high; ++p) {
+        if (!scales_by_p[p] || (offsets_by_p && !offsets_by_p[p])) return BCQ_ERR_NULL;
+        if (!aligned(scales_by_p[p], 2) || (offsets_by_p && !aligned(offsets_by_p[p], 2))) return BCQ_ERR_ALIGN;
+    }
+    hipError_t err = bcq::quantize_launch(reinterpret_cast<const _Float16 *>(w), p_low, p_high, cycles, planes,
+                                          reinterpret_cast<_Float16 *const *>(scales_by_p),
+                                          reinterpret_cast<_Float16 *const *>(offsets_by_p), m, n, group,
+                                          static_cast<hipStream_t>(stream));
+    g_last = "quantize";
+    return err == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
+}
+
 }  // extern "C"

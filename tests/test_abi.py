@@ -27,7 +27,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_gemv_offset", "bcq_gemm_mixed_offset", "bcq_gemv_multi",
-            "bcq_strerror", "bcq_select_kernel", "bcq_last_kernel"} <= set(names)
+            "bcq_quantize", "bcq_strerror", "bcq_select_kernel", "bcq_last_kernel"} <= set(names)
     for name in names:
         assert hasattr(lib, name), f"{name} declared in bcq.h but not exported"
 
@@ -97,6 +97,24 @@ def test_argument_validation_without_device(lib):
     assert multi(2, (ctypes.c_void_p * 2)(P, None), sp, mm, yp, 2, X, 128, 1, 128, None) == -1
     assert multi(2, (ctypes.c_void_p * 2)(P, P + 4), sp, mm, yp, 2, X, 128, 1, 128, None) == -4
     assert multi(2, pp, sp, mm, yp, 2, X, 128, 0, 128, None) == 0
+    # the quantiser
+    quant = lib.bcq_quantize
+    W = 0x7000
+    sets = (ctypes.c_void_p * 5)(None, None, S, S + 0x100, S + 0x200)
+    assert quant(None, 2, 4, 20, P, sets, None, 16, 128, 128, None) == -1
+    assert quant(W, 2, 4, 20, P, None, None, 16, 128, 128, None) == -1
+    assert quant(W, 0, 4, 20, P, sets, None, 16, 128, 128, None) == -2
+    assert quant(W, 3, 2, 20, P, sets, None, 16, 128, 128, None) == -2
+    assert quant(W, 2, 5, 20, P, sets, None, 16, 128, 128, None) == -2
+    assert quant(W, 2, 4, 0, P, sets, None, 16, 128, 128, None) == -2       # expansion needs a cycle
+    assert quant(W, 2, 2, -1, P, sets, None, 16, 128, 128, None) == -2
+    assert quant(W, 2, 4, 20, P, sets, None, 16, 192, 128, None) == -3
+    assert quant(W, 2, 4, 20, P, sets, None, 16, 192, 96, None) == -3       # group not 32/64/128/256
+    assert quant(W, 2, 4, 20, P, sets, None, 0, 128, 128, None) == -3
+    assert quant(W + 2, 2, 4, 20, P, sets, None, 16, 128, 128, None) == -4
+    assert quant(W, 2, 4, 20, P, (ctypes.c_void_p * 5)(None, None, S, None, S), None, 16, 128, 128, None) == -1
+    assert quant(W, 2, 4, 20, P, sets, (ctypes.c_void_p * 5)(None, None, Z, Z, None), 16, 128, 128, None) == -1
+    assert quant(W, 2, 4, 20, P, (ctypes.c_void_p * 5)(None, None, S + 1, S, S), None, 16, 128, 128, None) == -4
     assert lib.bcq_pack(0x1000, 0x2000, 4, 8, 48, None) == -3
     assert lib.bcq_pack(0x1000, 0x2000, 0, 8, 64, None) == -2
     assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1

@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a reference kernel of known traffic for counter runs)")
-    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused", "offset"], default=None,
+    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused", "offset", "quant"], default=None,
                     help="instead of the headline workload, time another workload family and print its table")
     return ap.parse_args()
 
@@ -196,6 +196,46 @@ def run_suite(args, torch, bcq, syn, dev):
                          "seven_calls_us": round(us_sep, 2), "four_calls_us": round(us_fus, 2),
                          "seven_calls_GBps": round(by / us_sep / 1e3, 1), "four_calls_GBps": round(by / us_fus / 1e3, 1),
                          "pct_of_hbm_peak_four_calls": round(100 * by / us_fus / 1e3 / HBM_PEAK_GBS, 2)})
+    elif args.suite == "quant":
+        # The offline quantiser (Algorithm 1, p_L = 2, p_H = 4, T = 20, g = 128) on Llama-3-8B layer shapes.
+        # Bound by double-precision vector arithmetic: per weight and cycle the base stage adds p signed terms
+        # and compares against 2^p levels (sub + compare), an expansion stage to p bits spends p + 1 operations
+        # (p - 1 level terms, the residual, the signed sum); the per-group solves add about one more per cycle.
+        p_low, p_high, cycles = 2, 4, 20
+        ops_per_weight = cycles * ((p_low + 2 * 2 ** p_low + 1) + sum(p + 2 for p in range(p_low + 1, p_high + 1))) + 3 * p_low
+        peak_ops = 256 * 4 * 16 * 2.4e9                               # lanes x clock: one double operation per lane and cycle
+        import time
+
+        import numpy as np
+
+        import oracle
+        for (m, n) in ((4096, 4096), (14336, 4096), (4096, 14336)):
+            w = torch.from_numpy(syn.make_weights(m, n, seed=(8, m))).to(dev)
+            for with_offset in (False, True):
+                out = bcq.bcq_quantize(w, p_low, p_high, cycles, with_offset=with_offset)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                reps = 5
+                e0.record()
+                for _ in range(reps):
+                    bcq.bcq_quantize(w, p_low, p_high, cycles, with_offset=with_offset, planes=out[0], scales_by_p=out[1],
+                                     offsets_by_p=out[2])
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                rows.append({"shape": f"{m}x{n}", "p_low": p_low, "p_high": p_high, "cycles": cycles, "offset": with_offset,
+                             "ms": round(ms, 3), "Gweights_per_s": round(m * n / ms / 1e6, 2),
+                             "roofline": {"bound": "alu", "unit": "Tops/s (fp64 lane operations)",
+                                          "achieved": round(ops_per_weight * m * n / ms / 1e9, 2),
+                                          "peak": round(peak_ops / 1e12, 2),
+                                          "frac": round(ops_per_weight * m * n / (ms * 1e-3) / peak_ops, 4)}})
+        sample = syn.make_weights(512, 4096, seed=(8, 0))
+        t0 = time.perf_counter()
+        oracle.quantize(sample, p_low, p_high, cycles)
+        dt = time.perf_counter() - t0
+        rows.append({"cpu_baseline": {"value": round(sample.size / dt / 1e9, 5), "unit": "Gweights/s", "cores": oracle.num_threads(),
+                                      "kind": "oracle", "sample": "512x4096 weights, p 2..4, T = 20, symmetric"}})
+        return {"suite": args.suite, "unit": "ms per matrix", "data": "synthetic", "ops_per_weight": ops_per_weight, "rows": rows}
     else:
         for (_, m, n) in syn.LLAMA3_70B_SHAPES:
             bench_shape(m, n, (1, 16, 64, 256), PRECISIONS)

@@ -15,8 +15,8 @@
 //
 // Choices where the algorithm leaves room (they decide codes, so they are part of the definition):
 //   sign(0) = +1;  the residual that re-signs the new plane p is taken after the p-1 frozen planes under
-//   the current scales (section 2.2's residual);  code reassignment enumerates the 2^p levels with plane 1
-//   as the most significant bit of the index and keeps the first strict minimum of |w - level|;  the
+//   the current scales (section 2.2's residual);  code reassignment enumerates the 2^p levels with the first
+//   plane as the most significant bit of the index and keeps the first strict minimum of |w - level|;  the
 //   normal equations are eliminated in plane order without pivoting, and a plane whose pivot is not above
 //   1e-9 (it depends on the planes before it) gets scale 0;  in the asymmetric scheme the offset is one
 //   more unknown with the all-ones basis vector, placed last, greedy starting from the group mean.
@@ -166,17 +166,6 @@ __device__ __forceinline__ double signed_sum(const Lane &s, int i)
     return group_sum<LANES>(acc);
 }
 
-// value of the level that the codes of planes 0..NP-1 select at column j: ((+-a_0 +- a_1) ...) + z
-template <int NP, bool OFFSET>
-__device__ __forceinline__ double level_at(const Lane &s, const uint32_t (&nw)[kMaxP], int j)
-{
-    double v = flip(s.alpha[0], minus_mask(nw[0], j));
-#pragma unroll
-    for (int i = 1; i < NP; ++i) v = v + flip(s.alpha[i], minus_mask(nw[i], j));
-    if constexpr (OFFSET) v = v + s.z;
-    return v;
-}
-
 // Greedy plane I: b_I = sign(r_{I-1}), a_I = <r_{I-1}, b_I> / g, with r_{I-1} = ((w - z) - a_0 b_0) - ...
 template <int I, int LANES, bool OFFSET>
 __device__ __forceinline__ void greedy_plane(Lane &s)
@@ -238,29 +227,95 @@ __device__ __forceinline__ void base_stage(Lane &s, int cycles, double sum_w)
     }
 }
 
-// Expansion to precision P: planes 0..P-2 frozen; T cycles of residual -> sign -> LS.
-template <int P, int LANES, bool OFFSET>
-__device__ __forceinline__ void expand_stage(Lane &s, int cycles, double sum_w)
+// The same for P = 2, the base precision of the paper's experiments, as a tournament: the nearer of
+// levels 0/1, the nearer of levels 2/3, then the nearer of the two winners, the lower index winning ties
+// at every node (which is the first strict minimum of the enumeration).  The signed sums <w, b_i> that
+// the next cycle's LS needs are gathered while the codes are chosen.
+template <int LANES, bool OFFSET>
+__device__ __forceinline__ void base_stage_two(Lane &s, int cycles, double sum_w)
 {
+    double rhs_w[kMaxP] = {0.0, 0.0, 0.0, 0.0};
+    rhs_w[0] = signed_sum<LANES>(s, 0);
+    rhs_w[1] = signed_sum<LANES>(s, 1);
+    for (int t = 0; t < cycles; ++t) {
+        least_squares<2, LANES, OFFSET>(s, rhs_w, sum_w);
+        double lev[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double v = ((c & 2) ? s.alpha[0] : -s.alpha[0]) + ((c & 1) ? s.alpha[1] : -s.alpha[1]);
+            lev[c] = OFFSET ? v + s.z : v;
+        }
+        uint32_t word0 = 0, word1 = 0;
+        double acc0[2] = {0.0, 0.0}, acc1[2] = {0.0, 0.0};
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const double wj = s.w[j];
+            const double d0 = __builtin_fabs(wj - lev[0]), d1 = __builtin_fabs(wj - lev[1]);
+            const double d2 = __builtin_fabs(wj - lev[2]), d3 = __builtin_fabs(wj - lev[3]);
+            const bool c01 = d1 < d0, c23 = d3 < d2;
+            const double m01 = __builtin_fmin(d0, d1), m23 = __builtin_fmin(d2, d3);
+            const bool top = m23 < m01;                 // plane 0: +1 for levels 2, 3
+            const bool low = top ? c23 : c01;           // plane 1
+            word0 |= top ? (1u << j) : 0u;
+            word1 |= low ? (1u << j) : 0u;
+            acc0[j & 1] += top ? wj : -wj;
+            acc1[j & 1] += low ? wj : -wj;
+        }
+        s.word[0] = word0;
+        s.word[1] = word1;
+        rhs_w[0] = group_sum<LANES>(acc0[0] + acc0[1]);
+        rhs_w[1] = group_sum<LANES>(acc1[0] + acc1[1]);
+    }
+}
+
+// Expansion to precision P: planes 0..P-2 frozen; T cycles of residual -> sign -> LS.
+// The frozen codes of a column select one of 2^(P-1) levels; each cycle the lanes of a group write those
+// levels into the group's LDS table (`table`, 8 doubles) and every column reads its own back.  The table
+// is private to lanes of one wave, whose LDS accesses complete in program order.
+template <int P, int LANES, bool OFFSET>
+__device__ __forceinline__ void expand_stage(Lane &s, int cycles, double sum_w, double *table, int lane_in_group)
+{
+    constexpr int NL = 1 << (P - 1);
     double rhs_w[kMaxP] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int i = 0; i < P - 1; ++i) rhs_w[i] = signed_sum<LANES>(s, i);     // frozen planes: once
-    uint32_t nw[kMaxP];
+    // byte (j & 3) of pick[j >> 2]: eight times the level index of column j (plane 0 = most significant bit)
+    uint32_t pick[8];
 #pragma unroll
-    for (int i = 0; i < kMaxP; ++i) nw[i] = ~s.word[i];
+    for (int k = 0; k < 8; ++k) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int i = 0; i < P - 1; ++i) {
+            // bits 4k..4k+3 of the word spread to bit (3 + P-2-i) of bytes 0..3
+            const uint32_t nib = (s.word[i] >> (4 * k)) & 0xfu;
+            const uint32_t spread = (nib & 1u) | ((nib & 2u) << 7) | ((nib & 4u) << 14) | ((nib & 8u) << 21);
+            v |= spread << (3 + (P - 2 - i));
+        }
+        pick[k] = v;
+    }
     s.alpha[P - 1] = 0.0;
     for (int t = 0; t < cycles; ++t) {
-        double acc = 0.0;
-        uint32_t bits = 0;
+        for (int c = lane_in_group; c < NL; c += LANES) {
+            double v = ((c >> (P - 2)) & 1) ? s.alpha[0] : -s.alpha[0];
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            const double r = s.w[j] - level_at<P - 1, OFFSET>(s, nw, j);
-            const bool plus = r >= 0.0;
-            bits |= plus ? (1u << j) : 0u;
-            acc += plus ? s.w[j] : -s.w[j];
+            for (int i = 1; i < P - 1; ++i) v = v + (((c >> (P - 2 - i)) & 1) ? s.alpha[i] : -s.alpha[i]);
+            table[c] = OFFSET ? v + s.z : v;
         }
-        s.word[P - 1] = bits;
-        rhs_w[P - 1] = group_sum<LANES>(acc);
+        __builtin_amdgcn_wave_barrier();
+        double acc[2] = {0.0, 0.0};
+        uint32_t minus = 0;                              // sign bits of the residuals, column 31 first
+#pragma unroll
+        for (int j = 31; j >= 0; --j) {
+            const uint32_t off = (pick[j >> 2] >> (8 * (j & 3))) & 0xffu;
+            const double lev = *reinterpret_cast<const double *>(reinterpret_cast<const char *>(table) + off);
+            const double r = s.w[j] - lev;               // never -0: the weights hold no -0
+            const uint32_t rhi = (uint32_t)(__builtin_bit_cast(uint64_t, r) >> 32);
+            minus = __builtin_amdgcn_alignbit(minus, rhi, 31);
+            acc[j & 1] += flip(s.w[j], rhi & 0x80000000u);
+        }
+        __builtin_amdgcn_wave_barrier();
+        s.word[P - 1] = ~minus;
+        rhs_w[P - 1] = group_sum<LANES>(acc[0] + acc[1]);
         least_squares<P, LANES, OFFSET>(s, rhs_w, sum_w);
     }
 }
@@ -279,6 +334,9 @@ __device__ __forceinline__ void store_set(const QuantParams &a, const Lane &s, i
 template <int LANES, bool OFFSET>
 __global__ __launch_bounds__(256) void quantize_kernel(QuantParams a)
 {
+    __shared__ double tables[(256 / LANES) * 8];
+    double *table = tables + (threadIdx.x / LANES) * 8;
+    const int lane_in_group = threadIdx.x % LANES;
     const uint64_t gw = (uint64_t)blockIdx.x * 256 + threadIdx.x;      // this lane's word
     const bool valid = gw < a.total_words;                              // whole groups are valid or not
     const uint64_t src = valid ? gw : a.total_words - 1;
@@ -311,7 +369,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams a)
     if (p_low > 3) greedy_plane<3, LANES, OFFSET>(s);
     switch (p_low) {
     case 1: base_stage<1, LANES, OFFSET>(s, a.cycles, sum_w); break;
-    case 2: base_stage<2, LANES, OFFSET>(s, a.cycles, sum_w); break;
+    case 2: base_stage_two<LANES, OFFSET>(s, a.cycles, sum_w); break;
     case 3: base_stage<3, LANES, OFFSET>(s, a.cycles, sum_w); break;
     default: base_stage<4, LANES, OFFSET>(s, a.cycles, sum_w); break;
     }
@@ -320,9 +378,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams a)
     store_set<LANES, OFFSET>(a, s, p_low, gid, writer);
     for (int p = p_low + 1; p <= a.p_high; ++p) {
         switch (p) {
-        case 2: expand_stage<2, LANES, OFFSET>(s, a.cycles, sum_w); break;
-        case 3: expand_stage<3, LANES, OFFSET>(s, a.cycles, sum_w); break;
-        default: expand_stage<4, LANES, OFFSET>(s, a.cycles, sum_w); break;
+        case 2: expand_stage<2, LANES, OFFSET>(s, a.cycles, sum_w, table, lane_in_group); break;
+        case 3: expand_stage<3, LANES, OFFSET>(s, a.cycles, sum_w, table, lane_in_group); break;
+        default: expand_stage<4, LANES, OFFSET>(s, a.cycles, sum_w, table, lane_in_group); break;
         }
         store_set<LANES, OFFSET>(a, s, p, gid, writer);
     }

@@ -27,11 +27,11 @@ int choose(const bcq::GemmArgs &a)
     using namespace bcq;
     int choice = g_forced;
     if (choice == BCQ_KERNEL_AUTO) {
-        // Dequantising a weight tile costs the same whatever the number of requests that then use it, and a
-        // workgroup takes 64 rows: the kernel pays from about 24 requests on when the rows fill the chip
-        // (m >= 8192), from about 96 when they fill a quarter of it, and not at all on shorter matrices; below
-        // that the plane-wise kernel wins (measured on Llama-3-8B and 70B shapes, p = 2 and 4).
-        const bool pays = (a.m >= 8192 && a.batch >= 24) || (a.m >= 4096 && a.batch >= 96);
+        // Dequantising a weight tile costs the same whatever the number of requests that then use it (the time
+        // of that kernel is flat up to 64 requests), while the plane-wise kernel grows with the batch: from about
+        // 24 requests on the dequantising kernel wins on every matrix of at least 4096 rows (measured on
+        // Llama-3-8B and 70B shapes, p = 2 and 4); shorter matrices leave it too few workgroups.
+        const bool pays = a.m >= 4096 && a.batch >= 24;
         if (dequant_mfma_supports(a) && pays) choice = BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         else choice = BCQ_KERNEL_SIGN_SELECT;

@@ -4,18 +4,19 @@
 // is no longer bound by HBM but by arithmetic, and one dense fp16 MFMA over dequantised weights
 // costs p times fewer matrix instructions than p plane-wise products.
 //
-// A workgroup of four waves owns 64 weight rows (16 per wave) and TB = 64, 128 or 256 requests.  Per
-// group of 128 columns
-//   * the workgroup stages the TB x 128 activation tile in LDS (fetched one group ahead with fully
+// A team of RW waves (RW = 4, 2 or 1) owns 16 RW weight rows (16 per wave) and TB = 64, 128 or 256 requests.
+// Per group of 128 columns
+//   * the team stages the TB x 128 activation tile in LDS (fetched one group ahead with fully
 //     coalesced loads into registers, stored into the tile the previous group has just left);
 //   * lane (row, kq) of a wave holds word kq of its row's group from each plane plus the group's
 //     scales (also one group ahead).  Matrix step t covers the columns 32 kq + 8 t + j of the group
 //     (a permutation of K that the activation operand follows), so for each step the lane takes
 //     byte t of each plane word, looks its two nibbles up in a 16-entry LDS table of four +-1.0
 //     binary16 values (each entry sits in banks of its own and equal addresses are broadcast, so
-//     these reads never conflict, unlike those of a 256-entry table of eight values), accumulates w_j = sum_i alpha_i * (+-1) in fp32 (one mixed-precision FMA per column
-//     and plane), starting from the group's offset in the asymmetric scheme (section 4.1), and
-//     rounds once to binary16: that IS the B operand of v_mfma_f32_16x16x32_f16;
+//     these reads never conflict, unlike those of a 256-entry table of eight values), accumulates
+//     w_j = sum_i alpha_i * (+-1) in fp32 (one mixed-precision FMA per column and plane), starting from
+//     the group's offset in the asymmetric scheme (section 4.1), and rounds once to binary16: that IS
+//     the B operand of v_mfma_f32_16x16x32_f16;
 //   * the wave multiplies its 16 x 128 weight tile with all TB requests, reading each activation
 //     operand (16 requests x 32 columns) from LDS.
 // A weight is therefore dequantised once per TB requests and never leaves the registers; the
@@ -24,11 +25,16 @@
 // accumulator.  One barrier per group.
 //
 // A wave cannot overlap its own vector, matrix and LDS instructions, and with one wave per SIMD every
-// latency is exposed.  So, LDS and registers permitting, a workgroup has several such teams of four
-// waves (four for TB = 64, two for TB = 128): all work on the same rows and requests, team k on the
-// groups k, k + TEAMS, ... with activation tiles and accumulators of its own; the teams meet at every
-// barrier and add their accumulators through LDS at the end.
+// latency is exposed.  So, LDS permitting, a workgroup has several teams (four for TB = 64, two for
+// TB = 128): all work on the same rows and requests, team k on the groups k, k + TEAMS, ... with
+// activation tiles and accumulators of its own; the teams meet at every barrier and add their
+// accumulators through LDS at the end.  The activation tiles fill the LDS, so a CU runs one workgroup at a
+// time and a short matrix needs small row blocks (RW < 4) to give every CU one; the host picks the shape
+// from measured per-shape costs (launch_p).
 #include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
 
 #include "bcq_internal.hpp"
 
@@ -41,7 +47,6 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kRowsPerWg = 64;              // 4 waves x 16 rows
 constexpr int kMaxP = 4;
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2 + 16;    // padded LDS row of one request's 128 activations: rows start 4 banks apart
@@ -66,33 +71,37 @@ struct DequantParams {
 };
 
 // What a thread fetches ahead: plane words and scales of its row for one group, and its share of the
-// activation tile of the group after (4 * NU units of 16 bytes).
-template <int P, int NU>
+// activation tile of the group after (XU units of 16 bytes).
+template <int P, int XU>
 struct Ahead {
     uint32_t w[P];
     _Float16 alpha[P];
     _Float16 z;
-    u32x4 xs[4 * NU];
+    u32x4 xs[XU];
 };
 
-template <int P, int NU, int TEAMS>
-__global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams a)
+// NU: 64-request tiles per workgroup; TEAMS: teams of waves (K split inside the workgroup); RW: waves per
+// team = 16-row blocks per workgroup.
+template <int P, int NU, int TEAMS, int RW>
+__global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantParams a)
 {
+    constexpr int kTeamThreads = 64 * RW;
+    constexpr int XU = 16 * NU / RW;          // 16-byte units of an activation tile per thread of a team
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     unsigned char *lut = lds;
 
     // team and wave are the same in all lanes of a wave: telling the compiler keeps group indices and
     // base addresses in scalar registers
-    const int tid = threadIdx.x & 255, team = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+    const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NU);     // the team's two activation tiles, used alternately
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
-    const uint32_t row0 = blockIdx.x * kRowsPerWg + wave * 16;
+    const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
     const int b0 = blockIdx.y * (64 * NU);    // first request of the workgroup
 
     // table: nibble -> four binary16 values, +1.0 where the bit is set, -1.0 where it is clear
-    if (team == 0 && tid < 16) {
+    if (threadIdx.x < 16) {
         uint32_t e[2];
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
@@ -111,11 +120,11 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
     const uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
     const uint32_t s_lane = frow * a.scale_row_stride;
     const int pull = (4 * n16 + kq) * 4;      // byte index of the lane to take from
-    // staging: unit tid + 256k of the tile = request (unit >> 4), 16-byte part (unit & 15) of its 256 bytes
-    uint32_t xs_src[4 * NU], xs_dst[4 * NU];
+    // staging: unit tid + kTeamThreads * k of the tile = request (unit >> 4), 16-byte part (unit & 15) of its 256 bytes
+    uint32_t xs_src[XU], xs_dst[XU];
 #pragma unroll
-    for (int k = 0; k < 4 * NU; ++k) {
-        const int unit = tid + 256 * k;
+    for (int k = 0; k < XU; ++k) {
+        const int unit = tid + kTeamThreads * k;
         const int req = unit >> 4, part = unit & 15;
         xs_src[k] = (uint32_t)min(b0 + req, a.batch - 1) * a.x_stride + part * 16;
         xs_dst[k] = req * kXRowBytes + part * 16;
@@ -123,7 +132,7 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
     // A operand of request tile u, step t: 16 bytes at (16u + n16) * kXRowBytes + (32kq + 8t) * 2
     const unsigned char *xa_lane = xt0 + n16 * kXRowBytes + kq * 64;
 
-    auto fetch_w = [&](Ahead<P, NU> &ah, int g) {
+    auto fetch_w = [&](Ahead<P, XU> &ah, int g) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
             // wave-uniform 64-bit base plus 32-bit lane offset: an addressing mode of the load instruction
@@ -134,14 +143,14 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
         }
         ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + (uint32_t)g * 2 + s_lane);
     };
-    auto fetch_x = [&](Ahead<P, NU> &ah, int g) {
+    auto fetch_x = [&](Ahead<P, XU> &ah, int g) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
 #pragma unroll
-        for (int k = 0; k < 4 * NU; ++k) ah.xs[k] = *reinterpret_cast<const u32x4 *>(x_base + xs_src[k]);
+        for (int k = 0; k < XU; ++k) ah.xs[k] = *reinterpret_cast<const u32x4 *>(x_base + xs_src[k]);
     };
-    auto store_x = [&](const Ahead<P, NU> &ah, int buf) {
+    auto store_x = [&](const Ahead<P, XU> &ah, int buf) {
 #pragma unroll
-        for (int k = 0; k < 4 * NU; ++k) *reinterpret_cast<u32x4 *>(xt0 + buf * x_tile_bytes(NU) + xs_dst[k]) = ah.xs[k];
+        for (int k = 0; k < XU; ++k) *reinterpret_cast<u32x4 *>(xt0 + buf * x_tile_bytes(NU) + xs_dst[k]) = ah.xs[k];
     };
 
     v4f acc[4 * NU];
@@ -151,7 +160,7 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
     // Group g, the team's next being g + TEAMS.  On entry `cur` holds the plane words and scales of group g
     // and the activation tile of the next group; the team's LDS tile `buf` holds the activations of group g.
     // Every wave of the workgroup passes the barrier of every step, with or without a group of its own.
-    auto step = [&](Ahead<P, NU> &cur, Ahead<P, NU> &nxt, int g, int buf) {
+    auto step = [&](Ahead<P, XU> &cur, Ahead<P, XU> &nxt, int g, int buf) {
         if (g < a.ngroups) {
         // Everything fetched ahead is claimed here, while it is all that is outstanding: the wait is
         // then exact.  (Claimed after the next loads have been issued, it would cover those too.)
@@ -159,7 +168,7 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
         for (int i = 0; i < P; ++i) asm volatile("" : "+v"(cur.w[i]), "+v"(cur.alpha[i]));
         asm volatile("" : "+v"(cur.z));
 #pragma unroll
-        for (int k = 0; k < 4 * NU; ++k) asm volatile("" : "+v"(cur.xs[k]));
+        for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(cur.xs[k]));
         const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.z));
         const float z = a.has_offsets ? (float)__builtin_bit_cast(_Float16, (unsigned short)zb) : 0.f;
         uint32_t w[P];
@@ -212,7 +221,7 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
         __syncthreads();                        // tile `buf` free, the other tile complete
     };
 
-    Ahead<P, NU> ah0, ah1;
+    Ahead<P, XU> ah0, ah1;
     if (team < a.ngroups) {
         fetch_x(ah0, team);
         store_x(ah0, 0);
@@ -232,14 +241,14 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
         v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
         if (team > 0) {
 #pragma unroll
-            for (int u = 0; u < 4 * NU; ++u) xchg[(((team - 1) * 4 + wave) * 4 * NU + u) * 64 + lane] = acc[u];
+            for (int u = 0; u < 4 * NU; ++u) xchg[(((team - 1) * RW + wave) * 4 * NU + u) * 64 + lane] = acc[u];
         }
         __syncthreads();
         if (team > 0) return;
 #pragma unroll
         for (int k = 1; k < TEAMS; ++k)
 #pragma unroll
-            for (int u = 0; u < 4 * NU; ++u) acc[u] += xchg[(((k - 1) * 4 + wave) * 4 * NU + u) * 64 + lane];
+            for (int u = 0; u < 4 * NU; ++u) acc[u] += xchg[(((k - 1) * RW + wave) * 4 * NU + u) * 64 + lane];
     }
 
     // accumulator u, register i: request b0 + 16u + 4kq + i of row row0 + n16
@@ -255,30 +264,64 @@ __global__ __launch_bounds__(256 * TEAMS) void dequant_mfma_kernel(DequantParams
     }
 }
 
-template <int P, int NU, int TEAMS>
-hipError_t launch_one(const DequantParams &pr, dim3 grid, hipStream_t stream)
+template <int P, int NU, int TEAMS, int RW>
+hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    auto kernel = dequant_mfma_kernel<P, NU, TEAMS>;
+    static_assert((TEAMS - 1) * RW * 4 * NU * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NU), "accumulator exchange must fit in the tiles");
+    auto kernel = dequant_mfma_kernel<P, NU, TEAMS, RW>;
     if (lds_bytes(NU, TEAMS) > 64 * 1024) {
         // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            lds_bytes(NU, TEAMS));
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kernel, grid, dim3(256 * TEAMS), lds_bytes(NU, TEAMS), stream, pr);
+    dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 64 * NU - 1) / (64 * NU)));
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NU, TEAMS), stream, pr);
     return hipGetLastError();
 }
+
+// Shape of the workgroups: NU = 1, 2 or 4 tiles of 64 requests (with four, two and one team), RW = 4, 2 or 1
+// blocks of 16 rows.  A CU holds one workgroup at a time, so the time of a call is about
+// (rounds of workgroups over the 256 CUs) x (time of one workgroup per group of columns).  The second factor
+// was measured for every shape on a grid that fills the chip once (microseconds per group, p = 4 and p = 2):
+// larger workgroups reuse dequantised weights and staged activations better, smaller ones keep CUs busy on
+// short matrices.  The cheapest product wins.  BCQ_DEQUANT_SHAPE = "NU,RW" overrides the choice (benchmarks).
+struct WgShape {
+    int nu, rw;
+    float us_p4, us_p2;
+};
+constexpr WgShape kShapes[] = {{1, 4, 1.20f, 0.77f}, {1, 2, 0.76f, 0.51f}, {1, 1, 0.60f, 0.49f},
+                               {2, 4, 1.77f, 1.25f}, {2, 2, 1.54f, 1.10f}, {4, 4, 3.50f, 3.20f}};
 
 template <int P>
 hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    // requests per workgroup: 64, 128 or 256, with four, two and one team of waves
-    const int nu = a.batch <= 64 ? 1 : a.batch <= 128 ? 2 : 4;
-    dim3 grid((unsigned)((a.m + kRowsPerWg - 1) / kRowsPerWg), (unsigned)((a.batch + 64 * nu - 1) / (64 * nu)));
-    switch (nu) {
-    case 1: return launch_one<P, 1, 4>(pr, grid, stream);
-    case 2: return launch_one<P, 2, 2>(pr, grid, stream);
-    default: return launch_one<P, 4, 1>(pr, grid, stream);
+    int nu = 1, rw = 4;
+    float best = 0.f;
+    for (const WgShape &c : kShapes) {
+        const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * (float)((a.batch + 64 * c.nu - 1) / (64 * c.nu));
+        const float cost = (wgs <= 256.f ? 1.f : wgs / 256.f) * (P >= 3 ? c.us_p4 : c.us_p2);
+        if (best == 0.f || cost < best) {
+            best = cost;
+            nu = c.nu;
+            rw = c.rw;
+        }
+    }
+    if (const char *env = getenv("BCQ_DEQUANT_SHAPE")) {
+        int e_nu = 0, e_rw = 0;
+        if (sscanf(env, "%d,%d", &e_nu, &e_rw) == 2) {
+            nu = e_nu;
+            rw = e_rw;
+        }
+    }
+    switch (nu * 10 + rw) {
+    case 14: return launch_one<P, 1, 4, 4>(pr, a, stream);
+    case 12: return launch_one<P, 1, 4, 2>(pr, a, stream);
+    case 11: return launch_one<P, 1, 4, 1>(pr, a, stream);
+    case 24: return launch_one<P, 2, 2, 4>(pr, a, stream);
+    case 22: return launch_one<P, 2, 2, 2>(pr, a, stream);
+    case 44: return launch_one<P, 4, 1, 4>(pr, a, stream);
+    default: return hipErrorInvalidValue;
     }
 }
 
@@ -289,7 +332,7 @@ bool dequant_mfma_supports(const GemmArgs &a)
     // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
     const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31);
     return a.uniform_p >= 1 && a.uniform_p <= kMaxP && a.group == 128 && small_enough &&
-           (a.batch + 63) / 64 <= 65535 && (a.m + kRowsPerWg - 1) / kRowsPerWg < (int64_t(1) << 31);
+           (a.batch + 63) / 64 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
 }
 
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)

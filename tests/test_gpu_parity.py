@@ -104,6 +104,22 @@ def test_dequant_mfma_uniform(gpu, m, n):
             assert used == "dequant_mfma"
 
 
+@pytest.mark.parametrize("shape", ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
+def test_dequant_mfma_every_workgroup_shape(gpu, shape, monkeypatch):
+    """The kernel picks its workgroup shape (request tiles, row blocks) from m and the batch; small test
+    matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles)."""
+    monkeypatch.setenv("BCQ_DEQUANT_SHAPE", shape)
+    layer = syn.make_layer(200, 1536, seed=(151, 0), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    offsets = syn.make_offsets(3, 200, 1536, seed=(151, 1))
+    for batch in (3, 64, 100, 257):
+        x = syn.make_x(batch, 1536, seed=(151, batch))
+        for p in (2, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma")
+            assert used == "dequant_mfma"
+        gpu.check_gemv(dl, 3, x, "dequant_mfma", offsets=offsets)
+
+
 def test_forced_variant_that_cannot_run_is_an_error(gpu):
     import paper_2510_10467_amd as bcq
     layer = syn.make_layer(16, 640, seed=(160, 0))            # n is shorter than one K slice
@@ -130,9 +146,9 @@ def test_auto_dispatch_by_batch(gpu):
     used, _ = gpu.check_gemv(dl, 3, syn.make_x(128, 2048, seed=(170, 3)), "auto")
     assert used == "plane_mfma"            # too few rows for the dequantising kernel to pay
     big = gpu.DeviceLayer(syn.make_layer(4096, 1024, seed=(171, 0)))
-    used, _ = gpu.check_gemv(big, 3, syn.make_x(64, 1024, seed=(171, 1)), "auto")
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(16, 1024, seed=(171, 1)), "auto")
     assert used == "plane_mfma"
-    used, _ = gpu.check_gemv(big, 3, syn.make_x(100, 1024, seed=(171, 2)), "auto")
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(64, 1024, seed=(171, 2)), "auto")
     assert used == "dequant_mfma"
     p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
     used, _ = gpu.check_mixed(dl, p_req, syn.make_x(40, 2048, seed=(170, 4)), "auto")

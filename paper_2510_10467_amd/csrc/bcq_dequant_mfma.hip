@@ -67,7 +67,8 @@ struct DequantParams {
     uint32_t scale_row_stride;              // bytes between scale rows:    (n/128) * 2
     uint32_t x_stride;                      // bytes between requests:      n * 2
     uint32_t m;
-    int batch, ngroups;
+    int batch, ngroups;                     // ngroups: steps of 128 columns
+    int gshift;                             // scale groups of 64 (-1), 128 (0) or 256 (+1) columns
 };
 
 // What a thread fetches ahead: plane words and scales of its row for one group, and its share of the
@@ -118,7 +119,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     // that uses them (row l & 15, word l >> 4) by a lane permute.
     const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
     const uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
-    const uint32_t s_lane = frow * a.scale_row_stride;
+    // the scale group of (step g, word kq): g with 128 columns per group, g >> 1 with 256, 2g + (kq >> 1) with 64
+    const uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
+    auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;      // byte index of the lane to take from
     // staging: unit tid + kTeamThreads * k of the tile = request (unit >> 4), 16-byte part (unit & 15) of its 256 bytes
     uint32_t xs_src[XU], xs_dst[XU];
@@ -138,10 +141,10 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             // wave-uniform 64-bit base plus 32-bit lane offset: an addressing mode of the load instruction
             const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
             ah.w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(w_base + w_lane));
-            const unsigned char *s_base = a.scales + (size_t)i * a.scale_plane_stride + (uint32_t)g * 2;
+            const unsigned char *s_base = a.scales + (size_t)i * a.scale_plane_stride + scale_col(g);
             ah.alpha[i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
         }
-        ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + (uint32_t)g * 2 + s_lane);
+        ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + scale_col(g) + s_lane);
     };
     auto fetch_x = [&](Ahead<P, XU> &ah, int g) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
@@ -331,7 +334,8 @@ bool dequant_mfma_supports(const GemmArgs &a)
 {
     // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
     const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31);
-    return a.uniform_p >= 1 && a.uniform_p <= kMaxP && a.group == 128 && small_enough &&
+    const bool group_ok = (a.group == 64 || a.group == 128 || a.group == 256) && (a.n % 128) == 0;
+    return a.uniform_p >= 1 && a.uniform_p <= kMaxP && group_ok && small_enough &&
            (a.batch + 63) / 64 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
 }
 
@@ -346,8 +350,9 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.y = a.y;
     pr.plane_stride = (uint32_t)(a.m * (a.n / 8));
     pr.row_stride = (uint32_t)(a.n / 8);
-    pr.scale_plane_stride = (uint32_t)(a.m * (a.n / 128) * 2);
-    pr.scale_row_stride = (uint32_t)((a.n / 128) * 2);
+    pr.scale_plane_stride = (uint32_t)(a.m * (a.n / a.group) * 2);
+    pr.scale_row_stride = (uint32_t)((a.n / a.group) * 2);
+    pr.gshift = a.group == 256 ? 1 : a.group == 64 ? -1 : 0;
     pr.x_stride = (uint32_t)(a.n * 2);
     pr.m = (uint32_t)a.m;
     pr.batch = a.batch;

@@ -68,7 +68,7 @@ struct PlaneMfmaParams {
     uint32_t m;
     int batch, p_max, uniform_p;
     int KS, RB, nchunk, nslices;
-    int glast;                              // groups in the last slice (8 unless n is not a multiple of 1024)
+    int glast;                              // 128-column groups in the last slice (8 unless n is not a multiple of 1024)
     // several matrices with the same n, p and activations in one launch (MULTI kernels): matrix k owns the
     // row blocks mat_blk0[k] .. mat_blk0[k+1]-1 of the grid; unused entries hold the total
     const unsigned char *mat_planes[BCQ_MAX_MULTI];
@@ -146,7 +146,15 @@ __device__ __forceinline__ u32x4 drop_first_half(u32x4 v)
                  __builtin_amdgcn_alignbit(v.w, v.z, 16), v.w >> 16};
 }
 
-template <int PH, int NB, bool MIXED, bool OFFSET>
+// four binary16 values in v.x, v.y -> each of them twice: {a, a, b, b, c, c, d, d}
+__device__ __forceinline__ u32x4 each_twice(u32x4 v)
+{
+    return u32x4{__builtin_amdgcn_perm(v.x, v.x, 0x01000100u), __builtin_amdgcn_perm(v.x, v.x, 0x03020302u),
+                 __builtin_amdgcn_perm(v.y, v.y, 0x01000100u), __builtin_amdgcn_perm(v.y, v.y, 0x03020302u)};
+}
+
+// WIDE: scale groups of 256 columns (a slice has four scales per row, not eight)
+template <int PH, int NB, bool MIXED, bool OFFSET, bool WIDE>
 __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneMfmaParams &pr, const LaneOffsets &off,
                                             const unsigned char *sbase, const unsigned char *zbase, int p_mine, int slice_c,
                                             int ngroups)
@@ -156,7 +164,17 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
     // are zero), and the 16 bytes of scales are the LAST eight of the row, shifted into place later.
     const uint32_t x_lane = off.lane < (uint32_t)ngroups * 8 ? off.lane * 32 : 0;
     const uint32_t w_lane = (off.lane & 7) < (uint32_t)ngroups ? (off.lane & 7) * 16 : 0;
-    const uint32_t s_slice = ngroups < kSliceGroups ? pr.scale_row_stride - kSliceGroups * 2 : (uint32_t)slice_c * (kSliceGroups * 2);
+    // (scale groups of 256 columns: four scales = 8 bytes per slice, spread to eight after the loads)
+    constexpr uint32_t s_bytes = WIDE ? kSliceGroups : kSliceGroups * 2;
+    const uint32_t s_slice = ngroups < kSliceGroups ? pr.scale_row_stride - s_bytes : (uint32_t)slice_c * s_bytes;
+    auto load_scales = [&](const unsigned char *p) {
+        if constexpr (WIDE) {
+            const v2u t = *reinterpret_cast<const v2u *>(p);
+            return u32x4{t.x, t.y, 0u, 0u};
+        } else {
+            return *reinterpret_cast<const u32x4 *>(p);
+        }
+    };
     // in the order of use: activations, scales, planes.  Every address is a wave-uniform 64-bit base plus
     // a 32-bit lane offset, which is an addressing mode of the load instruction: no 64-bit lane arithmetic.
     const unsigned char *x_base = pr.x + (uint32_t)slice_c * (kSliceCols * 2);
@@ -170,13 +188,13 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
     for (int i = 0; i < PH; ++i) {
         if constexpr (MIXED) {
             const int ii = min(i, max(p_mine, 1) - 1);              // stay inside the lane's own scale set
-            ld.sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)ii * pr.scale_plane_stride + off.s + s_slice);
+            ld.sc[i] = load_scales(sbase + (size_t)ii * pr.scale_plane_stride + off.s + s_slice);
         } else {
             const unsigned char *s_base = sbase + (size_t)i * pr.scale_plane_stride + s_slice;
-            ld.sc[i] = *reinterpret_cast<const u32x4 *>(s_base + off.s);
+            ld.sc[i] = load_scales(s_base + off.s);
         }
     }
-    if constexpr (OFFSET) ld.zc = *reinterpret_cast<const u32x4 *>(zbase + s_slice + off.s);
+    if constexpr (OFFSET) ld.zc = load_scales(zbase + s_slice + off.s);
     const uint32_t wa = off.wa + w_lane, wb = off.wb + w_lane;
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
@@ -192,7 +210,7 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
 // MIXED: lanes of different quarters may belong to requests of different precisions.
 // OFFSET: asymmetric scheme; zbase is the offset set of the lane's request (any readable array of that
 //         size when z_on is false: the request has none).
-template <int PH, int NB, bool MIXED, bool OFFSET>
+template <int PH, int NB, bool MIXED, bool OFFSET, bool WIDE>
 __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int RB, int wave, int lane,
                                        const LaneOffsets &off, int p_mine, const unsigned char *sbase,
                                        const unsigned char *zbase, bool z_on)
@@ -212,7 +230,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         // delays the memory phase of all waves that share the SIMD.  The lane id is made opaque after
         // them so that no LDS address arithmetic is moved in front of the loop.
         SliceLoads<PH, NB> ld;
-        issue_loads<PH, NB, MIXED, OFFSET>(ld, pr, off, sbase, zbase, p_mine, slice_ok ? slice : 0, ngroups);
+        issue_loads<PH, NB, MIXED, OFFSET, WIDE>(ld, pr, off, sbase, zbase, p_mine, slice_ok ? slice : 0, ngroups);
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" : "+v"(lane));
 
@@ -286,6 +304,12 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         }
         if (RB > 1) __syncthreads();
 
+        // scale groups of 256 columns: each of the four scales fetched serves two groups of 128
+        if constexpr (WIDE) {
+#pragma unroll
+            for (int i = 0; i < PH; ++i) ld.sc[i] = each_twice(ld.sc[i]);
+            if constexpr (OFFSET) ld.zc = each_twice(ld.zc);
+        }
         // short last slice: its scales are the last ngroups of the eight fetched; the rest become zero
         if (ngroups < kSliceGroups) {
             for (int k = ngroups; k < kSliceGroups; ++k) {
@@ -365,7 +389,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
 // workgroup leaves a wave (128), and their operand image limits the waves per CU anyway: they stop at 8.
 __host__ __device__ constexpr int max_waves(int NB, bool mixed) { return NB == 4 && mixed ? 8 : 16; }
 
-template <int P, int NB, bool MIXED, bool OFFSET, bool MULTI = false>
+template <int P, int NB, bool MIXED, bool OFFSET, bool MULTI = false, bool WIDE = false>
 __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(PlaneMfmaParams pr_in)
 {
     PlaneMfmaParams pr = pr_in;               // MULTI kernels overwrite the per-matrix fields below
@@ -434,7 +458,7 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB, false, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P], pr.offsets[P], true);
+        acc = sweep<P, NB, false, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P], pr.offsets[P], true);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs.
         // The four precisions of the tile are fetched together, and scale sets are picked by comparison
@@ -463,10 +487,10 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
         }
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
-        case 2: acc = sweep<2, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
-        case 3: acc = sweep<3, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
-        case 4: acc = sweep<4, NB, true, OFFSET>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 1: acc = sweep<1, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 2: acc = sweep<2, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 3: acc = sweep<3, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 4: acc = sweep<4, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }
@@ -544,16 +568,23 @@ hipError_t launch_one(K kernel, const PlaneMfmaParams &pr, const Plan &pl, dim3 
     return hipGetLastError();
 }
 
+template <int NB, bool OFFSET, bool WIDE>
+hipError_t launch_group(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
+{
+    if (a.uniform_p == 0) return launch_one(plane_mfma_kernel<kMaxP, NB, true, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
+    switch (a.uniform_p) {
+    case 1: return launch_one(plane_mfma_kernel<1, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
+    case 2: return launch_one(plane_mfma_kernel<2, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
+    case 3: return launch_one(plane_mfma_kernel<3, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
+    default: return launch_one(plane_mfma_kernel<4, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
+    }
+}
+
 template <int NB, bool OFFSET>
 hipError_t launch_nb(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
 {
-    if (a.uniform_p == 0) return launch_one(plane_mfma_kernel<kMaxP, NB, true, OFFSET>, pr, pl, grid, block, stream);
-    switch (a.uniform_p) {
-    case 1: return launch_one(plane_mfma_kernel<1, NB, false, OFFSET>, pr, pl, grid, block, stream);
-    case 2: return launch_one(plane_mfma_kernel<2, NB, false, OFFSET>, pr, pl, grid, block, stream);
-    case 3: return launch_one(plane_mfma_kernel<3, NB, false, OFFSET>, pr, pl, grid, block, stream);
-    default: return launch_one(plane_mfma_kernel<4, NB, false, OFFSET>, pr, pl, grid, block, stream);
-    }
+    return a.group == 256 ? launch_group<NB, OFFSET, true>(a, pr, pl, grid, block, stream)
+                          : launch_group<NB, OFFSET, false>(a, pr, pl, grid, block, stream);
 }
 
 template <int NB>
@@ -574,9 +605,10 @@ bool plane_mfma_supports(const GemmArgs &a)
     // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
     const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31) &&
                               a.m < (int64_t(1) << 24) && a.n < (int64_t(1) << 24);
-    // whole scale groups, 4-byte aligned scale rows, and at least eight groups per row (the scales of a
-    // short last slice are fetched as the last eight of the row)
-    return a.group == 128 && (a.n % 256) == 0 && a.n >= kSliceCols && a.p_max <= kMaxP && small_enough &&
+    // whole scale groups, 4-byte aligned scale rows, and at least eight groups of 128 per row (the scales of
+    // a short last slice are fetched as the last ones of the row); scale groups of 128 or 256 columns
+    const bool group_ok = (a.group == 128 && (a.n % 256) == 0) || (a.group == 256 && (a.n % 512) == 0);
+    return group_ok && a.n >= kSliceCols && a.p_max <= kMaxP && small_enough &&
            ((a.m + 15) / 16 + 8) * ((a.batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);
 }
 
@@ -598,8 +630,8 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     const bool with_offsets = a.uniform_p > 0 ? a.offsets[a.uniform_p] != nullptr : pr.offset_mask != 0;
     pr.plane_stride = (uint32_t)(a.m * (a.n / 8));
     pr.row_stride = (uint32_t)(a.n / 8);
-    pr.scale_plane_stride = (uint32_t)(a.m * (a.n / 128) * 2);
-    pr.scale_row_stride = (uint32_t)((a.n / 128) * 2);
+    pr.scale_plane_stride = (uint32_t)(a.m * (a.n / a.group) * 2);
+    pr.scale_row_stride = (uint32_t)((a.n / a.group) * 2);
     pr.x_stride = (uint32_t)(a.n * 2);
     pr.m = (uint32_t)a.m;
     pr.batch = a.batch;
@@ -641,7 +673,9 @@ bool plane_mfma_supports_multi(const GemmArgs *mats, int count)
     for (int k = 0; k < count; ++k) {
         const GemmArgs &a = mats[k];
         if (!plane_mfma_supports(a) || a.uniform_p < 1 || a.offsets[a.uniform_p]) return false;
-        if (a.n != mats[0].n || a.uniform_p != mats[0].uniform_p || a.batch != mats[0].batch || a.x != mats[0].x) return false;
+        if (a.n != mats[0].n || a.uniform_p != mats[0].uniform_p || a.batch != mats[0].batch || a.x != mats[0].x ||
+            a.group != 128)
+            return false;
         row_blocks += (a.m + 15) / 16;
     }
     return (row_blocks + 8) * ((mats[0].batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);

@@ -120,6 +120,39 @@ def test_dequant_mfma_every_workgroup_shape(gpu, shape, monkeypatch):
         gpu.check_gemv(dl, 3, x, "dequant_mfma", offsets=offsets)
 
 
+@pytest.mark.parametrize("m,n", [(37, 2048), (20, 1536), (33, 3584), (130, 4096)])
+def test_plane_mfma_groups_of_256(gpu, m, n):
+    """Scale groups of 256 columns: four scales per K slice, each serving two matrix instructions; 1536 and
+    3584 end in a half slice."""
+    layer = syn.make_layer(m, n, group=256, seed=(152, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    zs = {p: syn.make_offsets(p, m, n, 256, seed=(152, m)) for p in (2, 3)}
+    for batch in (1, 2, 3, 9):
+        x = syn.make_x(batch, n, seed=(152, batch))
+        for p in (1, 2, 3, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "plane_mfma", 256)
+            assert used == "plane_mfma"
+        gpu.check_gemv(dl, 3, x, "plane_mfma", 256, offsets=zs[3])
+        p_req = syn.make_p_req(batch, 1, 4, seed=(152, batch))
+        gpu.check_mixed(dl, p_req, x, "plane_mfma", 256)
+        gpu.check_mixed(dl, p_req, x, "plane_mfma", 256, offsets_by_p=zs)
+    used, _ = gpu.check_gemv(dl, 2, syn.make_x(1, n, seed=(152, 99)), "auto", 256)
+    assert used == "plane_mfma"
+
+
+@pytest.mark.parametrize("group", [64, 256])
+def test_dequant_mfma_other_group_sizes(gpu, group):
+    layer = syn.make_layer(150, 1536, group=group, seed=(153, group), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    offsets = syn.make_offsets(2, 150, 1536, group, seed=(153, 1))
+    for batch in (5, 64, 130):
+        x = syn.make_x(batch, 1536, seed=(153, batch))
+        for p in (1, 3, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma", group)
+            assert used == "dequant_mfma"
+        gpu.check_gemv(dl, 2, x, "dequant_mfma", group, offsets=offsets)
+
+
 def test_forced_variant_that_cannot_run_is_an_error(gpu):
     import paper_2510_10467_amd as bcq
     layer = syn.make_layer(16, 640, seed=(160, 0))            # n is shorter than one K slice

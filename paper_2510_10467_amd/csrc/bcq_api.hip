@@ -34,6 +34,9 @@ int choose(const bcq::GemmArgs &a)
         const bool pays = a.m >= 4096 && a.batch >= 24;
         if (dequant_mfma_supports(a) && pays) choice = BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
+        // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all
+        // of its work per request, so the dequantising one wins from the second request on
+        else if (dequant_mfma_supports(a) && a.batch >= 2 && a.m >= 1024) choice = BCQ_KERNEL_DEQUANT_MFMA;
         else choice = BCQ_KERNEL_SIGN_SELECT;
     }
     return choice;

@@ -198,26 +198,49 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
         }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
+            // every LDS read of this matrix step goes out first: the table entries, then the activation operands
+            // of the first four request tiles, which arrive while the weights are being rebuilt
+            v4h pl[P], ph[P];
+#pragma unroll
+            for (int i = 0; i < P; ++i) {
+                pl[i] = *reinterpret_cast<const v4h *>(lut + ((lo8[i] >> (8 * t)) & 0xffu));
+                ph[i] = *reinterpret_cast<const v4h *>(lut + ((hi8[i] >> (8 * t)) & 0xffu));
+            }
+            v8h xa[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + t * 16);
+            // (sixteen waves leave a wave 128 registers, too few to hold the operands across the arithmetic:
+            // there the compiler is left to place the reads itself)
+            if constexpr (RW * TEAMS <= 8) __builtin_amdgcn_sched_barrier(0);
             float wf[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) wf[j] = z;
 #pragma unroll
             for (int i = 0; i < P; ++i) {
-                const v4h pl = *reinterpret_cast<const v4h *>(lut + ((lo8[i] >> (8 * t)) & 0xffu));
-                const v4h ph = *reinterpret_cast<const v4h *>(lut + ((hi8[i] >> (8 * t)) & 0xffu));
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    wf[j] = fmaf((float)pl[j], alpha[i], wf[j]);
-                    wf[4 + j] = fmaf((float)ph[j], alpha[i], wf[4 + j]);
+                    wf[j] = fmaf((float)pl[i][j], alpha[i], wf[j]);
+                    wf[4 + j] = fmaf((float)ph[i][j], alpha[i], wf[4 + j]);
                 }
             }
             v8h wb;
 #pragma unroll
             for (int j = 0; j < 8; ++j) wb[j] = (_Float16)wf[j];    // the single rounding of W_p to binary16
 #pragma unroll
-            for (int u = 0; u < 4 * NU; ++u) {
-                const v8h xa = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + t * 16);
-                acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, wb, acc[u], 0, 0, 0);
+            for (int c = 0; c < NU; ++c) {
+                // the operands of the next four tiles are fetched while these four are in the matrix pipe
+                v8h xn[4];
+                if (c + 1 < NU) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        xn[u] = *reinterpret_cast<const v8h *>(xa_cur + (4 * (c + 1) + u) * (16 * kXRowBytes) + t * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[4 * c + u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[u], wb, acc[4 * c + u], 0, 0, 0);
+                if (c + 1 < NU) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) xa[u] = xn[u];
+                }
             }
         }
         }

@@ -414,6 +414,27 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": profiled_traffic_bytes(dom_p, dm, dn),
                 "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3)}
 
+    # What a pure streaming read reaches on this GPU: as many bytes as the dominant kernel moves (cold, rotating
+    # over distinct buffers, back-to-back launches in a graph), and 1 GiB in one launch.
+    sink = torch.zeros(64, dtype=torch.int32, device=dev)
+    small = [torch.empty(dom_bytes // 16 * 16, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(32)]
+
+    def read_burst():
+        for b in small:
+            bcq.bench_stream_read(b, sink)
+    read_burst()
+    torch.cuda.synchronize()
+    us_read = timed([capture(read_burst).replay], 10, 3) * 1e3 / len(small)
+    del small
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    bcq.bench_stream_read(big, sink)
+    torch.cuda.synchronize()
+    us_big = timed([lambda: bcq.bench_stream_read(big, sink)], 10, 3) * 1e3
+    del big
+    roofline["stream_read_same_bytes"] = {"us": round(us_read, 3), "GBps": round(dom_bytes / us_read / 1e3, 1),
+                                          "kernel_vs_stream_read": round(us_read / dom_us, 4)}
+    roofline["stream_read_1GiB"] = {"us": round(us_big, 1), "GBps": round((1 << 30) / us_big / 1e3, 1)}
+
     details = None
     if args.details:
         details = {"kernels": []}
@@ -439,6 +460,18 @@ def main():
         torch.cuda.synchronize()
         us16 = timed([fp16_burst], 10, 3) * 1e3 / 48
         details["fp16_gemv"] = {"m": dm, "n": dn, "us": round(us16, 3), "GBps": round(2 * dm * dn / (us16 * 1e-6) / 1e9, 1)}
+        # the same product with a plain hand-written kernel (one wavefront per row), so that the comparison
+        # does not hinge on a library's choice of kernel
+        yv = torch.empty((dm,), dtype=torch.float16, device=dev)
+
+        def fp16_own_burst():
+            for i in range(48):
+                bcq.bench_fp16_gemv(ws[i % len(ws)], xv, yv)
+        fp16_own_burst()
+        torch.cuda.synchronize()
+        us16o = timed([capture(fp16_own_burst).replay], 10, 3) * 1e3 / 48
+        details["fp16_gemv_plain_kernel"] = {"m": dm, "n": dn, "us": round(us16o, 3),
+                                             "GBps": round(2 * dm * dn / (us16o * 1e-6) / 1e9, 1)}
         del ws
 
     if args.calibrate_copy:

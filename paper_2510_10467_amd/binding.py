@@ -51,6 +51,10 @@ def lib() -> ctypes.CDLL:
         L.bcq_gemm_mixed_offset.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
         L.bcq_quantize.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, i64, i32, vp]
         L.bcq_quantize.restype = i32
+        L.bcq_bench_stream_read.argtypes = [vp, i64, vp, vp]
+        L.bcq_bench_stream_read.restype = i32
+        L.bcq_bench_fp16_gemv.argtypes = [vp, vp, vp, i64, i64, vp]
+        L.bcq_bench_fp16_gemv.restype = i32
         for f in (L.bcq_select_kernel, L.bcq_pack, L.bcq_unpack, L.bcq_gemv, L.bcq_gemm_mixed, L.bcq_gemv_offset,
                   L.bcq_gemm_mixed_offset):
             f.restype = i32
@@ -229,3 +233,21 @@ def bcq_quantize(w: torch.Tensor, p_low: int, p_high: int, cycles: int, group: i
                               ctypes.cast(op, ctypes.c_void_p) if offsets_by_p is not None else None,
                               m, n, group, _stream()), "bcq_quantize")
     return planes, scales_by_p, offsets_by_p
+
+
+def bench_stream_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    """Benchmark reference: stream ``buf`` (any dtype, a multiple of 16 bytes) through 128-bit loads."""
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise TypeError("buf must be a contiguous GPU tensor")
+    _check(lib().bcq_bench_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), _dev(sink, torch.int32, "sink"), _stream()),
+           "bcq_bench_stream_read")
+
+
+def bench_fp16_gemv(w: torch.Tensor, x: torch.Tensor, y: torch.Tensor) -> torch.Tensor:
+    """Benchmark reference: y = w @ x in binary16 with fp32 accumulation, one wavefront per row."""
+    m, n = w.shape
+    if x.shape != (n,) or y.shape != (m,):
+        raise ValueError("bench_fp16_gemv: inconsistent shapes")
+    _check(lib().bcq_bench_fp16_gemv(_dev(w, torch.float16, "w"), _dev(x, torch.float16, "x"), _dev(y, torch.float16, "y"), m, n,
+                                     _stream()), "bcq_bench_fp16_gemv")
+    return y

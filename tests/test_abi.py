@@ -19,17 +19,20 @@ def lib():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "bcq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(bcq_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(bcq_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_gemv_offset", "bcq_gemm_mixed_offset", "bcq_gemv_multi",
-            "bcq_quantize", "bcq_strerror", "bcq_select_kernel", "bcq_last_kernel"} <= set(names)
+            "bcq_quantize", "bcq_bench_stream_read", "bcq_bench_fp16_gemv", "bcq_strerror", "bcq_select_kernel", "bcq_last_kernel"} <= set(names)
     for name in names:
-        assert hasattr(lib, name), f"{name} declared in bcq.h but not exported"
+        assert hasattr(lib, name), f"{name} declared in include/ but not exported"
 
 
 def test_strerror_covers_all_codes(lib):
@@ -115,6 +118,13 @@ def test_argument_validation_without_device(lib):
     assert quant(W, 2, 4, 20, P, (ctypes.c_void_p * 5)(None, None, S, None, S), None, 16, 128, 128, None) == -1
     assert quant(W, 2, 4, 20, P, sets, (ctypes.c_void_p * 5)(None, None, Z, Z, None), 16, 128, 128, None) == -1
     assert quant(W, 2, 4, 20, P, (ctypes.c_void_p * 5)(None, None, S + 1, S, S), None, 16, 128, 128, None) == -4
+    # benchmark reference kernels
+    assert lib.bcq_bench_stream_read(None, 1024, 0x2000, None) == -1
+    assert lib.bcq_bench_stream_read(0x1000, 1000, 0x2000, None) == -3
+    assert lib.bcq_bench_stream_read(0x1008, 1024, 0x2000, None) == -3
+    assert lib.bcq_bench_fp16_gemv(0x1000, 0x2000, None, 4, 64, None) == -1
+    assert lib.bcq_bench_fp16_gemv(0x1000, 0x2000, 0x3000, 4, 60, None) == -3
+    assert lib.bcq_bench_fp16_gemv(0x1002, 0x2000, 0x3000, 4, 64, None) == -4
     assert lib.bcq_pack(0x1000, 0x2000, 4, 8, 48, None) == -3
     assert lib.bcq_pack(0x1000, 0x2000, 0, 8, 64, None) == -2
     assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1

@@ -288,3 +288,23 @@ def test_gemv_multi_falls_back_to_separate_launches(gpu, oracle):
     for d, y in zip(dls, ys):
         y_ref, a_ref = oracle.gemv(d.layer.planes, d.layer.scales[3], xh)
         gpu.assert_within_tolerance(y, y_ref, a_ref, "bcq_gemv_multi fallback")
+
+
+def test_benchmark_reference_kernels(gpu):
+    """The plain binary16 matrix-vector kernel the benchmark compares against computes what it says, and
+    the streaming-read kernel leaves its sink alone."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    rng = np.random.default_rng(5)
+    w = (rng.standard_normal((77, 1096)) * 0.05).astype(np.float16)
+    x = rng.standard_normal(1096).astype(np.float16)
+    y = bcq.bench_fp16_gemv(gpu.to_dev(w), gpu.to_dev(x), torch.empty(77, dtype=torch.float16, device=gpu.DEV))
+    ref = w.astype(np.float64) @ x.astype(np.float64)
+    mag = np.abs(w.astype(np.float64)) @ np.abs(x.astype(np.float64))
+    assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= 1e-3 * mag + 1e-3)
+    buf = gpu.to_dev(rng.integers(0, 2 ** 31, size=100_003 * 4, dtype=np.int64).astype(np.int32))
+    sink = torch.zeros(64, dtype=torch.int32, device=gpu.DEV)
+    bcq.bench_stream_read(buf, sink)
+    torch.cuda.synchronize()
+    assert int(sink.abs().sum()) == 0

@@ -37,7 +37,8 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
     dl = gpu.DeviceLayer(layer)
     rng = np.random.default_rng([syn.BASE_SEED, 200, m])
     rows = np.unique(np.concatenate([[0, 15, 16, m - 17, m - 1], rng.integers(0, m, size=120)]))
-    for batch, kernels in ((1, ("auto",)), (3, ("auto",)), (80, ("auto",))):
+    batches = (1, 3, 80, 256) if name in ("gate_proj", "llama70b_down", "q_proj") else (1, 3, 80)
+    for batch in batches:
         x = syn.make_x(batch, n, seed=(200, batch))
         xd = gpu.to_dev(x)
         for p in (2, 3, 4):

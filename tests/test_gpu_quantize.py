@@ -100,3 +100,20 @@ def test_quantised_layer_runs_through_the_product():
         rel.append(np.linalg.norm(yy - exact) / np.linalg.norm(exact))
     assert rel[0] > rel[1] > rel[2]
     assert rel[0] < 0.45 and rel[2] < 0.16
+
+
+@pytest.mark.parametrize("m,n,with_offset", [(14336, 4096, False), (4096, 14336, True)])
+def test_full_size_layers_sampled_rows(m, n, with_offset):
+    """The benchmark's shapes and settings (p 2..4, T = 20); groups are independent, so the oracle runs on a
+    sample of rows and every plane word, scale and offset of those rows must match bit for bit."""
+    w = syn.make_weights(m, n, seed=(97, m))
+    print(f"quantize full size m={m} n={n} offset={with_offset}", flush=True)
+    planes, scales, offsets = run_gpu(w, 2, 4, 20, 128, with_offset)
+    rng = np.random.default_rng([syn.BASE_SEED, 97, m])
+    rows = np.unique(np.concatenate([[0, 1, m - 1], rng.integers(0, m, size=45)]))
+    q = oracle.quantize(np.ascontiguousarray(w[rows]), 2, 4, 20, with_offset=with_offset)
+    assert np.array_equal(planes[:, rows, :], oracle.pack(q["codes"]))
+    for p in (2, 3, 4):
+        assert np.array_equal(scales[p][:, rows, :].view(np.uint16), q["scales"][p].astype(np.float16).view(np.uint16))
+        if with_offset:
+            assert np.array_equal(offsets[p][rows, :].view(np.uint16), q["offsets"][p].astype(np.float16).view(np.uint16))

@@ -143,7 +143,7 @@ def run_suite(args, torch, bcq, syn, dev):
                 us = timed_graph(burst_mixed) * 1e3 / launches
                 pmax = int(p_req_h.max())
                 by = m * n * pmax // 8 + sum(m * (n // syn.GROUP) * q * 2 for q in sorted(set(p_req_h.tolist()))) + batch * (n + m) * 2
-                rows.append({"m": m, "n": n, "batch": batch, "p": "mixed:" + ",".join(str(v) for v in p_req_h.tolist()),
+                rows.append({"m": m, "n": n, "batch": batch, "p": "mixed:" + ",".join(str(v) for v in p_req_h.tolist()[:16]) + ("..." if batch > 16 else ""),
                              "kernel": bcq.last_kernel(), "us": round(us, 2), "GBps": round(by / us / 1e3, 1),
                              "pct_of_hbm_peak": round(100 * by / us / 1e3 / HBM_PEAK_GBS, 2)})
         del sets
@@ -152,7 +152,8 @@ def run_suite(args, torch, bcq, syn, dev):
         for (m, n) in ((14336, 4096), (4096, 14336)):
             bench_shape(m, n, (1, 2, 4, 8, 16, 32), PRECISIONS)
     elif args.suite == "mixed":
-        bench_shape(14336, 4096, (16,), PRECISIONS, mixed=True)
+        # the paper-sized case (16 requests, plane-wise kernel) and serving-sized batches (dequantising kernel)
+        bench_shape(14336, 4096, (16, 64, 256), PRECISIONS, mixed=True)
     elif args.suite == "offset":
         # asymmetric scheme next to the symmetric one, batch 1 and a dequantising batch
         for (m, n) in ((4096, 4096), (14336, 4096), (4096, 14336)):

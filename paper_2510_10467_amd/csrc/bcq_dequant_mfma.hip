@@ -69,6 +69,11 @@ struct DequantParams {
     uint32_t m;
     int batch, ngroups;                     // ngroups: steps of 128 columns
     int gshift;                             // scale groups of 64 (-1), 128 (0) or 256 (+1) columns
+    // per-request precision (dequant_mixed_kernel): a scale / offset set per precision, nullptr where there is none
+    const unsigned char *scale_sets[kMaxP + 1];
+    const unsigned char *offset_sets[kMaxP + 1];
+    const int32_t *p_req;
+    int p_max;
 };
 
 // What a thread fetches ahead: plane words and scales of its row for one group, and its share of the
@@ -290,6 +295,269 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     }
 }
 
+// ---- per-request precision -------------------------------------------------------------------------
+// The planes are shared by all precisions and only the scale sets differ (section 3.2), so one pass over
+// the planes rebuilds W_q for every precision q that occurs among the workgroup's 64 requests - the table
+// look-ups are shared, the FMAs are not - and multiplies ALL 64 requests with each of them into an
+// accumulator set of its own (the matrix pipe has room to spare); at the end every request keeps the
+// result of its own precision.  Requests are not sorted and nothing is masked.  A precision outside
+// [1, p_max] is clamped; a request whose precision has no scale set yields zeros.
+struct AheadMixed {
+    uint32_t w[kMaxP];
+    _Float16 alpha[10];                     // set q, plane i at q (q - 1) / 2 + i
+    _Float16 z[kMaxP];
+};
+
+template <int TEAMS, int RW>
+__global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantParams a)
+{
+    constexpr int kTeamThreads = 64 * RW;
+    constexpr int XU = 16 / RW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    unsigned char *lut = lds;
+    unsigned char *preq = lds + 128;          // precision of each of the 64 requests, behind the 128-byte table
+
+    const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(1);
+    const int n16 = lane & 15, kq = lane >> 4;
+    const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
+    const int b0 = blockIdx.y * 64;
+
+    if (threadIdx.x < 16) {
+        uint32_t e[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const uint32_t lo = ((tid >> (2 * c)) & 1) ? 0x3C00u : 0xBC00u;
+            const uint32_t hi = ((tid >> (2 * c + 1)) & 1) ? 0x3C00u : 0xBC00u;
+            e[c] = lo | (hi << 16);
+        }
+        *reinterpret_cast<u32x2 *>(lut + tid * 8) = u32x2{e[0], e[1]};
+    }
+    // which precisions occur: lane l looks at request b0 + l; every wave sees the same 64 requests
+    int p_lane = 0;
+    if (b0 + lane < a.batch) {
+        const int pr = a.p_req[b0 + lane];
+        p_lane = pr < 1 ? 1 : (pr > a.p_max ? a.p_max : pr);
+        if (!a.scale_sets[p_lane]) p_lane = 0;
+    }
+    if (threadIdx.x < 64) preq[lane] = (unsigned char)p_lane;
+    bool has[kMaxP + 1];
+    int p_hi = 0;
+#pragma unroll
+    for (int q = 1; q <= kMaxP; ++q) {
+        has[q] = __ballot(p_lane == q) != 0;
+        if (has[q]) p_hi = q;
+    }
+    const unsigned char *const set1 = a.scale_sets[1], *const set2 = a.scale_sets[2], *const set3 = a.scale_sets[3],
+                        *const set4 = a.scale_sets[4];
+    const unsigned char *const off1 = a.offset_sets[1], *const off2 = a.offset_sets[2], *const off3 = a.offset_sets[3],
+                        *const off4 = a.offset_sets[4];
+    auto set_of = [&](int q) { return q == 1 ? set1 : q == 2 ? set2 : q == 3 ? set3 : set4; };
+    auto off_of = [&](int q) { return q == 1 ? off1 : q == 2 ? off2 : q == 3 ? off3 : off4; };
+
+    const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
+    const uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
+    const uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
+    auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
+    const int pull = (4 * n16 + kq) * 4;
+    uint32_t xs_src[XU], xs_dst[XU];
+#pragma unroll
+    for (int k = 0; k < XU; ++k) {
+        const int unit = tid + kTeamThreads * k;
+        const int req = unit >> 4, part = unit & 15;
+        xs_src[k] = (uint32_t)min(b0 + req, a.batch - 1) * a.x_stride + part * 16;
+        xs_dst[k] = req * kXRowBytes + part * 16;
+    }
+    const unsigned char *xa_lane = xt0 + n16 * kXRowBytes + kq * 64;
+
+    auto fetch_w = [&](AheadMixed &ah, int g) {
+#pragma unroll
+        for (int i = 0; i < kMaxP; ++i) {
+            if (i < p_hi) {
+                const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
+                ah.w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(w_base + w_lane));
+            }
+        }
+#pragma unroll
+        for (int q = 1; q <= kMaxP; ++q) {
+            if (has[q]) {
+#pragma unroll
+                for (int i = 0; i < q; ++i) {
+                    const unsigned char *s_base = set_of(q) + (size_t)i * a.scale_plane_stride + scale_col(g);
+                    ah.alpha[q * (q - 1) / 2 + i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
+                }
+                if (off_of(q)) ah.z[q - 1] = *reinterpret_cast<const _Float16 *>(off_of(q) + scale_col(g) + s_lane);
+            }
+        }
+    };
+    auto fetch_x = [&](u32x4 (&xs)[XU], int g) {
+        const unsigned char *x_base = a.x + (uint32_t)g * 256;
+#pragma unroll
+        for (int k = 0; k < XU; ++k) xs[k] = *reinterpret_cast<const u32x4 *>(x_base + xs_src[k]);
+    };
+    auto store_x = [&](const u32x4 (&xs)[XU], int buf) {
+#pragma unroll
+        for (int k = 0; k < XU; ++k) *reinterpret_cast<u32x4 *>(xt0 + buf * x_tile_bytes(1) + xs_dst[k]) = xs[k];
+    };
+
+    v4f acc[kMaxP][4];
+#pragma unroll
+    for (int q = 0; q < kMaxP; ++q)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[q][u] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    auto step = [&](AheadMixed &cur, u32x4 (&cur_xs)[XU], AheadMixed &nxt, u32x4 (&nxt_xs)[XU], int g, int buf) {
+        if (g < a.ngroups) {
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.w[i]));
+#pragma unroll
+            for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(cur.alpha[i]));
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.z[i]));
+#pragma unroll
+            for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(cur_xs[k]));
+            auto handed = [&](_Float16 v) {
+                const uint32_t bits = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, v));
+                return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
+            };
+            uint32_t w[kMaxP];
+            float alpha[10], z[kMaxP];
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) w[i] = i < p_hi ? (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)cur.w[i]) : 0u;
+#pragma unroll
+            for (int q = 1; q <= kMaxP; ++q) {
+                z[q - 1] = 0.f;
+                if (has[q]) {
+#pragma unroll
+                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = handed(cur.alpha[q * (q - 1) / 2 + i]);
+                    if (off_of(q)) z[q - 1] = handed(cur.z[q - 1]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = 0.f;
+                }
+            }
+            if (g + TEAMS < a.ngroups) {
+                store_x(cur_xs, buf ^ 1);
+                fetch_w(nxt, g + TEAMS);
+                if (g + 2 * TEAMS < a.ngroups) fetch_x(nxt_xs, g + 2 * TEAMS);
+            }
+            const unsigned char *xa_cur = xa_lane + buf * x_tile_bytes(1);
+            uint32_t lo8[kMaxP], hi8[kMaxP];
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) {
+                lo8[i] = (w[i] << 3) & 0x78787878u;
+                hi8[i] = (w[i] >> 1) & 0x78787878u;
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                v4h pl[kMaxP], ph[kMaxP];
+#pragma unroll
+                for (int i = 0; i < kMaxP; ++i) {
+                    if (i < p_hi) {
+                        pl[i] = *reinterpret_cast<const v4h *>(lut + ((lo8[i] >> (8 * t)) & 0xffu));
+                        ph[i] = *reinterpret_cast<const v4h *>(lut + ((hi8[i] >> (8 * t)) & 0xffu));
+                    } else {
+                        pl[i] = ph[i] = v4h{0, 0, 0, 0};
+                    }
+                }
+                v8h xa[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + t * 16);
+#pragma unroll
+                for (int q = 1; q <= kMaxP; ++q) {
+                    if (has[q]) {
+                        float wf[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) wf[j] = z[q - 1];
+#pragma unroll
+                        for (int i = 0; i < q; ++i) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                wf[j] = fmaf((float)pl[i][j], alpha[q * (q - 1) / 2 + i], wf[j]);
+                                wf[4 + j] = fmaf((float)ph[i][j], alpha[q * (q - 1) / 2 + i], wf[4 + j]);
+                            }
+                        }
+                        v8h wb;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) wb[j] = (_Float16)wf[j];      // the single rounding of W_q to binary16
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc[q - 1][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[u], wb, acc[q - 1][u], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    };
+
+    AheadMixed ah0{}, ah1{};
+    u32x4 xs0[XU], xs1[XU];
+#pragma unroll
+    for (int k = 0; k < XU; ++k) xs0[k] = xs1[k] = u32x4{0, 0, 0, 0};
+    if (team < a.ngroups) {
+        fetch_x(xs0, team);
+        store_x(xs0, 0);
+        fetch_w(ah0, team);
+        if (team + TEAMS < a.ngroups) fetch_x(xs0, team + TEAMS);
+    }
+    __syncthreads();
+    const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
+    for (int it = 0; it < npairs; ++it) {
+        const int g = 2 * it * TEAMS + team;
+        step(ah0, xs0, ah1, xs1, g, 0);
+        step(ah1, xs1, ah0, xs0, g + TEAMS, 1);
+    }
+
+    if constexpr (TEAMS > 1) {
+        v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
+        if (team > 0) {
+#pragma unroll
+            for (int q = 0; q < kMaxP; ++q)
+                if (has[q + 1]) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) xchg[((((team - 1) * RW + wave) * kMaxP + q) * 4 + u) * 64 + lane] = acc[q][u];
+                }
+        }
+        __syncthreads();
+        if (team > 0) return;
+#pragma unroll
+        for (int k = 1; k < TEAMS; ++k)
+#pragma unroll
+            for (int q = 0; q < kMaxP; ++q)
+                if (has[q + 1]) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc[q][u] += xchg[((((k - 1) * RW + wave) * kMaxP + q) * 4 + u) * 64 + lane];
+                }
+    }
+
+    // accumulator u, register i: request b0 + 16u + 4kq + i of row row0 + n16, at each precision; keep its own
+    const uint32_t row = row0 + n16;
+    if (row < a.m) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = 16 * u + 4 * kq + i;
+                const int pb = preq[r];
+                const float v = pb == 1 ? acc[0][u][i] : pb == 2 ? acc[1][u][i] : pb == 3 ? acc[2][u][i] : pb == 4 ? acc[3][u][i] : 0.f;
+                if (b0 + r < a.batch) a.y[(size_t)(b0 + r) * a.m + row] = (_Float16)v;
+            }
+    }
+}
+
+template <int TEAMS, int RW>
+hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
+{
+    static_assert((TEAMS - 1) * RW * kMaxP * 4 * 64 * 16 <= TEAMS * 2 * x_tile_bytes(1), "accumulator exchange must fit in the tiles");
+    auto kernel = dequant_mixed_kernel<TEAMS, RW>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       lds_bytes(1, TEAMS));
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 63) / 64));
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(1, TEAMS), stream, pr);
+    return hipGetLastError();
+}
+
 template <int P, int NU, int TEAMS, int RW>
 hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
@@ -358,17 +626,15 @@ bool dequant_mfma_supports(const GemmArgs &a)
     // 32-bit byte offsets inside one plane / one scale plane / the activation matrix
     const bool small_enough = a.m * (a.n / 8) < (int64_t(1) << 31) && (int64_t)a.batch * a.n * 2 < (int64_t(1) << 31);
     const bool group_ok = (a.group == 64 || a.group == 128 || a.group == 256) && (a.n % 128) == 0;
-    return a.uniform_p >= 1 && a.uniform_p <= kMaxP && group_ok && small_enough &&
-           (a.batch + 63) / 64 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
+    // one precision for all requests, or one per request with planes stored to at most four
+    const bool p_ok = a.uniform_p > 0 ? a.uniform_p <= kMaxP : (a.p_req != nullptr && a.p_max >= 1 && a.p_max <= kMaxP);
+    return p_ok && group_ok && small_enough && (a.batch + 63) / 64 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
 }
 
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
 {
     DequantParams pr{};
     pr.planes = reinterpret_cast<const unsigned char *>(a.planes);
-    pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);
-    pr.has_offsets = a.offsets[a.uniform_p] != nullptr;
-    pr.offsets = pr.has_offsets ? reinterpret_cast<const unsigned char *>(a.offsets[a.uniform_p]) : pr.scales;
     pr.x = reinterpret_cast<const unsigned char *>(a.x);
     pr.y = a.y;
     pr.plane_stride = (uint32_t)(a.m * (a.n / 8));
@@ -380,6 +646,37 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.m = (uint32_t)a.m;
     pr.batch = a.batch;
     pr.ngroups = (int)(a.n / 128);
+    if (a.uniform_p == 0) {
+        // per-request precision: 64 requests per workgroup, 32 or 16 rows (four accumulator sets need the registers)
+        for (int q = 1; q <= kMaxP; ++q) {
+            pr.scale_sets[q] = reinterpret_cast<const unsigned char *>(a.scales[q]);
+            pr.offset_sets[q] = a.scales[q] ? reinterpret_cast<const unsigned char *>(a.offsets[q]) : nullptr;
+        }
+        pr.p_req = a.p_req;
+        pr.p_max = a.p_max;
+        // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured: 2.2, 1.75
+        // and 1.12 microseconds per workgroup and group of columns with three precisions present);
+        // BCQ_DEQUANT_SHAPE = "NU,RW" overrides the rows (benchmarks)
+        const float tiles = (float)((a.batch + 63) / 64);
+        int rw = 4;
+        float best = 0.f;
+        for (int r = 4; r >= 1; r >>= 1) {
+            const float wgs = (float)((a.m + 16 * r - 1) / (16 * r)) * tiles;
+            const float cost = (wgs <= 256.f ? 1.f : wgs / 256.f) * (r == 4 ? 2.2f : r == 2 ? 1.75f : 1.12f);
+            if (best == 0.f || cost < best) {
+                best = cost;
+                rw = r;
+            }
+        }
+        if (const char *env = getenv("BCQ_DEQUANT_SHAPE")) {
+            int e_nu = 0, e_rw = 0;
+            if (sscanf(env, "%d,%d", &e_nu, &e_rw) == 2 && (e_rw == 1 || e_rw == 2 || e_rw == 4)) rw = e_rw;
+        }
+        return rw == 4 ? launch_mixed<2, 4>(pr, a, stream) : rw == 2 ? launch_mixed<2, 2>(pr, a, stream) : launch_mixed<4, 1>(pr, a, stream);
+    }
+    pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);
+    pr.has_offsets = a.offsets[a.uniform_p] != nullptr;
+    pr.offsets = pr.has_offsets ? reinterpret_cast<const unsigned char *>(a.offsets[a.uniform_p]) : pr.scales;
     switch (a.uniform_p) {
     case 1: return launch_p<1>(pr, a, stream);
     case 2: return launch_p<2>(pr, a, stream);

@@ -153,6 +153,54 @@ def test_dequant_mfma_other_group_sizes(gpu, group):
         gpu.check_gemv(dl, 2, x, "dequant_mfma", group, offsets=offsets)
 
 
+@pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1"])
+def test_dequant_mfma_mixed(gpu, rows, monkeypatch):
+    """Per-request precision on the dequantising kernel: every workgroup shape, ragged rows and request
+    tiles, tiles in which one, some or all precisions occur, a precision without a scale set (zeros),
+    precisions outside [1, p_max] (clamped), offsets for some precisions only."""
+    monkeypatch.setenv("BCQ_DEQUANT_SHAPE", rows)
+    m, n = 150, 1536
+    layer = syn.make_layer(m, n, seed=(154, 0), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (5, 64, 130):
+        x = syn.make_x(batch, n, seed=(154, batch))
+        p_req = syn.make_p_req(batch, 1, 4, seed=(154, batch))
+        used, _ = gpu.check_mixed(dl, p_req, x, "dequant_mfma")
+        assert used == "dequant_mfma"
+        gpu.check_mixed(dl, np.full(batch, 3, dtype=np.int32), x, "dequant_mfma")           # one precision only
+        two = np.where(np.arange(batch) % 2 == 0, 2, 4).astype(np.int32)
+        gpu.check_mixed(dl, two, x, "dequant_mfma")
+    zs = {p: syn.make_offsets(p, m, n, seed=(154, p)) for p in (2, 4)}
+    x = syn.make_x(70, n, seed=(154, 70))
+    p_req = syn.make_p_req(70, 1, 4, seed=(154, 71))
+    gpu.check_mixed(dl, p_req, x, "dequant_mfma", offsets_by_p=zs)
+
+
+def test_dequant_mfma_mixed_clamps_and_missing_sets(gpu):
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    m, n, batch = 100, 1024, 40
+    layer = syn.make_layer(m, n, seed=(155, 0))
+    dl = gpu.DeviceLayer(layer)
+    x = syn.make_x(batch, n, seed=(155, 1))
+    wild = np.array([0, -3, 9, 2, 3] * 8, dtype=np.int32)                 # clamped to 1, 1, 4, 2, 3
+    clamped = np.clip(wild, 1, 4).astype(np.int32)
+    bcq.select_kernel("dequant_mfma")
+    try:
+        y_wild = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(wild), gpu.to_dev(x))
+        y_ok = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(clamped), gpu.to_dev(x))
+        some = {p: s for p, s in dl.scales.items() if p != 3}              # no scale set for precision 3
+        y_some = bcq.bcq_gemm_mixed(dl.planes, some, gpu.to_dev(clamped), gpu.to_dev(x))
+        torch.cuda.synchronize()
+        assert bcq.last_kernel() == "dequant_mfma"
+    finally:
+        bcq.select_kernel("auto")
+    assert torch.equal(y_wild, y_ok)
+    is3 = torch.from_numpy(clamped == 3).to(y_ok.device)
+    assert torch.all(y_some[is3] == 0) and torch.equal(y_some[~is3], y_ok[~is3])
+
+
 def test_forced_variant_that_cannot_run_is_an_error(gpu):
     import paper_2510_10467_amd as bcq
     layer = syn.make_layer(16, 640, seed=(160, 0))            # n is shorter than one K slice
@@ -185,6 +233,10 @@ def test_auto_dispatch_by_batch(gpu):
     assert used == "dequant_mfma"
     p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
     used, _ = gpu.check_mixed(dl, p_req, syn.make_x(40, 2048, seed=(170, 4)), "auto")
+    assert used == "plane_mfma"            # 96 rows: too short for the dequantising kernel
+    used, _ = gpu.check_mixed(big, p_req, syn.make_x(40, 1024, seed=(171, 4)), "auto")  # 40 requests
+    assert used == "dequant_mfma"
+    used, _ = gpu.check_mixed(big, p_req[:16], syn.make_x(16, 1024, seed=(171, 5)), "auto")
     assert used == "plane_mfma"
 
 

@@ -126,7 +126,8 @@ __device__ __forceinline__ float sum_over_8_lanes(float v)
 template <int PH, int NB>
 struct SliceLoads {
     u32x4 xv[NB][2];                        // 16 consecutive columns (one image unit) per request slot
-    u32x4 sc[PH];                           // the 8 scales of the lane's row, per plane
+    u32x4 sc[PH];                           // the 8 scales of the lane's row, per plane (groups of 64: the first 8 of 16)
+    u32x4 sc2[PH];                          // groups of 64 columns only: scales 8..15 of the slice
     u32x4 zc;                               // the 8 offsets of the lane's row (asymmetric scheme only)
     u32x4 wa[PH], wb[PH];                   // plane words: rows 0-7 and rows 8-15 of the block
 };
@@ -153,8 +154,8 @@ __device__ __forceinline__ u32x4 each_twice(u32x4 v)
                  __builtin_amdgcn_perm(v.y, v.y, 0x01000100u), __builtin_amdgcn_perm(v.y, v.y, 0x03020302u)};
 }
 
-// WIDE: scale groups of 256 columns (a slice has four scales per row, not eight)
-template <int PH, int NB, bool MIXED, bool OFFSET, bool WIDE>
+// GS: scale groups of 128 columns (0: a slice has eight scales per row), of 256 (+1: four) or of 64 (-1: sixteen)
+template <int PH, int NB, bool MIXED, bool OFFSET, int GS>
 __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneMfmaParams &pr, const LaneOffsets &off,
                                             const unsigned char *sbase, const unsigned char *zbase, int p_mine, int slice_c,
                                             int ngroups)
@@ -165,10 +166,10 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
     const uint32_t x_lane = off.lane < (uint32_t)ngroups * 8 ? off.lane * 32 : 0;
     const uint32_t w_lane = (off.lane & 7) < (uint32_t)ngroups ? (off.lane & 7) * 16 : 0;
     // (scale groups of 256 columns: four scales = 8 bytes per slice, spread to eight after the loads)
-    constexpr uint32_t s_bytes = WIDE ? kSliceGroups : kSliceGroups * 2;
+    constexpr uint32_t s_bytes = GS > 0 ? kSliceGroups : GS < 0 ? kSliceGroups * 4 : kSliceGroups * 2;
     const uint32_t s_slice = ngroups < kSliceGroups ? pr.scale_row_stride - s_bytes : (uint32_t)slice_c * s_bytes;
     auto load_scales = [&](const unsigned char *p) {
-        if constexpr (WIDE) {
+        if constexpr (GS > 0) {
             const v2u t = *reinterpret_cast<const v2u *>(p);
             return u32x4{t.x, t.y, 0u, 0u};
         } else {
@@ -189,9 +190,11 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
         if constexpr (MIXED) {
             const int ii = min(i, max(p_mine, 1) - 1);              // stay inside the lane's own scale set
             ld.sc[i] = load_scales(sbase + (size_t)ii * pr.scale_plane_stride + off.s + s_slice);
+            if constexpr (GS < 0) ld.sc2[i] = load_scales(sbase + (size_t)ii * pr.scale_plane_stride + off.s + s_slice + 16);
         } else {
             const unsigned char *s_base = sbase + (size_t)i * pr.scale_plane_stride + s_slice;
             ld.sc[i] = load_scales(s_base + off.s);
+            if constexpr (GS < 0) ld.sc2[i] = load_scales(s_base + off.s + 16);
         }
     }
     if constexpr (OFFSET) ld.zc = load_scales(zbase + s_slice + off.s);
@@ -210,7 +213,7 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
 // MIXED: lanes of different quarters may belong to requests of different precisions.
 // OFFSET: asymmetric scheme; zbase is the offset set of the lane's request (any readable array of that
 //         size when z_on is false: the request has none).
-template <int PH, int NB, bool MIXED, bool OFFSET, bool WIDE>
+template <int PH, int NB, bool MIXED, bool OFFSET, int GS>
 __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char *lds, int ks, int rb, int RB, int wave, int lane,
                                        const LaneOffsets &off, int p_mine, const unsigned char *sbase,
                                        const unsigned char *zbase, bool z_on)
@@ -230,7 +233,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         // delays the memory phase of all waves that share the SIMD.  The lane id is made opaque after
         // them so that no LDS address arithmetic is moved in front of the loop.
         SliceLoads<PH, NB> ld;
-        issue_loads<PH, NB, MIXED, OFFSET, WIDE>(ld, pr, off, sbase, zbase, p_mine, slice_ok ? slice : 0, ngroups);
+        issue_loads<PH, NB, MIXED, OFFSET, GS>(ld, pr, off, sbase, zbase, p_mine, slice_ok ? slice : 0, ngroups);
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" : "+v"(lane));
 
@@ -305,13 +308,13 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         if (RB > 1) __syncthreads();
 
         // scale groups of 256 columns: each of the four scales fetched serves two groups of 128
-        if constexpr (WIDE) {
+        if constexpr (GS > 0) {
 #pragma unroll
             for (int i = 0; i < PH; ++i) ld.sc[i] = each_twice(ld.sc[i]);
             if constexpr (OFFSET) ld.zc = each_twice(ld.zc);
         }
         // short last slice: its scales are the last ngroups of the eight fetched; the rest become zero
-        if (ngroups < kSliceGroups) {
+        if (GS >= 0 && ngroups < kSliceGroups) {          // (groups of 64 columns come with whole slices only)
             for (int k = ngroups; k < kSliceGroups; ++k) {
 #pragma unroll
                 for (int i = 0; i < PH; ++i) ld.sc[i] = drop_first_half(ld.sc[i]);
@@ -325,7 +328,10 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
         if (MIXED || !slice_ok) {
 #pragma unroll
             for (int i = 0; i < PH; ++i)
-                if (!(i < p_eff)) ld.sc[i] = u32x4{0, 0, 0, 0};
+                if (!(i < p_eff)) {
+                    ld.sc[i] = u32x4{0, 0, 0, 0};
+                    if constexpr (GS < 0) ld.sc2[i] = u32x4{0, 0, 0, 0};
+                }
         }
 
         // ---- 2. plane words into operand order.  LDS operations of a wave complete in order: a plane
@@ -360,21 +366,49 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 hi = *reinterpret_cast<const u32x4 *>(img_lane + (gl + 1) * L::kGroupBytes + L::kHalfBytes);
                 if constexpr (OFFSET) xsum = *reinterpret_cast<const float *>(img_xsum + (gl + 1) * L::kGroupBytes);
             }
-            v4f d[PH];
-#pragma unroll
-            for (int i = 0; i < PH; ++i) {
-                const v8i wb = expand_plane_word(wt[i][gl], sign, one);
+            if constexpr (GS < 0) {
+                // Groups of 64 columns: columns 0-63 of the 128 sit in operand registers 0-3, columns 64-127 in
+                // registers 4-7, so each half gets an instruction of its own with the other half zeroed.  The
+                // sums of a plane are taken while the next plane is in the matrix pipe.
+                const v8i xa_lo = {xa[0], xa[1], xa[2], xa[3], 0, 0, 0, 0}, xa_hi = {0, 0, 0, 0, xa[4], xa[5], xa[6], xa[7]};
                 const v4f zero = {0.f, 0.f, 0.f, 0.f};
-                // A: E5M2 activation terms (cbsz = 1), B: FP4 weight codes (blgp = 4), no block scaling
-                d[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, zero, 1, 4, 0, 0, 0, 0);
-            }
+                v4f d_lo = zero, d_hi = zero;
 #pragma unroll
-            for (int i = 0; i < PH; ++i) {
-                const uint32_t sw = ld.sc[i][gl >> 1];
-                const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
-                const float sum = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
-                // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
-                acc = fmaf(-alpha, sum, acc);
+                for (int i = 0; i <= PH; ++i) {
+                    v4f n_lo = zero, n_hi = zero;
+                    if (i < PH) {
+                        const v8i wb = expand_plane_word(wt[i][gl], sign, one);
+                        n_lo = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa_lo, wb, zero, 1, 4, 0, 0, 0, 0);
+                        n_hi = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa_hi, wb, zero, 1, 4, 0, 0, 0, 0);
+                    }
+                    if (i > 0) {
+                        // scales 2 gl and 2 gl + 1 of the slice: the two halves of dword gl of the sixteen fetched
+                        const uint32_t sw = gl < 4 ? ld.sc[i - 1][gl & 3] : ld.sc2[i - 1][gl & 3];
+                        const float a_lo = (float)__builtin_bit_cast(_Float16, (unsigned short)(sw & 0xffffu));
+                        const float a_hi = (float)__builtin_bit_cast(_Float16, (unsigned short)(sw >> 16));
+                        acc = fmaf(-a_lo, (d_lo[0] + d_lo[1]) + (d_lo[2] + d_lo[3]), acc);
+                        acc = fmaf(-a_hi, (d_hi[0] + d_hi[1]) + (d_hi[2] + d_hi[3]), acc);
+                    }
+                    d_lo = n_lo;
+                    d_hi = n_hi;
+                }
+            } else {
+                v4f d[PH];
+#pragma unroll
+                for (int i = 0; i < PH; ++i) {
+                    const v8i wb = expand_plane_word(wt[i][gl], sign, one);
+                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+                    // A: E5M2 activation terms (cbsz = 1), B: FP4 weight codes (blgp = 4), no block scaling
+                    d[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa, wb, zero, 1, 4, 0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < PH; ++i) {
+                    const uint32_t sw = ld.sc[i][gl >> 1];
+                    const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
+                    const float sum = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
+                    // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
+                    acc = fmaf(-alpha, sum, acc);
+                }
             }
             // groups stay in order: deferring the sums would keep every MFMA result register alive
             __builtin_amdgcn_sched_barrier(0);
@@ -387,10 +421,11 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
 
 // Waves per workgroup.  Four requests of mixed precision per tile need more registers than a 16-wave
 // workgroup leaves a wave (128), and their operand image limits the waves per CU anyway: they stop at 8.
-__host__ __device__ constexpr int max_waves(int NB, bool mixed) { return NB == 4 && mixed ? 8 : 16; }
+// So do groups of 64 columns (twice the scales and two results per plane in flight).
+__host__ __device__ constexpr int max_waves(int NB, bool mixed, int gs = 0) { return (NB == 4 && mixed) || gs < 0 ? 8 : 16; }
 
-template <int P, int NB, bool MIXED, bool OFFSET, bool MULTI = false, bool WIDE = false>
-__global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(PlaneMfmaParams pr_in)
+template <int P, int NB, bool MIXED, bool OFFSET, bool MULTI = false, int GS = 0>
+__global__ __launch_bounds__(64 * max_waves(NB, MIXED, GS)) void plane_mfma_kernel(PlaneMfmaParams pr_in)
 {
     PlaneMfmaParams pr = pr_in;               // MULTI kernels overwrite the per-matrix fields below
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -458,7 +493,7 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
 
     float acc = 0.f;
     if constexpr (!MIXED) {
-        acc = sweep<P, NB, false, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P], pr.offsets[P], true);
+        acc = sweep<P, NB, false, OFFSET, GS>(pr, lds, ks, rb, RB, wave, lane, off, P, pr.scales[P], pr.offsets[P], true);
     } else {
         // precision of the request this lane reports on, and the deepest plane any request of the tile needs.
         // The four precisions of the tile are fetched together, and scale sets are picked by comparison
@@ -487,10 +522,10 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED)) void plane_mfma_kernel(P
         }
         // one straight-line sweep per possible depth: only planes 0 .. p_hi-1 are fetched
         switch (p_hi) {
-        case 1: acc = sweep<1, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
-        case 2: acc = sweep<2, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
-        case 3: acc = sweep<3, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
-        case 4: acc = sweep<4, NB, true, OFFSET, WIDE>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 1: acc = sweep<1, NB, true, OFFSET, GS>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 2: acc = sweep<2, NB, true, OFFSET, GS>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 3: acc = sweep<3, NB, true, OFFSET, GS>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
+        case 4: acc = sweep<4, NB, true, OFFSET, GS>(pr, lds, ks, rb, RB, wave, lane, off, p_mine, sbase, zbase, z_on); break;
         default: break;                                             // no request has a scale set: zeros
         }
     }
@@ -534,7 +569,7 @@ Plan make_plan(const GemmArgs &a, bool share_row_blocks = true)
     const int nslices = (int)((a.n + kSliceCols - 1) / kSliceCols);
     Plan pl;
     pl.NB = a.batch == 1 ? 1 : a.batch == 2 ? 2 : 4;
-    const int wave_cap = max_waves(pl.NB, a.uniform_p == 0);
+    const int wave_cap = max_waves(pl.NB, a.uniform_p == 0, a.group == 64 ? -1 : 0);
     int ks_cap = wave_cap;
     while (ks_cap > 1 && (size_t)lds_total(pl.NB, ks_cap, 1) > lds_budget()) --ks_cap;
     int KS = 1;
@@ -568,23 +603,26 @@ hipError_t launch_one(K kernel, const PlaneMfmaParams &pr, const Plan &pl, dim3 
     return hipGetLastError();
 }
 
-template <int NB, bool OFFSET, bool WIDE>
+template <int NB, bool OFFSET, int GS>
 hipError_t launch_group(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
 {
-    if (a.uniform_p == 0) return launch_one(plane_mfma_kernel<kMaxP, NB, true, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
+    if (a.uniform_p == 0) return launch_one(plane_mfma_kernel<kMaxP, NB, true, OFFSET, false, GS>, pr, pl, grid, block, stream);
     switch (a.uniform_p) {
-    case 1: return launch_one(plane_mfma_kernel<1, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
-    case 2: return launch_one(plane_mfma_kernel<2, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
-    case 3: return launch_one(plane_mfma_kernel<3, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
-    default: return launch_one(plane_mfma_kernel<4, NB, false, OFFSET, false, WIDE>, pr, pl, grid, block, stream);
+    case 1: return launch_one(plane_mfma_kernel<1, NB, false, OFFSET, false, GS>, pr, pl, grid, block, stream);
+    case 2: return launch_one(plane_mfma_kernel<2, NB, false, OFFSET, false, GS>, pr, pl, grid, block, stream);
+    case 3: return launch_one(plane_mfma_kernel<3, NB, false, OFFSET, false, GS>, pr, pl, grid, block, stream);
+    default: return launch_one(plane_mfma_kernel<4, NB, false, OFFSET, false, GS>, pr, pl, grid, block, stream);
     }
 }
 
 template <int NB, bool OFFSET>
 hipError_t launch_nb(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
 {
-    return a.group == 256 ? launch_group<NB, OFFSET, true>(a, pr, pl, grid, block, stream)
-                          : launch_group<NB, OFFSET, false>(a, pr, pl, grid, block, stream);
+    if constexpr (!OFFSET) {
+        if (a.group == 64) return launch_group<NB, false, -1>(a, pr, pl, grid, block, stream);
+    }
+    return a.group == 256 ? launch_group<NB, OFFSET, 1>(a, pr, pl, grid, block, stream)
+                          : launch_group<NB, OFFSET, 0>(a, pr, pl, grid, block, stream);
 }
 
 template <int NB>
@@ -607,7 +645,11 @@ bool plane_mfma_supports(const GemmArgs &a)
                               a.m < (int64_t(1) << 24) && a.n < (int64_t(1) << 24);
     // whole scale groups, 4-byte aligned scale rows, and at least eight groups of 128 per row (the scales of
     // a short last slice are fetched as the last ones of the row); scale groups of 128 or 256 columns
-    const bool group_ok = (a.group == 128 && (a.n % 256) == 0) || (a.group == 256 && (a.n % 512) == 0);
+    // groups of 64 (two matrix instructions per 128 columns, one per half): whole K slices, symmetric scheme
+    bool any_offsets = false;
+    for (int q = 1; q <= kMaxP; ++q) any_offsets = any_offsets || a.offsets[q] != nullptr;
+    const bool group_ok = (a.group == 128 && (a.n % 256) == 0) || (a.group == 256 && (a.n % 512) == 0) ||
+                          (a.group == 64 && (a.n % kSliceCols) == 0 && !any_offsets);
     return group_ok && a.n >= kSliceCols && a.p_max <= kMaxP && small_enough &&
            ((a.m + 15) / 16 + 8) * ((a.batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);
 }

@@ -140,6 +140,27 @@ def test_plane_mfma_groups_of_256(gpu, m, n):
     assert used == "plane_mfma"
 
 
+@pytest.mark.parametrize("m,n", [(37, 2048), (20, 1024), (130, 4096), (24, 9216)])
+def test_plane_mfma_groups_of_64(gpu, m, n):
+    """Scale groups of 64 columns: sixteen scales per K slice, one matrix instruction per half group.
+    9216 columns run as two chunks of slices."""
+    layer = syn.make_layer(m, n, group=64, seed=(156, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 2, 3, 9):
+        x = syn.make_x(batch, n, seed=(156, batch))
+        for p in (1, 2, 3, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "plane_mfma", 64)
+            assert used == "plane_mfma"
+        p_req = syn.make_p_req(batch, 1, 4, seed=(156, batch))
+        gpu.check_mixed(dl, p_req, x, "plane_mfma", 64)
+    used, _ = gpu.check_gemv(dl, 2, syn.make_x(1, n, seed=(156, 99)), "auto", 64)
+    assert used == "plane_mfma"
+    # the asymmetric scheme and ragged widths stay on the other kernels
+    z = syn.make_offsets(2, m, n, 64, seed=(156, 1))
+    used, _ = gpu.check_gemv(dl, 2, syn.make_x(1, n, seed=(156, 98)), "auto", 64, offsets=z)
+    assert used != "plane_mfma"
+
+
 @pytest.mark.parametrize("group", [64, 256])
 def test_dequant_mfma_other_group_sizes(gpu, group):
     layer = syn.make_layer(150, 1536, group=group, seed=(153, group), signed=True)

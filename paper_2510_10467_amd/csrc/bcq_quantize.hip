@@ -405,7 +405,8 @@ hipError_t launch_lanes(const QuantParams &pr, bool offset, hipStream_t stream)
 bool quantize_supports(int64_t m, int64_t n, int group)
 {
     const bool group_ok = group == 32 || group == 64 || group == 128 || group == 256;
-    return group_ok && m >= 1 && n >= group && n % group == 0 && (m * n) / 32 + 255 < (int64_t(1) << 32) * 256;
+    // one thread per 32-column word, 256 per workgroup, at most 2^31 - 1 workgroups
+    return group_ok && m >= 1 && n >= group && n % group == 0 && ((m * n) / 32 + 255) / 256 < (int64_t(1) << 31);
 }
 
 hipError_t quantize_launch(const _Float16 *w, int p_low, int p_high, int cycles, uint32_t *planes, _Float16 *const *scales_by_p,

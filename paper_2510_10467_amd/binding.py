@@ -40,6 +40,8 @@ def lib() -> ctypes.CDLL:
         L.bcq_strerror.restype = ctypes.c_char_p
         L.bcq_strerror.argtypes = [i32]
         L.bcq_select_kernel.argtypes = [i32]
+        L.bcq_select_dequant_shape.argtypes = [i32, i32]
+        L.bcq_select_dequant_shape.restype = i32
         L.bcq_last_kernel.restype = ctypes.c_char_p
         L.bcq_pack.argtypes = [vp, vp, i32, i64, i64, vp]
         L.bcq_unpack.argtypes = [vp, vp, i32, i64, i64, vp]
@@ -85,6 +87,11 @@ def select_kernel(variant) -> None:
     """Force a kernel variant by name or id ('auto' restores the default choice)."""
     vid = KERNEL_IDS[variant] if isinstance(variant, str) else int(variant)
     _check(lib().bcq_select_kernel(vid), "bcq_select_kernel")
+
+
+def select_dequant_shape(request_tiles: int = 0, row_blocks: int = 0) -> None:
+    """Benchmarks and tests: force the workgroup shape of the large-batch kernel ((0, 0) = automatic)."""
+    _check(lib().bcq_select_dequant_shape(int(request_tiles), int(row_blocks)), "bcq_select_dequant_shape")
 
 
 def last_kernel() -> str:

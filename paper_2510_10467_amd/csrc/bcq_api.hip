@@ -96,6 +96,11 @@ int bcq_select_kernel(int variant)
 
 const char *bcq_last_kernel(void) { return g_last; }
 
+int bcq_select_dequant_shape(int request_tiles, int row_blocks)
+{
+    return bcq::dequant_mfma_force_shape(request_tiles, row_blocks) ? BCQ_OK : BCQ_ERR_VARIANT;
+}
+
 int bcq_pack(const int8_t *codes, uint32_t *planes, int n_planes, int64_t m, int64_t n, void *stream)
 {
     if (!codes || !planes) return BCQ_ERR_NULL;

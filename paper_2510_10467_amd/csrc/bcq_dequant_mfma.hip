@@ -33,9 +33,6 @@
 // from measured per-shape costs (launch_p).
 #include <hip/hip_runtime.h>
 
-#include <cstdio>
-#include <cstdlib>
-
 #include "bcq_internal.hpp"
 
 namespace bcq {
@@ -48,6 +45,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxP = 4;
+int g_forced_nu = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2 + 16;    // padded LDS row of one request's 128 activations: rows start 4 banks apart
 
@@ -579,7 +577,7 @@ hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t st
 // (rounds of workgroups over the 256 CUs) x (time of one workgroup per group of columns).  The second factor
 // was measured for every shape on a grid that fills the chip once (microseconds per group, p = 4 and p = 2):
 // larger workgroups reuse dequantised weights and staged activations better, smaller ones keep CUs busy on
-// short matrices.  The cheapest product wins.  BCQ_DEQUANT_SHAPE = "NU,RW" overrides the choice (benchmarks).
+// short matrices.  The cheapest product wins; dequant_mfma_force_shape overrides the choice (benchmarks, tests).
 struct WgShape {
     int nu, rw;
     float us_p4, us_p2;
@@ -601,12 +599,9 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
             rw = c.rw;
         }
     }
-    if (const char *env = getenv("BCQ_DEQUANT_SHAPE")) {
-        int e_nu = 0, e_rw = 0;
-        if (sscanf(env, "%d,%d", &e_nu, &e_rw) == 2) {
-            nu = e_nu;
-            rw = e_rw;
-        }
+    if (g_forced_nu > 0) {
+        nu = g_forced_nu;
+        rw = g_forced_rw;
     }
     switch (nu * 10 + rw) {
     case 14: return launch_one<P, 1, 4, 4>(pr, a, stream);
@@ -620,6 +615,20 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
 }
 
 }  // namespace
+
+bool dequant_mfma_force_shape(int request_tiles, int row_blocks)
+{
+    const int key = request_tiles * 10 + row_blocks;
+    const bool known = key == 14 || key == 12 || key == 11 || key == 24 || key == 22 || key == 44;
+    if (request_tiles == 0 && row_blocks == 0) {
+        g_forced_nu = g_forced_rw = 0;
+        return true;
+    }
+    if (!known) return false;
+    g_forced_nu = request_tiles;
+    g_forced_rw = row_blocks;
+    return true;
+}
 
 bool dequant_mfma_supports(const GemmArgs &a)
 {
@@ -656,7 +665,7 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
         pr.p_max = a.p_max;
         // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured: 2.2, 1.75
         // and 1.12 microseconds per workgroup and group of columns with three precisions present);
-        // BCQ_DEQUANT_SHAPE = "NU,RW" overrides the rows (benchmarks)
+        // a forced shape overrides the rows (benchmarks, tests)
         const float tiles = (float)((a.batch + 63) / 64);
         int rw = 4;
         float best = 0.f;
@@ -668,10 +677,7 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
                 rw = r;
             }
         }
-        if (const char *env = getenv("BCQ_DEQUANT_SHAPE")) {
-            int e_nu = 0, e_rw = 0;
-            if (sscanf(env, "%d,%d", &e_nu, &e_rw) == 2 && (e_rw == 1 || e_rw == 2 || e_rw == 4)) rw = e_rw;
-        }
+        if (g_forced_nu > 0) rw = g_forced_rw;
         return rw == 4 ? launch_mixed<2, 4>(pr, a, stream) : rw == 2 ? launch_mixed<2, 2>(pr, a, stream) : launch_mixed<4, 1>(pr, a, stream);
     }
     pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);

@@ -49,6 +49,8 @@ bool plane_mfma_supports_multi(const GemmArgs *mats, int count);
 hipError_t plane_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t stream);
 
 bool dequant_mfma_supports(const GemmArgs &a);
+// benchmarks and tests: force the workgroup shape (request tiles of 64, blocks of 16 rows); (0, 0) = automatic
+bool dequant_mfma_force_shape(int request_tiles, int row_blocks);
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream);
 
 // Offline quantiser (Algorithm 1): group must be 32, 64, 128 or 256; 1 <= p_low <= p_high <= 4.

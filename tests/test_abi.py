@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_gemv_offset", "bcq_gemm_mixed_offset", "bcq_gemv_multi",
-            "bcq_quantize", "bcq_bench_stream_read", "bcq_bench_fp16_gemv", "bcq_strerror", "bcq_select_kernel", "bcq_last_kernel"} <= set(names)
+            "bcq_quantize", "bcq_bench_stream_read", "bcq_bench_fp16_gemv", "bcq_strerror", "bcq_select_kernel", "bcq_select_dequant_shape", "bcq_last_kernel"} <= set(names)
     for name in names:
         assert hasattr(lib, name), f"{name} declared in include/ but not exported"
 
@@ -128,6 +128,9 @@ def test_argument_validation_without_device(lib):
     assert lib.bcq_pack(0x1000, 0x2000, 4, 8, 48, None) == -3
     assert lib.bcq_pack(0x1000, 0x2000, 0, 8, 64, None) == -2
     assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1
+    assert lib.bcq_select_dequant_shape(3, 4) == -6
+    assert lib.bcq_select_dequant_shape(2, 2) == 0
+    assert lib.bcq_select_dequant_shape(0, 0) == 0
     assert lib.bcq_select_kernel(17) == -6
     assert lib.bcq_select_kernel(0) == 0
 

@@ -64,6 +64,18 @@ def test_sign_select_mixed(gpu, m, n, group):
         gpu.check_mixed(dl, p_req, x, "sign_select", group)
 
 
+@pytest.fixture
+def forced_shape():
+    """Force a workgroup shape of the large-batch kernel ("tiles,row blocks") for one test."""
+    import paper_2510_10467_amd as bcq
+
+    def force(shape):
+        tiles, rows = (int(v) for v in shape.split(","))
+        bcq.select_dequant_shape(tiles, rows)
+    yield force
+    bcq.select_dequant_shape(0, 0)
+
+
 PLANE_MFMA_SHAPES = [
     # m, n: one and several K slices of 1024 columns, ragged row tails, chunked K (n = 28672),
     # short last slices of 2, 6, 1+... groups (n a multiple of 256 but not of 1024; 17920 is the Phi-4 width)
@@ -105,10 +117,10 @@ def test_dequant_mfma_uniform(gpu, m, n):
 
 
 @pytest.mark.parametrize("shape", ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
-def test_dequant_mfma_every_workgroup_shape(gpu, shape, monkeypatch):
+def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape):
     """The kernel picks its workgroup shape (request tiles, row blocks) from m and the batch; small test
     matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles)."""
-    monkeypatch.setenv("BCQ_DEQUANT_SHAPE", shape)
+    forced_shape(shape)
     layer = syn.make_layer(200, 1536, seed=(151, 0), signed=True)
     dl = gpu.DeviceLayer(layer)
     offsets = syn.make_offsets(3, 200, 1536, seed=(151, 1))
@@ -175,11 +187,11 @@ def test_dequant_mfma_other_group_sizes(gpu, group):
 
 
 @pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1"])
-def test_dequant_mfma_mixed(gpu, rows, monkeypatch):
+def test_dequant_mfma_mixed(gpu, rows, forced_shape):
     """Per-request precision on the dequantising kernel: every workgroup shape, ragged rows and request
     tiles, tiles in which one, some or all precisions occur, a precision without a scale set (zeros),
     precisions outside [1, p_max] (clamped), offsets for some precisions only."""
-    monkeypatch.setenv("BCQ_DEQUANT_SHAPE", rows)
+    forced_shape(rows)
     m, n = 150, 1536
     layer = syn.make_layer(m, n, seed=(154, 0), signed=True)
     dl = gpu.DeviceLayer(layer)

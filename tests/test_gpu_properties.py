@@ -104,6 +104,28 @@ def test_one_hot_readout_and_symmetries(gpu, oracle):
             bcq.select_kernel("auto")
 
 
+@pytest.mark.parametrize("m,n,batch", [(14336, 4096, 16), (14336, 4096, 96), (4096, 14336, 200)])
+def test_full_size_mixed_precision_sampled_rows(gpu, oracle, m, n, batch):
+    """Per-request precision at the benchmark's shapes: the paper-sized batch on the plane-wise kernel, serving-sized
+    ones on the dequantising kernel, and on the latter the same bits as its uniform-precision path per request."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    layer = syn.make_layer(m, n, seed=(231, m, n))
+    dl = gpu.DeviceLayer(layer)
+    x = syn.make_x(batch, n, seed=(231, batch))
+    p_req = syn.make_p_req(batch, 2, 4, seed=(231, batch))
+    y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req), gpu.to_dev(x))
+    torch.cuda.synchronize()
+    assert bcq.last_kernel() == ("plane_mfma" if batch < 40 else "dequant_mfma")
+    rng = np.random.default_rng([syn.BASE_SEED, 231, m])
+    rows = np.unique(np.concatenate([[0, 15, 16, m - 1], rng.integers(0, m, size=60)]))
+    sub = {p: np.ascontiguousarray(s[:, rows, :]) for p, s in layer.scales.items()}
+    y_ref, a_ref = oracle.gemm_mixed(np.ascontiguousarray(layer.planes[:, rows, :]), sub, p_req, x)
+    err = np.abs(y.cpu().numpy().astype(np.float64)[:, rows] - y_ref)
+    assert np.all(err <= oracle.tolerance(y_ref, a_ref))
+
+
 def test_mixed_equals_uniform_per_request_and_request_permutation(gpu):
     import torch
 

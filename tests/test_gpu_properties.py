@@ -107,7 +107,7 @@ def test_one_hot_readout_and_symmetries(gpu, oracle):
 @pytest.mark.parametrize("m,n,batch", [(14336, 4096, 16), (14336, 4096, 96), (4096, 14336, 200)])
 def test_full_size_mixed_precision_sampled_rows(gpu, oracle, m, n, batch):
     """Per-request precision at the benchmark's shapes: the paper-sized batch on the plane-wise kernel, serving-sized
-    ones on the dequantising kernel, and on the latter the same bits as its uniform-precision path per request."""
+    ones on the dequantising kernel."""
     import torch
 
     import paper_2510_10467_amd as bcq

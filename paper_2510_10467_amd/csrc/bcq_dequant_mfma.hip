@@ -6,8 +6,10 @@
 //
 // A team of RW waves (RW = 4, 2 or 1) owns 16 RW weight rows (16 per wave) and TB = 64, 128 or 256 requests.
 // Per group of 128 columns
-//   * the team stages the TB x 128 activation tile in LDS (fetched one group ahead with fully
-//     coalesced loads into registers, stored into the tile the previous group has just left);
+//   * the team stages the TB x 128 activation tile of the NEXT group in LDS with loads that write LDS
+//     directly (global_load_lds_dwordx4: 64 lanes deliver 1 KiB = four requests' rows, no registers, no
+//     LDS store instructions), into the tile the previous group has just left; a request's sixteen
+//     16-byte parts sit XOR-permuted by the request number so that operand reads spread over all banks;
 //   * lane (row, kq) of a wave holds word kq of its row's group from each plane plus the group's
 //     scales (also one group ahead).  Matrix step t covers the columns 32 kq + 8 t + j of the group
 //     (a permutation of K that the activation operand follows), so for each step the lane takes
@@ -47,7 +49,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kMaxP = 4;
 int g_forced_nu = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
-constexpr int kXRowBytes = 128 * 2 + 16;    // padded LDS row of one request's 128 activations: rows start 4 banks apart
+constexpr int kXRowBytes = 128 * 2;         // LDS row of one request's 128 activations; its sixteen parts sit XOR-permuted
 
 constexpr int x_tile_bytes(int nu) { return 64 * nu * kXRowBytes; }
 constexpr int lds_bytes(int nu, int teams) { return kLutBytes + teams * 2 * x_tile_bytes(nu); }
@@ -81,7 +83,6 @@ struct Ahead {
     uint32_t w[P];
     _Float16 alpha[P];
     _Float16 z;
-    u32x4 xs[XU];
 };
 
 // NU: 64-request tiles per workgroup; TEAMS: teams of waves (K split inside the workgroup); RW: waves per
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NU);     // the team's two activation tiles, used alternately
+    constexpr int kTile = x_tile_bytes(NU);
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
     const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
@@ -127,16 +129,22 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;      // byte index of the lane to take from
     // staging: unit tid + kTeamThreads * k of the tile = request (unit >> 4), 16-byte part (unit & 15) of its 256 bytes
-    uint32_t xs_src[XU], xs_dst[XU];
+    // Staging straight into LDS: load instruction i of a tile (i = k * RW + wave) brings the 1 KiB of requests
+    // 4i .. 4i+3; lane l delivers the 16 bytes that land at chunk l of that KiB, which is part
+    // (l & 15) ^ (request & 15) of request 4i + (l >> 4): rows are 256 bytes apart and the XOR spreads the
+    // operand reads of sixteen requests over all banks.
+    uint32_t xs_src[XU];
 #pragma unroll
     for (int k = 0; k < XU; ++k) {
-        const int unit = tid + kTeamThreads * k;
-        const int req = unit >> 4, part = unit & 15;
+        const int req = 4 * (k * RW + wave) + (lane >> 4);
+        const int part = (lane & 15) ^ (req & 15);
         xs_src[k] = (uint32_t)min(b0 + req, a.batch - 1) * a.x_stride + part * 16;
-        xs_dst[k] = req * kXRowBytes + part * 16;
     }
-    // A operand of request tile u, step t: 16 bytes at (16u + n16) * kXRowBytes + (32kq + 8t) * 2
-    const unsigned char *xa_lane = xt0 + n16 * kXRowBytes + kq * 64;
+    // A operand of request tile u, step t: request 16u + n16, part 4kq + t
+    const unsigned char *xa_lane = xt0 + n16 * kXRowBytes;
+    uint32_t xa_off[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) xa_off[t] = (uint32_t)(((4 * kq + t) ^ n16) * 16);
 
     auto fetch_w = [&](Ahead<P, XU> &ah, int g) {
 #pragma unroll
@@ -149,14 +157,12 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
         }
         ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + scale_col(g) + s_lane);
     };
-    auto fetch_x = [&](Ahead<P, XU> &ah, int g) {
+    auto stage_x = [&](int g, int buf) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
 #pragma unroll
-        for (int k = 0; k < XU; ++k) ah.xs[k] = *reinterpret_cast<const u32x4 *>(x_base + xs_src[k]);
-    };
-    auto store_x = [&](const Ahead<P, XU> &ah, int buf) {
-#pragma unroll
-        for (int k = 0; k < XU; ++k) *reinterpret_cast<u32x4 *>(xt0 + buf * x_tile_bytes(NU) + xs_dst[k]) = ah.xs[k];
+        for (int k = 0; k < XU; ++k)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
+                                             (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
     };
 
     v4f acc[4 * NU];
@@ -173,8 +179,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
 #pragma unroll
         for (int i = 0; i < P; ++i) asm volatile("" : "+v"(cur.w[i]), "+v"(cur.alpha[i]));
         asm volatile("" : "+v"(cur.z));
-#pragma unroll
-        for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(cur.xs[k]));
         const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.z));
         const float z = a.has_offsets ? (float)__builtin_bit_cast(_Float16, (unsigned short)zb) : 0.f;
         uint32_t w[P];
@@ -186,11 +190,10 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             alpha[i] = (float)__builtin_bit_cast(_Float16, (unsigned short)ab);
         }
         if (g + TEAMS < a.ngroups) {
-            store_x(cur, buf ^ 1);              // that tile was last read before the previous barrier
+            stage_x(g + TEAMS, buf ^ 1);        // that tile was last read before the previous barrier
             fetch_w(nxt, g + TEAMS);
-            if (g + 2 * TEAMS < a.ngroups) fetch_x(nxt, g + 2 * TEAMS);
         }
-        const unsigned char *xa_cur = xa_lane + buf * x_tile_bytes(NU);
+        const unsigned char *xa_cur = xa_lane + buf * kTile;
         // table offsets of all low and all high nibbles of a plane word at once: byte t of `lo8` (`hi8`) is
         // eight times the low (high) nibble of byte t
         uint32_t lo8[P], hi8[P];
@@ -211,10 +214,10 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             }
             v8h xa[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + t * 16);
+            for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
             // (sixteen waves leave a wave 128 registers, too few to hold the operands across the arithmetic:
             // there the compiler is left to place the reads itself)
-            if constexpr (RW * TEAMS <= 8) __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0);
             float wf[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) wf[j] = z;
@@ -236,7 +239,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
                 if (c + 1 < NU) {
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        xn[u] = *reinterpret_cast<const v8h *>(xa_cur + (4 * (c + 1) + u) * (16 * kXRowBytes) + t * 16);
+                        xn[u] = *reinterpret_cast<const v8h *>(xa_cur + (4 * (c + 1) + u) * (16 * kXRowBytes) + xa_off[t]);
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) acc[4 * c + u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[u], wb, acc[4 * c + u], 0, 0, 0);
@@ -247,16 +250,16 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             }
         }
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
         __syncthreads();                        // tile `buf` free, the other tile complete
     };
 
     Ahead<P, XU> ah0, ah1;
     if (team < a.ngroups) {
-        fetch_x(ah0, team);
-        store_x(ah0, 0);
+        stage_x(team, 0);
         fetch_w(ah0, team);
-        if (team + TEAMS < a.ngroups) fetch_x(ah0, team + TEAMS);
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();                            // table and first tiles complete
     const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
     for (int it = 0; it < npairs; ++it) {
@@ -318,6 +321,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
     const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(1);
+    constexpr int kTile = x_tile_bytes(1);
     const int n16 = lane & 15, kq = lane >> 4;
     const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
     const int b0 = blockIdx.y * 64;
@@ -359,15 +363,18 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
     const uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
     auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;
-    uint32_t xs_src[XU], xs_dst[XU];
+    // staging straight into LDS and the XOR placement of the parts: as in dequant_mfma_kernel
+    uint32_t xs_src[XU];
 #pragma unroll
     for (int k = 0; k < XU; ++k) {
-        const int unit = tid + kTeamThreads * k;
-        const int req = unit >> 4, part = unit & 15;
+        const int req = 4 * (k * RW + wave) + (lane >> 4);
+        const int part = (lane & 15) ^ (req & 15);
         xs_src[k] = (uint32_t)min(b0 + req, a.batch - 1) * a.x_stride + part * 16;
-        xs_dst[k] = req * kXRowBytes + part * 16;
     }
-    const unsigned char *xa_lane = xt0 + n16 * kXRowBytes + kq * 64;
+    const unsigned char *xa_lane = xt0 + n16 * kXRowBytes;
+    uint32_t xa_off[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) xa_off[t] = (uint32_t)(((4 * kq + t) ^ n16) * 16);
 
     auto fetch_w = [&](AheadMixed &ah, int g) {
 #pragma unroll
@@ -389,14 +396,12 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
             }
         }
     };
-    auto fetch_x = [&](u32x4 (&xs)[XU], int g) {
+    auto stage_x = [&](int g, int buf) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
 #pragma unroll
-        for (int k = 0; k < XU; ++k) xs[k] = *reinterpret_cast<const u32x4 *>(x_base + xs_src[k]);
-    };
-    auto store_x = [&](const u32x4 (&xs)[XU], int buf) {
-#pragma unroll
-        for (int k = 0; k < XU; ++k) *reinterpret_cast<u32x4 *>(xt0 + buf * x_tile_bytes(1) + xs_dst[k]) = xs[k];
+        for (int k = 0; k < XU; ++k)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
+                                             (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
     };
 
     v4f acc[kMaxP][4];
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc[q][u] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    auto step = [&](AheadMixed &cur, u32x4 (&cur_xs)[XU], AheadMixed &nxt, u32x4 (&nxt_xs)[XU], int g, int buf) {
+    auto step = [&](AheadMixed &cur, AheadMixed &nxt, int g, int buf) {
         if (g < a.ngroups) {
 #pragma unroll
             for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.w[i]));
@@ -413,8 +418,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
             for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(cur.alpha[i]));
 #pragma unroll
             for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.z[i]));
-#pragma unroll
-            for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(cur_xs[k]));
             auto handed = [&](_Float16 v) {
                 const uint32_t bits = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, v));
                 return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
@@ -436,11 +439,10 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
                 }
             }
             if (g + TEAMS < a.ngroups) {
-                store_x(cur_xs, buf ^ 1);
+                stage_x(g + TEAMS, buf ^ 1);
                 fetch_w(nxt, g + TEAMS);
-                if (g + 2 * TEAMS < a.ngroups) fetch_x(nxt_xs, g + 2 * TEAMS);
             }
-            const unsigned char *xa_cur = xa_lane + buf * x_tile_bytes(1);
+            const unsigned char *xa_cur = xa_lane + buf * kTile;
             uint32_t lo8[kMaxP], hi8[kMaxP];
 #pragma unroll
             for (int i = 0; i < kMaxP; ++i) {
@@ -461,7 +463,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
                 }
                 v8h xa[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + t * 16);
+                for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
 #pragma unroll
                 for (int q = 1; q <= kMaxP; ++q) {
                     if (has[q]) {
@@ -485,25 +487,22 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
                 }
             }
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
         __syncthreads();
     };
 
     AheadMixed ah0{}, ah1{};
-    u32x4 xs0[XU], xs1[XU];
-#pragma unroll
-    for (int k = 0; k < XU; ++k) xs0[k] = xs1[k] = u32x4{0, 0, 0, 0};
     if (team < a.ngroups) {
-        fetch_x(xs0, team);
-        store_x(xs0, 0);
+        stage_x(team, 0);
         fetch_w(ah0, team);
-        if (team + TEAMS < a.ngroups) fetch_x(xs0, team + TEAMS);
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
     for (int it = 0; it < npairs; ++it) {
         const int g = 2 * it * TEAMS + team;
-        step(ah0, xs0, ah1, xs1, g, 0);
-        step(ah1, xs1, ah0, xs0, g + TEAMS, 1);
+        step(ah0, ah1, g, 0);
+        step(ah1, ah0, g + TEAMS, 1);
     }
 
     if constexpr (TEAMS > 1) {
@@ -582,8 +581,8 @@ struct WgShape {
     int nu, rw;
     float us_p4, us_p2;
 };
-constexpr WgShape kShapes[] = {{1, 4, 1.20f, 0.77f}, {1, 2, 0.76f, 0.51f}, {1, 1, 0.60f, 0.49f},
-                               {2, 4, 1.77f, 1.25f}, {2, 2, 1.54f, 1.10f}, {4, 4, 3.50f, 3.20f}};
+constexpr WgShape kShapes[] = {{1, 4, 1.15f, 0.70f}, {1, 2, 0.70f, 0.50f}, {1, 1, 0.50f, 0.40f},
+                               {2, 4, 1.60f, 1.10f}, {2, 2, 1.00f, 0.85f}, {4, 4, 2.60f, 2.10f}};
 
 template <int P>
 hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
@@ -663,15 +662,16 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
         }
         pr.p_req = a.p_req;
         pr.p_max = a.p_max;
-        // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured: 2.2, 1.75
-        // and 1.12 microseconds per workgroup and group of columns with three precisions present);
-        // a forced shape overrides the rows (benchmarks, tests)
+        // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured with three
+        // precisions present: 2.1, 1.53 and 1.0 microseconds per workgroup and group of columns; two of the
+        // 32-row workgroups fit a CU side by side, which is worth about a third once there are that many)
         const float tiles = (float)((a.batch + 63) / 64);
         int rw = 4;
         float best = 0.f;
         for (int r = 4; r >= 1; r >>= 1) {
             const float wgs = (float)((a.m + 16 * r - 1) / (16 * r)) * tiles;
-            const float cost = (wgs <= 256.f ? 1.f : wgs / 256.f) * (r == 4 ? 2.2f : r == 2 ? 1.75f : 1.12f);
+            const float rounds = wgs <= 256.f ? 1.f : (r == 2 ? 0.65f : 1.f) * wgs / 256.f;
+            const float cost = rounds * (r == 4 ? 2.1f : r == 2 ? 1.53f : 1.0f);
             if (best == 0.f || cost < best) {
                 best = cost;
                 rw = r;

@@ -29,10 +29,10 @@ int choose(const bcq::GemmArgs &a)
     if (choice == BCQ_KERNEL_AUTO) {
         // Dequantising a weight tile costs the same whatever the number of requests that then use it (the time
         // of that kernel is flat up to 64 requests), while the plane-wise kernel grows with the batch: from about
-        // 24 requests on the dequantising kernel wins on every matrix of at least 4096 rows (measured on
-        // Llama-3-8B and 70B shapes, p = 2 and 4); shorter matrices leave it too few workgroups.
-        // (with per-request precision it rebuilds the weights once per precision present: from 40 requests on)
-        const bool pays = a.m >= 4096 && a.batch >= (a.uniform_p > 0 ? 24 : 40);
+        // 20 requests on the dequantising kernel wins on every matrix of at least 4096 rows (measured on
+        // Llama-3-8B and 70B shapes, p = 2 and 4); shorter matrices leave it too few workgroups.  With
+        // per-request precision it rebuilds the weights once per precision present: from 36 requests on.
+        const bool pays = a.m >= 4096 && a.batch >= (a.uniform_p > 0 ? 20 : 36);
         if (dequant_mfma_supports(a) && pays) choice = BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all

@@ -28,11 +28,14 @@ int choose(const bcq::GemmArgs &a)
     int choice = g_forced;
     if (choice == BCQ_KERNEL_AUTO) {
         // Dequantising a weight tile costs the same whatever the number of requests that then use it (the time
-        // of that kernel is flat up to 64 requests), while the plane-wise kernel grows with the batch: from about
-        // 20 requests on the dequantising kernel wins on every matrix of at least 4096 rows (measured on
-        // Llama-3-8B and 70B shapes, p = 2 and 4); shorter matrices leave it too few workgroups.  With
-        // per-request precision it rebuilds the weights once per precision present: from 36 requests on.
-        const bool pays = a.m >= 4096 && a.batch >= (a.uniform_p > 0 ? 20 : 36);
+        // of that kernel is flat up to 64 requests), while the plane-wise kernel grows with the batch in steps of
+        // four requests.  Measured crossovers (Llama-3-8B and 70B shapes, p = 2 and 4): 9 requests on matrices
+        // of at least 8192 rows, 17 (p >= 3) or 21 requests from 4096 rows on; shorter matrices leave the
+        // dequantising kernel too few workgroups.  With per-request precision it rebuilds the weights once
+        // per precision present: from 28 requests (8192 rows and more) or 40 requests on.
+        int from = a.m >= 8192 ? 9 : a.uniform_p >= 3 ? 17 : 21;
+        if (a.uniform_p == 0) from = a.m >= 8192 ? 28 : 40;
+        const bool pays = a.m >= 4096 && a.batch >= from;
         if (dequant_mfma_supports(a) && pays) choice = BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all

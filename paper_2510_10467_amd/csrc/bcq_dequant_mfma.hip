@@ -146,23 +146,30 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
 #pragma unroll
     for (int t = 0; t < 4; ++t) xa_off[t] = (uint32_t)(((4 * kq + t) ^ n16) * 16);
 
+    // Plane words are loaded as ordinary (cached) loads: a wave takes 16 bytes of each row per step and the
+    // rest of the 128-byte line serves the other teams and the next step; marked non-temporal the line was
+    // fetched from memory again and again (up to 1.4x slower).
+    auto fetch_plane = [&](Ahead<P, XU> &ah, int g, int i) {
+        // wave-uniform 64-bit base plus 32-bit lane offset: an addressing mode of the load instruction
+        const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
+        ah.w[i] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);
+        const unsigned char *s_base = a.scales + (size_t)i * a.scale_plane_stride + scale_col(g);
+        ah.alpha[i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
+    };
+    auto fetch_offset = [&](Ahead<P, XU> &ah, int g) { ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + scale_col(g) + s_lane); };
     auto fetch_w = [&](Ahead<P, XU> &ah, int g) {
 #pragma unroll
-        for (int i = 0; i < P; ++i) {
-            // wave-uniform 64-bit base plus 32-bit lane offset: an addressing mode of the load instruction
-            const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
-            ah.w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(w_base + w_lane));
-            const unsigned char *s_base = a.scales + (size_t)i * a.scale_plane_stride + scale_col(g);
-            ah.alpha[i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
-        }
-        ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + scale_col(g) + s_lane);
+        for (int i = 0; i < P; ++i) fetch_plane(ah, g, i);
+        fetch_offset(ah, g);
+    };
+    auto stage_x_unit = [&](int g, int buf, int k) {
+        const unsigned char *x_base = a.x + (uint32_t)g * 256;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
+                                         (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
     };
     auto stage_x = [&](int g, int buf) {
-        const unsigned char *x_base = a.x + (uint32_t)g * 256;
 #pragma unroll
-        for (int k = 0; k < XU; ++k)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
-                                             (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
+        for (int k = 0; k < XU; ++k) stage_x_unit(g, buf, k);
     };
 
     v4f acc[4 * NU];
@@ -189,10 +196,13 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.alpha[i]));
             alpha[i] = (float)__builtin_bit_cast(_Float16, (unsigned short)ab);
         }
-        if (g + TEAMS < a.ngroups) {
-            stage_x(g + TEAMS, buf ^ 1);        // that tile was last read before the previous barrier
-            fetch_w(nxt, g + TEAMS);
-        }
+        // The loads for the team's next group are spread over the four matrix steps below: issued all at once
+        // right after the barrier, by every wave of the workgroup, they queue up in the memory pipe while
+        // no wave has arithmetic to do.  With three or four planes the plane words go two planes per
+        // matrix step, otherwise all of them here.
+        constexpr bool kSpreadPlanes = P >= 3;
+        const bool more = g + TEAMS < a.ngroups;
+        if (more && !kSpreadPlanes) fetch_w(nxt, g + TEAMS);
         const unsigned char *xa_cur = xa_lane + buf * kTile;
         // table offsets of all low and all high nibbles of a plane word at once: byte t of `lo8` (`hi8`) is
         // eight times the low (high) nibble of byte t
@@ -215,8 +225,18 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             v8h xa[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
-            // (sixteen waves leave a wave 128 registers, too few to hold the operands across the arithmetic:
-            // there the compiler is left to place the reads itself)
+            if (more) {
+                if (kSpreadPlanes) {
+                    if (t == 0) fetch_offset(nxt, g + TEAMS);
+#pragma unroll
+                    for (int i = 0; i < P; ++i)
+                        if (i / 2 == t) fetch_plane(nxt, g + TEAMS, i);
+                }
+                // tile buf ^ 1 was last read before the previous barrier
+#pragma unroll
+                for (int k = 0; k < XU; ++k)
+                    if (k * 4 / XU == t) stage_x_unit(g + TEAMS, buf ^ 1, k);
+            }
             __builtin_amdgcn_sched_barrier(0);
             float wf[8];
 #pragma unroll
@@ -381,7 +401,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
         for (int i = 0; i < kMaxP; ++i) {
             if (i < p_hi) {
                 const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
-                ah.w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(w_base + w_lane));
+                ah.w[i] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);     // cached, as in dequant_mfma_kernel
             }
         }
 #pragma unroll
@@ -396,12 +416,14 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
             }
         }
     };
-    auto stage_x = [&](int g, int buf) {
+    auto stage_x_unit = [&](int g, int buf, int k) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
+                                         (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
+    };
+    auto stage_x = [&](int g, int buf) {
 #pragma unroll
-        for (int k = 0; k < XU; ++k)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
-                                             (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
+        for (int k = 0; k < XU; ++k) stage_x_unit(g, buf, k);
     };
 
     v4f acc[kMaxP][4];
@@ -438,10 +460,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
                     for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = 0.f;
                 }
             }
-            if (g + TEAMS < a.ngroups) {
-                stage_x(g + TEAMS, buf ^ 1);
-                fetch_w(nxt, g + TEAMS);
-            }
+            const bool more = g + TEAMS < a.ngroups;
+            if (more) fetch_w(nxt, g + TEAMS);
             const unsigned char *xa_cur = xa_lane + buf * kTile;
             uint32_t lo8[kMaxP], hi8[kMaxP];
 #pragma unroll
@@ -464,6 +484,12 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
                 v8h xa[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
+                if (more) {
+                    // the next tile's loads spread over the matrix steps, as in dequant_mfma_kernel
+#pragma unroll
+                    for (int k = 0; k < XU; ++k)
+                        if (k * 4 / XU == t) stage_x_unit(g + TEAMS, buf ^ 1, k);
+                }
 #pragma unroll
                 for (int q = 1; q <= kMaxP; ++q) {
                     if (has[q]) {
@@ -581,8 +607,8 @@ struct WgShape {
     int nu, rw;
     float us_p4, us_p2;
 };
-constexpr WgShape kShapes[] = {{1, 4, 1.15f, 0.70f}, {1, 2, 0.70f, 0.50f}, {1, 1, 0.50f, 0.40f},
-                               {2, 4, 1.60f, 1.10f}, {2, 2, 1.00f, 0.85f}, {4, 4, 2.60f, 2.10f}};
+constexpr WgShape kShapes[] = {{1, 4, 0.82f, 0.54f}, {1, 2, 0.52f, 0.36f}, {1, 1, 0.45f, 0.37f},
+                               {2, 4, 1.10f, 0.80f}, {2, 2, 0.85f, 0.70f}, {4, 4, 2.10f, 1.75f}};
 
 template <int P>
 hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
@@ -591,7 +617,7 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
     float best = 0.f;
     for (const WgShape &c : kShapes) {
         const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * (float)((a.batch + 64 * c.nu - 1) / (64 * c.nu));
-        const float cost = (wgs <= 256.f ? 1.f : wgs / 256.f) * (P >= 3 ? c.us_p4 : c.us_p2);
+        const float cost = (wgs <= 256.f ? 1.f : __builtin_ceilf(wgs / 256.f)) * (P >= 3 ? c.us_p4 : c.us_p2);
         if (best == 0.f || cost < best) {
             best = cost;
             nu = c.nu;
@@ -663,15 +689,15 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
         pr.p_req = a.p_req;
         pr.p_max = a.p_max;
         // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured with three
-        // precisions present: 2.1, 1.53 and 1.0 microseconds per workgroup and group of columns; two of the
-        // 32-row workgroups fit a CU side by side, which is worth about a third once there are that many)
+        // precisions present: 1.8, 1.43 and 0.94 microseconds per workgroup and group of columns; two of the
+        // 32-row workgroups fit a CU side by side, which is worth about 40 % once there are that many)
         const float tiles = (float)((a.batch + 63) / 64);
         int rw = 4;
         float best = 0.f;
         for (int r = 4; r >= 1; r >>= 1) {
             const float wgs = (float)((a.m + 16 * r - 1) / (16 * r)) * tiles;
-            const float rounds = wgs <= 256.f ? 1.f : (r == 2 ? 0.65f : 1.f) * wgs / 256.f;
-            const float cost = rounds * (r == 4 ? 2.1f : r == 2 ? 1.53f : 1.0f);
+            const float rounds = wgs <= 256.f ? 1.f : (r == 2 ? 0.6f : 1.f) * wgs / 256.f;
+            const float cost = rounds * (r == 4 ? 1.8f : r == 2 ? 1.43f : 0.94f);
             if (best == 0.f || cost < best) {
                 best = cost;
                 rw = r;

@@ -271,6 +271,13 @@ def test_auto_dispatch_by_batch(gpu):
     assert used == "dequant_mfma"
     used, _ = gpu.check_mixed(big, p_req[:16], syn.make_x(16, 1024, seed=(171, 5)), "auto")
     assert used == "plane_mfma"
+    tall = gpu.DeviceLayer(syn.make_layer(8192, 1024, seed=(172, 0)))          # 8192 rows: the crossover sits at 9 requests
+    used, _ = gpu.check_gemv(tall, 2, syn.make_x(8, 1024, seed=(172, 1)), "auto")
+    assert used == "plane_mfma"
+    used, _ = gpu.check_gemv(tall, 2, syn.make_x(9, 1024, seed=(172, 2)), "auto")
+    assert used == "dequant_mfma"
+    used, _ = gpu.check_mixed(tall, p_req[:30], syn.make_x(30, 1024, seed=(172, 3)), "auto")
+    assert used == "dequant_mfma"
 
 
 # ----------------------------------------------------------------------------

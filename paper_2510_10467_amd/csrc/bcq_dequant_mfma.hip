@@ -51,6 +51,13 @@ int g_forced_nu = 0, g_forced_rw = 0;       // workgroup shape forced by dequant
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2;         // LDS row of one request's 128 activations; its sixteen parts sit XOR-permuted
 
+// pointer into LDS from its 32-bit address
+template <typename T>
+__device__ __forceinline__ const T *lds_at(uint32_t addr)
+{
+    return (const T *)(const __attribute__((address_space(3))) T *)(uintptr_t)addr;
+}
+
 constexpr int x_tile_bytes(int nu) { return 64 * nu * kXRowBytes; }
 constexpr int lds_bytes(int nu, int teams) { return kLutBytes + teams * 2 * x_tile_bytes(nu); }
 
@@ -123,9 +130,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     // l & 3), which the memory pipe combines into one request per row, and then handed to the lane
     // that uses them (row l & 15, word l >> 4) by a lane permute.
     const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
-    const uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
+    uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
     // the scale group of (step g, word kq): g with 128 columns per group, g >> 1 with 256, 2g + (kq >> 1) with 64
-    const uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
+    uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
     auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;      // byte index of the lane to take from
     // staging: unit tid + kTeamThreads * k of the tile = request (unit >> 4), 16-byte part (unit & 15) of its 256 bytes
@@ -172,6 +179,11 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
         for (int k = 0; k < XU; ++k) stage_x_unit(g, buf, k);
     };
 
+    // LDS address of the table as a number the compiler cannot see through (it would otherwise add a literal zero
+    // to every look-up address in a separate instruction)
+    uint32_t lut_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lut;
+    asm volatile("" : "+s"(lut_base));
+
     v4f acc[4 * NU];
 #pragma unroll
     for (int u = 0; u < 4 * NU; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -186,6 +198,12 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
 #pragma unroll
         for (int i = 0; i < P; ++i) asm volatile("" : "+v"(cur.w[i]), "+v"(cur.alpha[i]));
         asm volatile("" : "+v"(cur.z));
+        // The lane offsets are made new values in every step: hoisted out of the loop as 64-bit numbers they
+        // cost a register pair and a 64-bit add per load; widened where they are used they ride in the load's
+        // own addressing mode (scalar base + 32-bit lane offset).
+        asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+#pragma unroll
+        for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
         const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.z));
         const float z = a.has_offsets ? (float)__builtin_bit_cast(_Float16, (unsigned short)zb) : 0.f;
         uint32_t w[P];
@@ -211,6 +229,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
         for (int i = 0; i < P; ++i) {
             lo8[i] = (w[i] << 3) & 0x78787878u;
             hi8[i] = (w[i] >> 1) & 0x78787878u;
+            // kept as they are: a look-up is then one add that picks byte t (the compiler would otherwise shift
+            // and mask the plane word again for every nibble)
+            asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
         }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -219,8 +240,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             v4h pl[P], ph[P];
 #pragma unroll
             for (int i = 0; i < P; ++i) {
-                pl[i] = *reinterpret_cast<const v4h *>(lut + ((lo8[i] >> (8 * t)) & 0xffu));
-                ph[i] = *reinterpret_cast<const v4h *>(lut + ((hi8[i] >> (8 * t)) & 0xffu));
+                pl[i] = *lds_at<v4h>(lut_base + ((lo8[i] >> (8 * t)) & 0xffu));
+                ph[i] = *lds_at<v4h>(lut_base + ((hi8[i] >> (8 * t)) & 0xffu));
             }
             v8h xa[4];
 #pragma unroll
@@ -379,8 +400,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
     auto off_of = [&](int q) { return q == 1 ? off1 : q == 2 ? off2 : q == 3 ? off3 : off4; };
 
     const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
-    const uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
-    const uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
+    uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
+    uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
     auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;
     // staging straight into LDS and the XOR placement of the parts: as in dequant_mfma_kernel
@@ -426,6 +447,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
         for (int k = 0; k < XU; ++k) stage_x_unit(g, buf, k);
     };
 
+    uint32_t lut_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lut;
+    asm volatile("" : "+s"(lut_base));
+
     v4f acc[kMaxP][4];
 #pragma unroll
     for (int q = 0; q < kMaxP; ++q)
@@ -440,6 +464,10 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
             for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(cur.alpha[i]));
 #pragma unroll
             for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.z[i]));
+            // lane offsets made new in every step, table look-ups by byte pick: as in dequant_mfma_kernel
+            asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+#pragma unroll
+            for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
             auto handed = [&](_Float16 v) {
                 const uint32_t bits = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, v));
                 return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
@@ -468,6 +496,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
             for (int i = 0; i < kMaxP; ++i) {
                 lo8[i] = (w[i] << 3) & 0x78787878u;
                 hi8[i] = (w[i] >> 1) & 0x78787878u;
+                if (i < p_hi) asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
@@ -475,8 +504,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 #pragma unroll
                 for (int i = 0; i < kMaxP; ++i) {
                     if (i < p_hi) {
-                        pl[i] = *reinterpret_cast<const v4h *>(lut + ((lo8[i] >> (8 * t)) & 0xffu));
-                        ph[i] = *reinterpret_cast<const v4h *>(lut + ((hi8[i] >> (8 * t)) & 0xffu));
+                        pl[i] = *lds_at<v4h>(lut_base + ((lo8[i] >> (8 * t)) & 0xffu));
+                        ph[i] = *lds_at<v4h>(lut_base + ((hi8[i] >> (8 * t)) & 0xffu));
                     } else {
                         pl[i] = ph[i] = v4h{0, 0, 0, 0};
                     }

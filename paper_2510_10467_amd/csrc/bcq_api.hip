@@ -28,12 +28,12 @@ int choose(const bcq::GemmArgs &a)
     int choice = g_forced;
     if (choice == BCQ_KERNEL_AUTO) {
         // Dequantising a weight tile costs the same whatever the number of requests that then use it (the time
-        // of that kernel is flat up to 64 requests), while the plane-wise kernel grows with the batch in steps of
-        // four requests.  Measured crossovers (Llama-3-8B and 70B shapes, p = 2 and 4): 9 requests on matrices
-        // of at least 8192 rows, 17 (p >= 3) or 21 requests from 4096 rows on; shorter matrices leave the
-        // dequantising kernel too few workgroups.  With per-request precision it rebuilds the weights once
-        // per precision present: from 28 requests (8192 rows and more) or 40 requests on.
-        int from = a.m >= 8192 ? 9 : a.uniform_p >= 3 ? 17 : 21;
+        // of that kernel is flat up to 16 and again up to 64 requests), while the plane-wise kernel grows with
+        // the batch in steps of four requests.  Measured crossovers (Llama-3-8B and 70B shapes, p = 2 and 4): on
+        // matrices of at least 8192 rows 9 requests (5 for p <= 2), from 4096 rows on 13; shorter matrices
+        // leave the dequantising kernel too few workgroups.  With per-request precision it rebuilds the
+        // weights once per precision present: from 28 requests (8192 rows and more) or 40 requests on.
+        int from = a.m >= 8192 ? (a.uniform_p >= 3 ? 9 : 5) : 13;
         if (a.uniform_p == 0) from = a.m >= 8192 ? 28 : 40;
         const bool pays = a.m >= 4096 && a.batch >= from;
         if (dequant_mfma_supports(a) && pays) choice = BCQ_KERNEL_DEQUANT_MFMA;

@@ -47,7 +47,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxP = 4;
-int g_forced_nu = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
+int g_forced_nt = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2;         // LDS row of one request's 128 activations; its sixteen parts sit XOR-permuted
 
@@ -58,8 +58,8 @@ __device__ __forceinline__ const T *lds_at(uint32_t addr)
     return (const T *)(const __attribute__((address_space(3))) T *)(uintptr_t)addr;
 }
 
-constexpr int x_tile_bytes(int nu) { return 64 * nu * kXRowBytes; }
-constexpr int lds_bytes(int nu, int teams) { return kLutBytes + teams * 2 * x_tile_bytes(nu); }
+constexpr int x_tile_bytes(int nt) { return 16 * nt * kXRowBytes; }       // nt tiles of 16 requests
+constexpr int lds_bytes(int nt, int teams) { return kLutBytes + teams * 2 * x_tile_bytes(nt); }
 
 struct DequantParams {
     const unsigned char *planes;            // plane 0
@@ -92,13 +92,15 @@ struct Ahead {
     _Float16 z;
 };
 
-// NU: 64-request tiles per workgroup; TEAMS: teams of waves (K split inside the workgroup); RW: waves per
+// NT: 16-request tiles per workgroup (1, 4, 8 or 16); TEAMS: teams of waves (K split inside the workgroup); RW: waves per
 // team = 16-row blocks per workgroup.
-template <int P, int NU, int TEAMS, int RW>
+template <int P, int NT, int TEAMS, int RW>
 __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantParams a)
 {
     constexpr int kTeamThreads = 64 * RW;
-    constexpr int XU = 16 * NU / RW;          // 16-byte units of an activation tile per thread of a team
+    constexpr int XU = 4 * NT / RW;           // 16-byte units of an activation tile per thread of a team
+    constexpr int UT = NT < 4 ? NT : 4;       // request tiles whose operands are held at a time
+    static_assert(XU >= 1 && NT % UT == 0, "tile does not split over the team");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     unsigned char *lut = lds;
 
@@ -106,12 +108,12 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     // base addresses in scalar registers
     const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NU);     // the team's two activation tiles, used alternately
-    constexpr int kTile = x_tile_bytes(NU);
+    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NT);     // the team's two activation tiles, used alternately
+    constexpr int kTile = x_tile_bytes(NT);
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
     const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
-    const int b0 = blockIdx.y * (64 * NU);    // first request of the workgroup
+    const int b0 = blockIdx.y * (16 * NT);    // first request of the workgroup
 
     // table: nibble -> four binary16 values, +1.0 where the bit is set, -1.0 where it is clear
     if (threadIdx.x < 16) {
@@ -184,9 +186,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     uint32_t lut_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lut;
     asm volatile("" : "+s"(lut_base));
 
-    v4f acc[4 * NU];
+    v4f acc[NT];
 #pragma unroll
-    for (int u = 0; u < 4 * NU; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < NT; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
 
     // Group g, the team's next being g + TEAMS.  On entry `cur` holds the plane words and scales of group g
     // and the activation tile of the next group; the team's LDS tile `buf` holds the activations of group g.
@@ -243,9 +245,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
                 pl[i] = *lds_at<v4h>(lut_base + ((lo8[i] >> (8 * t)) & 0xffu));
                 ph[i] = *lds_at<v4h>(lut_base + ((hi8[i] >> (8 * t)) & 0xffu));
             }
-            v8h xa[4];
+            v8h xa[UT];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
+            for (int u = 0; u < UT; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
             if (more) {
                 if (kSpreadPlanes) {
                     if (t == 0) fetch_offset(nxt, g + TEAMS);
@@ -274,19 +276,19 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
 #pragma unroll
             for (int j = 0; j < 8; ++j) wb[j] = (_Float16)wf[j];    // the single rounding of W_p to binary16
 #pragma unroll
-            for (int c = 0; c < NU; ++c) {
+            for (int c = 0; c < NT / UT; ++c) {
                 // the operands of the next four tiles are fetched while these four are in the matrix pipe
-                v8h xn[4];
-                if (c + 1 < NU) {
+                v8h xn[UT];
+                if (c + 1 < NT / UT) {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        xn[u] = *reinterpret_cast<const v8h *>(xa_cur + (4 * (c + 1) + u) * (16 * kXRowBytes) + xa_off[t]);
+                    for (int u = 0; u < UT; ++u)
+                        xn[u] = *reinterpret_cast<const v8h *>(xa_cur + (UT * (c + 1) + u) * (16 * kXRowBytes) + xa_off[t]);
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) acc[4 * c + u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[u], wb, acc[4 * c + u], 0, 0, 0);
-                if (c + 1 < NU) {
+                for (int u = 0; u < UT; ++u) acc[UT * c + u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[u], wb, acc[UT * c + u], 0, 0, 0);
+                if (c + 1 < NT / UT) {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) xa[u] = xn[u];
+                    for (int u = 0; u < UT; ++u) xa[u] = xn[u];
                 }
             }
         }
@@ -314,21 +316,21 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
         v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
         if (team > 0) {
 #pragma unroll
-            for (int u = 0; u < 4 * NU; ++u) xchg[(((team - 1) * RW + wave) * 4 * NU + u) * 64 + lane] = acc[u];
+            for (int u = 0; u < NT; ++u) xchg[(((team - 1) * RW + wave) * NT + u) * 64 + lane] = acc[u];
         }
         __syncthreads();
         if (team > 0) return;
 #pragma unroll
         for (int k = 1; k < TEAMS; ++k)
 #pragma unroll
-            for (int u = 0; u < 4 * NU; ++u) acc[u] += xchg[(((k - 1) * RW + wave) * 4 * NU + u) * 64 + lane];
+            for (int u = 0; u < NT; ++u) acc[u] += xchg[(((k - 1) * RW + wave) * NT + u) * 64 + lane];
     }
 
     // accumulator u, register i: request b0 + 16u + 4kq + i of row row0 + n16
     const uint32_t row = row0 + n16;
     if (row < a.m) {
 #pragma unroll
-        for (int u = 0; u < 4 * NU; ++u)
+        for (int u = 0; u < NT; ++u)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int b = b0 + 16 * u + 4 * kq + i;
@@ -361,8 +363,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 
     const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(1);
-    constexpr int kTile = x_tile_bytes(1);
+    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(4);
+    constexpr int kTile = x_tile_bytes(4);
     const int n16 = lane & 15, kq = lane >> 4;
     const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
     const int b0 = blockIdx.y * 64;
@@ -600,86 +602,100 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 template <int TEAMS, int RW>
 hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    static_assert((TEAMS - 1) * RW * kMaxP * 4 * 64 * 16 <= TEAMS * 2 * x_tile_bytes(1), "accumulator exchange must fit in the tiles");
+    static_assert((TEAMS - 1) * RW * kMaxP * 4 * 64 * 16 <= TEAMS * 2 * x_tile_bytes(4), "accumulator exchange must fit in the tiles");
     auto kernel = dequant_mixed_kernel<TEAMS, RW>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       lds_bytes(1, TEAMS));
+                                       lds_bytes(4, TEAMS));
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 63) / 64));
-    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(1, TEAMS), stream, pr);
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(4, TEAMS), stream, pr);
     return hipGetLastError();
 }
 
-template <int P, int NU, int TEAMS, int RW>
+template <int P, int NT, int TEAMS, int RW>
 hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    static_assert((TEAMS - 1) * RW * 4 * NU * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NU), "accumulator exchange must fit in the tiles");
-    auto kernel = dequant_mfma_kernel<P, NU, TEAMS, RW>;
-    if (lds_bytes(NU, TEAMS) > 64 * 1024) {
+    static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
+    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW>;
+    if (lds_bytes(NT, TEAMS) > 64 * 1024) {
         // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           lds_bytes(NU, TEAMS));
+                                           lds_bytes(NT, TEAMS));
         if (e != hipSuccess) return e;
     }
-    dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 64 * NU - 1) / (64 * NU)));
-    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NU, TEAMS), stream, pr);
+    dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, TEAMS), stream, pr);
     return hipGetLastError();
 }
 
-// Shape of the workgroups: NU = 1, 2 or 4 tiles of 64 requests (with four, two and one team), RW = 4, 2 or 1
-// blocks of 16 rows.  A CU holds one workgroup at a time, so the time of a call is about
-// (rounds of workgroups over the 256 CUs) x (time of one workgroup per group of columns).  The second factor
-// was measured for every shape on a grid that fills the chip once (microseconds per group, p = 4 and p = 2):
-// larger workgroups reuse dequantised weights and staged activations better, smaller ones keep CUs busy on
-// short matrices.  The cheapest product wins; dequant_mfma_force_shape overrides the choice (benchmarks, tests).
+// Shape of the workgroups: NT = 1, 4, 8 or 16 tiles of 16 requests (with four, four, two and one team), RW = 4, 2
+// or 1 blocks of 16 rows.  With the 64-request tiles and larger a CU holds one workgroup at a time, so the time of a
+// call is about (rounds of workgroups over the 256 CUs) x (time of one workgroup per group of columns).  The
+// second factor was measured for every shape on a grid that fills the chip once (microseconds per group, p = 4
+// and p = 2): larger workgroups reuse dequantised weights and staged activations better, smaller ones keep CUs
+// busy on short matrices; the 16-request tile saves matrix instructions and operand reads when the batch is
+// that small.  The cheapest product wins; dequant_mfma_force_shape overrides the choice (benchmarks, tests).
 struct WgShape {
-    int nu, rw;
-    float us_p4, us_p2;
+    int nt, rw;
+    float us_p4, us_p2;         // one workgroup per CU or fewer
+    float many_p4, many_p2;     // per workgroup when the grid exceeds the chip (0: whole rounds of the above)
 };
-constexpr WgShape kShapes[] = {{1, 4, 0.82f, 0.54f}, {1, 2, 0.52f, 0.36f}, {1, 1, 0.45f, 0.37f},
-                               {2, 4, 1.10f, 0.80f}, {2, 2, 0.85f, 0.70f}, {4, 4, 2.10f, 1.75f}};
+// The 16-request shapes need 32 KiB of LDS and few registers, so several of their workgroups share a CU and a
+// grid beyond 256 workgroups costs less than whole rounds; they are used up to 16 requests only (two such tiles
+// never beat one 64-request tile).
+constexpr WgShape kShapes[] = {{1, 4, 0.62f, 0.40f, 0.62f, 0.40f}, {1, 2, 0.40f, 0.28f, 0.36f, 0.235f}, {1, 1, 0.36f, 0.28f, 0.19f, 0.13f},
+                               {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
+                               {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
 
 template <int P>
 hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    int nu = 1, rw = 4;
+    int nt = 4, rw = 4;
     float best = 0.f;
     for (const WgShape &c : kShapes) {
-        const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * (float)((a.batch + 64 * c.nu - 1) / (64 * c.nu));
-        const float cost = (wgs <= 256.f ? 1.f : __builtin_ceilf(wgs / 256.f)) * (P >= 3 ? c.us_p4 : c.us_p2);
+        if (c.nt == 1 && a.batch > 16) continue;
+        const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * (float)((a.batch + 16 * c.nt - 1) / (16 * c.nt));
+        const float one = P >= 3 ? c.us_p4 : c.us_p2, many = P >= 3 ? c.many_p4 : c.many_p2;
+        float cost = one;
+        if (wgs > 256.f) cost = many > 0.f ? (wgs / 256.f * many > one ? wgs / 256.f * many : one) : __builtin_ceilf(wgs / 256.f) * one;
         if (best == 0.f || cost < best) {
             best = cost;
-            nu = c.nu;
+            nt = c.nt;
             rw = c.rw;
         }
     }
-    if (g_forced_nu > 0) {
-        nu = g_forced_nu;
+    if (g_forced_nt > 0) {
+        nt = g_forced_nt;
         rw = g_forced_rw;
     }
-    switch (nu * 10 + rw) {
+    switch (nt * 10 + rw) {
     case 14: return launch_one<P, 1, 4, 4>(pr, a, stream);
     case 12: return launch_one<P, 1, 4, 2>(pr, a, stream);
     case 11: return launch_one<P, 1, 4, 1>(pr, a, stream);
-    case 24: return launch_one<P, 2, 2, 4>(pr, a, stream);
-    case 22: return launch_one<P, 2, 2, 2>(pr, a, stream);
-    case 44: return launch_one<P, 4, 1, 4>(pr, a, stream);
+    case 44: return launch_one<P, 4, 4, 4>(pr, a, stream);
+    case 42: return launch_one<P, 4, 4, 2>(pr, a, stream);
+    case 41: return launch_one<P, 4, 4, 1>(pr, a, stream);
+    case 84: return launch_one<P, 8, 2, 4>(pr, a, stream);
+    case 82: return launch_one<P, 8, 2, 2>(pr, a, stream);
+    case 164: return launch_one<P, 16, 1, 4>(pr, a, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
+// request_tiles: 1, 2 or 4 tiles of 64 requests, or 0 (with row_blocks != 0) for a single tile of 16 requests
 bool dequant_mfma_force_shape(int request_tiles, int row_blocks)
 {
-    const int key = request_tiles * 10 + row_blocks;
-    const bool known = key == 14 || key == 12 || key == 11 || key == 24 || key == 22 || key == 44;
     if (request_tiles == 0 && row_blocks == 0) {
-        g_forced_nu = g_forced_rw = 0;
+        g_forced_nt = g_forced_rw = 0;
         return true;
     }
-    if (!known) return false;
-    g_forced_nu = request_tiles;
+    const int nt = request_tiles == 0 ? 1 : 4 * request_tiles;
+    const int key = nt * 10 + row_blocks;
+    const bool known = key == 14 || key == 12 || key == 11 || key == 44 || key == 42 || key == 41 || key == 84 || key == 82 || key == 164;
+    if (!known || request_tiles < 0 || (row_blocks != 1 && row_blocks != 2 && row_blocks != 4)) return false;
+    g_forced_nt = nt;
     g_forced_rw = row_blocks;
     return true;
 }
@@ -691,7 +707,7 @@ bool dequant_mfma_supports(const GemmArgs &a)
     const bool group_ok = (a.group == 64 || a.group == 128 || a.group == 256) && (a.n % 128) == 0;
     // one precision for all requests, or one per request with planes stored to at most four
     const bool p_ok = a.uniform_p > 0 ? a.uniform_p <= kMaxP : (a.p_req != nullptr && a.p_max >= 1 && a.p_max <= kMaxP);
-    return p_ok && group_ok && small_enough && (a.batch + 63) / 64 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
+    return p_ok && group_ok && small_enough && (a.batch + 15) / 16 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
 }
 
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
@@ -732,7 +748,7 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
                 rw = r;
             }
         }
-        if (g_forced_nu > 0) rw = g_forced_rw;
+        if (g_forced_nt > 0) rw = g_forced_rw;
         return rw == 4 ? launch_mixed<2, 4>(pr, a, stream) : rw == 2 ? launch_mixed<2, 2>(pr, a, stream) : launch_mixed<4, 1>(pr, a, stream);
     }
     pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);

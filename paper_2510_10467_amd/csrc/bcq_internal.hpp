@@ -49,7 +49,7 @@ bool plane_mfma_supports_multi(const GemmArgs *mats, int count);
 hipError_t plane_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t stream);
 
 bool dequant_mfma_supports(const GemmArgs &a);
-// benchmarks and tests: force the workgroup shape (request tiles of 64, blocks of 16 rows); (0, 0) = automatic
+// benchmarks and tests: force the workgroup shape (request tiles of 64, or 0 for one tile of 16; blocks of 16 rows); (0, 0) = automatic
 bool dequant_mfma_force_shape(int request_tiles, int row_blocks);
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream);
 

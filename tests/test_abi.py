@@ -130,6 +130,9 @@ def test_argument_validation_without_device(lib):
     assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1
     assert lib.bcq_select_dequant_shape(3, 4) == -6
     assert lib.bcq_select_dequant_shape(2, 2) == 0
+    assert lib.bcq_select_dequant_shape(0, 4) == 0
+    assert lib.bcq_select_dequant_shape(0, 3) == -6
+    assert lib.bcq_select_dequant_shape(-1, 4) == -6
     assert lib.bcq_select_dequant_shape(0, 0) == 0
     assert lib.bcq_select_kernel(17) == -6
     assert lib.bcq_select_kernel(0) == 0

@@ -116,15 +116,16 @@ def test_dequant_mfma_uniform(gpu, m, n):
             assert used == "dequant_mfma"
 
 
-@pytest.mark.parametrize("shape", ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
+@pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
 def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape):
     """The kernel picks its workgroup shape (request tiles, row blocks) from m and the batch; small test
-    matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles)."""
+    matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles;
+    "0" is the single tile of 16 requests)."""
     forced_shape(shape)
     layer = syn.make_layer(200, 1536, seed=(151, 0), signed=True)
     dl = gpu.DeviceLayer(layer)
     offsets = syn.make_offsets(3, 200, 1536, seed=(151, 1))
-    for batch in (3, 64, 100, 257):
+    for batch in (3, 16, 64, 100, 257):
         x = syn.make_x(batch, 1536, seed=(151, batch))
         for p in (2, 4):
             used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma")
@@ -260,8 +261,10 @@ def test_auto_dispatch_by_batch(gpu):
     used, _ = gpu.check_gemv(dl, 3, syn.make_x(128, 2048, seed=(170, 3)), "auto")
     assert used == "plane_mfma"            # too few rows for the dequantising kernel to pay
     big = gpu.DeviceLayer(syn.make_layer(4096, 1024, seed=(171, 0)))
-    used, _ = gpu.check_gemv(big, 3, syn.make_x(16, 1024, seed=(171, 1)), "auto")
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(12, 1024, seed=(171, 1)), "auto")
     assert used == "plane_mfma"
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(13, 1024, seed=(171, 6)), "auto")     # 4096 rows: from 13 requests on
+    assert used == "dequant_mfma"
     used, _ = gpu.check_gemv(big, 3, syn.make_x(64, 1024, seed=(171, 2)), "auto")
     assert used == "dequant_mfma"
     p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
@@ -271,10 +274,14 @@ def test_auto_dispatch_by_batch(gpu):
     assert used == "dequant_mfma"
     used, _ = gpu.check_mixed(big, p_req[:16], syn.make_x(16, 1024, seed=(171, 5)), "auto")
     assert used == "plane_mfma"
-    tall = gpu.DeviceLayer(syn.make_layer(8192, 1024, seed=(172, 0)))          # 8192 rows: the crossover sits at 9 requests
-    used, _ = gpu.check_gemv(tall, 2, syn.make_x(8, 1024, seed=(172, 1)), "auto")
+    tall = gpu.DeviceLayer(syn.make_layer(8192, 1024, seed=(172, 0)))          # 8192 rows: the crossover sits at 9 requests (5 for p <= 2)
+    used, _ = gpu.check_gemv(tall, 3, syn.make_x(8, 1024, seed=(172, 1)), "auto")
     assert used == "plane_mfma"
-    used, _ = gpu.check_gemv(tall, 2, syn.make_x(9, 1024, seed=(172, 2)), "auto")
+    used, _ = gpu.check_gemv(tall, 3, syn.make_x(9, 1024, seed=(172, 2)), "auto")
+    assert used == "dequant_mfma"
+    used, _ = gpu.check_gemv(tall, 2, syn.make_x(4, 1024, seed=(172, 4)), "auto")
+    assert used == "plane_mfma"
+    used, _ = gpu.check_gemv(tall, 2, syn.make_x(5, 1024, seed=(172, 5)), "auto")
     assert used == "dequant_mfma"
     used, _ = gpu.check_mixed(tall, p_req[:30], syn.make_x(30, 1024, seed=(172, 3)), "auto")
     assert used == "dequant_mfma"

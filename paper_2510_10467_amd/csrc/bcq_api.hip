@@ -28,15 +28,17 @@ int choose(const bcq::GemmArgs &a)
     int choice = g_forced;
     if (choice == BCQ_KERNEL_AUTO) {
         // Dequantising a weight tile costs the same whatever the number of requests that then use it (the time
-        // of that kernel is flat up to 16 and again up to 64 requests), while the plane-wise kernel grows with
+        // of that kernel is flat up to 16 and again up to 64 requests), while the plane-wise FP4 kernel grows with
         // the batch in steps of four requests.  Measured crossovers (Llama-3-8B and 70B shapes, p = 2 and 4): on
-        // matrices of at least 8192 rows 9 requests (5 for p <= 2), from 4096 rows on 13; shorter matrices
-        // leave the dequantising kernel too few workgroups.  With per-request precision it rebuilds the
-        // weights once per precision present: from 28 requests (8192 rows and more) or 40 requests on.
-        int from = a.m >= 8192 ? (a.uniform_p >= 3 ? 9 : 5) : 13;
+        // matrices of at least 8192 rows 9 requests (5 for p <= 2), from 4096 rows on 9; shorter matrices
+        // leave the large-batch kernels too few workgroups.  With per-request precision the weights are rebuilt
+        // once per precision present: from 28 requests (8192 rows and more) or 40 requests on.
+        // Up to 16 requests (one tile) multiplying the +-1 planes themselves and scaling the group sums beats
+        // rebuilding the weights by 5-15 %; beyond that it is the other way round.
+        int from = a.m >= 8192 && a.uniform_p <= 2 ? 5 : 9;
         if (a.uniform_p == 0) from = a.m >= 8192 ? 28 : 40;
         const bool pays = a.m >= 4096 && a.batch >= from;
-        if (dequant_mfma_supports(a) && pays) choice = BCQ_KERNEL_DEQUANT_MFMA;
+        if (dequant_mfma_supports(a) && pays) choice = a.uniform_p > 0 && a.batch <= 16 && a.group >= 128 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all
         // of its work per request, so the dequantising one wins from the second request on
@@ -66,6 +68,12 @@ int run(const bcq::GemmArgs &a, hipStream_t stream)
         err = dequant_mfma_launch(a, stream);
         g_last = "dequant_mfma";
         break;
+    case BCQ_KERNEL_PLANE_F16:
+        // a matrix instruction sums over all 128 columns of a step: one scale per row and step, so groups of 128 or 256
+        if (!dequant_mfma_supports(a) || a.uniform_p == 0 || a.group < 128) return BCQ_ERR_VARIANT;
+        err = dequant_mfma_launch(a, stream, true);
+        g_last = "plane_f16";
+        break;
     default:
         return BCQ_ERR_VARIANT;
     }
@@ -92,7 +100,7 @@ const char *bcq_strerror(int status)
 
 int bcq_select_kernel(int variant)
 {
-    if (variant < BCQ_KERNEL_AUTO || variant > BCQ_KERNEL_DEQUANT_MFMA) return BCQ_ERR_VARIANT;
+    if (variant < BCQ_KERNEL_AUTO || variant > BCQ_KERNEL_PLANE_F16) return BCQ_ERR_VARIANT;
     g_forced = variant;
     return BCQ_OK;
 }

@@ -94,7 +94,13 @@ struct Ahead {
 
 // NT: 16-request tiles per workgroup (1, 4, 8 or 16); TEAMS: teams of waves (K split inside the workgroup); RW: waves per
 // team = 16-row blocks per workgroup.
-template <int P, int NT, int TEAMS, int RW>
+// PW (plane-wise): instead of rebuilding W_p, the +-1.0 values from the table are themselves the matrix operand:
+//   tmp_i = B_i x over the group's 128 columns (fp16 matrix instructions, exact products, fp32 sums), then
+//   acc += alpha_i * tmp_i in fp32 - y = sum_i alpha_i (B_i x) as section 3.3 writes it, group by group.
+// That trades the P fused multiply-adds per weight for P times the matrix instructions, which the matrix pipe
+// has room for; the offset of the asymmetric scheme multiplies the group's plain activation sum, formed by
+// one more pass with an all-ones operand.
+template <int P, int NT, int TEAMS, int RW, bool PW = false>
 __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantParams a)
 {
     constexpr int kTeamThreads = 64 * RW;
@@ -235,6 +241,80 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             // and mask the plane word again for every nibble)
             asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
         }
+        if constexpr (PW) {
+            constexpr int PP = NT <= 2 ? 4 : 2;              // planes per pass: PP * NT partial-sum tiles live at a time
+            constexpr int NPASS = (P + PP - 1) / PP;
+            constexpr int NSLOT = 4 * NPASS;                 // matrix sub-steps over which the next loads are spread
+            const v4f zero4 = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int pass = 0; pass < NPASS; ++pass) {
+                v4f tmp[PP][NT];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    v8h bw[PP];
+#pragma unroll
+                    for (int ii = 0; ii < PP; ++ii) {
+                        const int i = pass * PP + ii;
+                        if (i < P) {
+                            const v4h lo = *lds_at<v4h>(lut_base + ((lo8[i] >> (8 * t)) & 0xffu));
+                            const v4h hi = *lds_at<v4h>(lut_base + ((hi8[i] >> (8 * t)) & 0xffu));
+                            bw[ii] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        }
+                    }
+                    if (more) {
+                        const int slot = pass * 4 + t;
+                        if (kSpreadPlanes) {
+                            if (slot == 0) fetch_offset(nxt, g + TEAMS);
+#pragma unroll
+                            for (int i = 0; i < P; ++i)
+                                if (i / 2 == slot) fetch_plane(nxt, g + TEAMS, i);
+                        }
+#pragma unroll
+                        for (int k = 0; k < XU; ++k)
+                            if (k * NSLOT / XU == slot) stage_x_unit(g + TEAMS, buf ^ 1, k);
+                    }
+#pragma unroll
+                    for (int c = 0; c < NT / UT; ++c) {
+                        v8h xa[UT];
+#pragma unroll
+                        for (int u = 0; u < UT; ++u)
+                            xa[u] = *reinterpret_cast<const v8h *>(xa_cur + (UT * c + u) * (16 * kXRowBytes) + xa_off[t]);
+#pragma unroll
+                        for (int u = 0; u < UT; ++u)
+#pragma unroll
+                            for (int ii = 0; ii < PP; ++ii)
+                                if (pass * PP + ii < P)
+                                    tmp[ii][UT * c + u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[u], bw[ii], t == 0 ? zero4 : tmp[ii][UT * c + u], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int ii = 0; ii < PP; ++ii)
+                    if (pass * PP + ii < P) {
+#pragma unroll
+                        for (int u = 0; u < NT; ++u)
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) acc[u][k] = fmaf(alpha[pass * PP + ii], tmp[ii][u][k], acc[u][k]);
+                    }
+            }
+            if (a.has_offsets) {
+                // z * (sum of the group's activations): the same product with an all-ones operand
+                v8h ones;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
+                v4f tz[NT];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) {
+                        const v8h xo = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
+                        tz[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xo, ones, t == 0 ? zero4 : tz[u], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int u = 0; u < NT; ++u)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) acc[u][k] = fmaf(z, tz[u][k], acc[u][k]);
+            }
+        } else {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             // every LDS read of this matrix step goes out first: the table entries, then the activation operands
@@ -291,6 +371,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
                     for (int u = 0; u < UT; ++u) xa[u] = xn[u];
                 }
             }
+        }
         }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
@@ -612,11 +693,11 @@ hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t 
     return hipGetLastError();
 }
 
-template <int P, int NT, int TEAMS, int RW>
+template <int P, int NT, int TEAMS, int RW, bool PW>
 hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
     static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
-    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW>;
+    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW>;
     if (lds_bytes(NT, TEAMS) > 64 * 1024) {
         // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -647,7 +728,7 @@ constexpr WgShape kShapes[] = {{1, 4, 0.62f, 0.40f, 0.62f, 0.40f}, {1, 2, 0.40f,
                                {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
                                {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
 
-template <int P>
+template <int P, bool PW>
 hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
     int nt = 4, rw = 4;
@@ -669,15 +750,15 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
         rw = g_forced_rw;
     }
     switch (nt * 10 + rw) {
-    case 14: return launch_one<P, 1, 4, 4>(pr, a, stream);
-    case 12: return launch_one<P, 1, 4, 2>(pr, a, stream);
-    case 11: return launch_one<P, 1, 4, 1>(pr, a, stream);
-    case 44: return launch_one<P, 4, 4, 4>(pr, a, stream);
-    case 42: return launch_one<P, 4, 4, 2>(pr, a, stream);
-    case 41: return launch_one<P, 4, 4, 1>(pr, a, stream);
-    case 84: return launch_one<P, 8, 2, 4>(pr, a, stream);
-    case 82: return launch_one<P, 8, 2, 2>(pr, a, stream);
-    case 164: return launch_one<P, 16, 1, 4>(pr, a, stream);
+    case 14: return launch_one<P, 1, 4, 4, PW>(pr, a, stream);
+    case 12: return launch_one<P, 1, 4, 2, PW>(pr, a, stream);
+    case 11: return launch_one<P, 1, 4, 1, PW>(pr, a, stream);
+    case 44: return launch_one<P, 4, 4, 4, PW>(pr, a, stream);
+    case 42: return launch_one<P, 4, 4, 2, PW>(pr, a, stream);
+    case 41: return launch_one<P, 4, 4, 1, PW>(pr, a, stream);
+    case 84: return launch_one<P, 8, 2, 4, PW>(pr, a, stream);
+    case 82: return launch_one<P, 8, 2, 2, PW>(pr, a, stream);
+    case 164: return launch_one<P, 16, 1, 4, PW>(pr, a, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -710,7 +791,7 @@ bool dequant_mfma_supports(const GemmArgs &a)
     return p_ok && group_ok && small_enough && (a.batch + 15) / 16 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
 }
 
-hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
+hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool planewise)
 {
     DequantParams pr{};
     pr.planes = reinterpret_cast<const unsigned char *>(a.planes);
@@ -754,11 +835,19 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);
     pr.has_offsets = a.offsets[a.uniform_p] != nullptr;
     pr.offsets = pr.has_offsets ? reinterpret_cast<const unsigned char *>(a.offsets[a.uniform_p]) : pr.scales;
+    if (planewise) {
+        switch (a.uniform_p) {
+        case 1: return launch_p<1, true>(pr, a, stream);
+        case 2: return launch_p<2, true>(pr, a, stream);
+        case 3: return launch_p<3, true>(pr, a, stream);
+        default: return launch_p<4, true>(pr, a, stream);
+        }
+    }
     switch (a.uniform_p) {
-    case 1: return launch_p<1>(pr, a, stream);
-    case 2: return launch_p<2>(pr, a, stream);
-    case 3: return launch_p<3>(pr, a, stream);
-    default: return launch_p<4>(pr, a, stream);
+    case 1: return launch_p<1, false>(pr, a, stream);
+    case 2: return launch_p<2, false>(pr, a, stream);
+    case 3: return launch_p<3, false>(pr, a, stream);
+    default: return launch_p<4, false>(pr, a, stream);
     }
 }
 

@@ -105,19 +105,23 @@ def test_plane_mfma_mixed(gpu, m, n):
         gpu.check_mixed(dl, p_req, x, "plane_mfma")
 
 
+@pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
 @pytest.mark.parametrize("m,n", [(37, 2048), (131, 4096), (70, 1536), (64, 640), (200, 8192)])
-def test_dequant_mfma_uniform(gpu, m, n):
+def test_dequant_mfma_uniform(gpu, m, n, kernel):
+    """Both large-batch variants: weights rebuilt in fp16 (dequant_mfma), or the +-1 planes multiplied
+    themselves and the group sums scaled in fp32 (plane_f16)."""
     layer = syn.make_layer(m, n, seed=(150, m), signed=True)
     dl = gpu.DeviceLayer(layer)
     for batch in (1, 17, 64, 100, 256):
         x = syn.make_x(batch, n, seed=(150, batch))
         for p in (1, 2, 3, 4):
-            used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma")
-            assert used == "dequant_mfma"
+            used, _ = gpu.check_gemv(dl, p, x, kernel)
+            assert used == kernel
 
 
+@pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
 @pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
-def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape):
+def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape, kernel):
     """The kernel picks its workgroup shape (request tiles, row blocks) from m and the batch; small test
     matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles;
     "0" is the single tile of 16 requests)."""
@@ -128,9 +132,9 @@ def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape):
     for batch in (3, 16, 64, 100, 257):
         x = syn.make_x(batch, 1536, seed=(151, batch))
         for p in (2, 4):
-            used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma")
-            assert used == "dequant_mfma"
-        gpu.check_gemv(dl, 3, x, "dequant_mfma", offsets=offsets)
+            used, _ = gpu.check_gemv(dl, p, x, kernel)
+            assert used == kernel
+        gpu.check_gemv(dl, 3, x, kernel, offsets=offsets)
 
 
 @pytest.mark.parametrize("m,n", [(37, 2048), (20, 1536), (33, 3584), (130, 4096)])
@@ -174,17 +178,29 @@ def test_plane_mfma_groups_of_64(gpu, m, n):
     assert used != "plane_mfma"
 
 
+@pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
 @pytest.mark.parametrize("group", [64, 256])
-def test_dequant_mfma_other_group_sizes(gpu, group):
+def test_dequant_mfma_other_group_sizes(gpu, group, kernel):
+    import paper_2510_10467_amd as bcq
     layer = syn.make_layer(150, 1536, group=group, seed=(153, group), signed=True)
     dl = gpu.DeviceLayer(layer)
+    if kernel == "plane_f16" and group == 64:
+        # its matrix instruction sums over the 128 columns of a step, which would mix two groups of 64
+        bcq.select_kernel(kernel)
+        try:
+            with pytest.raises(bcq.BcqError) as e:
+                bcq.bcq_gemv(dl.planes, dl.scales[2], 2, gpu.to_dev(syn.make_x(5, 1536, seed=(153, 5))), group=64)
+            assert e.value.status == -6
+        finally:
+            bcq.select_kernel("auto")
+        return
     offsets = syn.make_offsets(2, 150, 1536, group, seed=(153, 1))
     for batch in (5, 64, 130):
         x = syn.make_x(batch, 1536, seed=(153, batch))
         for p in (1, 3, 4):
-            used, _ = gpu.check_gemv(dl, p, x, "dequant_mfma", group)
-            assert used == "dequant_mfma"
-        gpu.check_gemv(dl, 2, x, "dequant_mfma", group, offsets=offsets)
+            used, _ = gpu.check_gemv(dl, p, x, kernel, group)
+            assert used == kernel
+        gpu.check_gemv(dl, 2, x, kernel, group, offsets=offsets)
 
 
 @pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1"])
@@ -261,10 +277,10 @@ def test_auto_dispatch_by_batch(gpu):
     used, _ = gpu.check_gemv(dl, 3, syn.make_x(128, 2048, seed=(170, 3)), "auto")
     assert used == "plane_mfma"            # too few rows for the dequantising kernel to pay
     big = gpu.DeviceLayer(syn.make_layer(4096, 1024, seed=(171, 0)))
-    used, _ = gpu.check_gemv(big, 3, syn.make_x(12, 1024, seed=(171, 1)), "auto")
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(8, 1024, seed=(171, 1)), "auto")
     assert used == "plane_mfma"
-    used, _ = gpu.check_gemv(big, 3, syn.make_x(13, 1024, seed=(171, 6)), "auto")     # 4096 rows: from 13 requests on
-    assert used == "dequant_mfma"
+    used, _ = gpu.check_gemv(big, 3, syn.make_x(9, 1024, seed=(171, 6)), "auto")      # 4096 rows: from 9 requests on,
+    assert used == "plane_f16"                                                         # one tile of 16: planes multiplied as they are
     used, _ = gpu.check_gemv(big, 3, syn.make_x(64, 1024, seed=(171, 2)), "auto")
     assert used == "dequant_mfma"
     p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
@@ -278,11 +294,13 @@ def test_auto_dispatch_by_batch(gpu):
     used, _ = gpu.check_gemv(tall, 3, syn.make_x(8, 1024, seed=(172, 1)), "auto")
     assert used == "plane_mfma"
     used, _ = gpu.check_gemv(tall, 3, syn.make_x(9, 1024, seed=(172, 2)), "auto")
+    assert used == "plane_f16"
+    used, _ = gpu.check_gemv(tall, 3, syn.make_x(17, 1024, seed=(172, 6)), "auto")
     assert used == "dequant_mfma"
     used, _ = gpu.check_gemv(tall, 2, syn.make_x(4, 1024, seed=(172, 4)), "auto")
     assert used == "plane_mfma"
     used, _ = gpu.check_gemv(tall, 2, syn.make_x(5, 1024, seed=(172, 5)), "auto")
-    assert used == "dequant_mfma"
+    assert used == "plane_f16"
     used, _ = gpu.check_mixed(tall, p_req[:30], syn.make_x(30, 1024, seed=(172, 3)), "auto")
     assert used == "dequant_mfma"
 

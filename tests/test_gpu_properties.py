@@ -37,7 +37,7 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
     dl = gpu.DeviceLayer(layer)
     rng = np.random.default_rng([syn.BASE_SEED, 200, m])
     rows = np.unique(np.concatenate([[0, 15, 16, m - 17, m - 1], rng.integers(0, m, size=120)]))
-    batches = (1, 3, 80, 256) if name in ("gate_proj", "llama70b_down", "q_proj") else (1, 3, 80)
+    batches = (1, 3, 16, 80, 256) if name in ("gate_proj", "llama70b_down", "q_proj") else (1, 3, 16, 80)
     for batch in batches:
         x = syn.make_x(batch, n, seed=(200, batch))
         xd = gpu.to_dev(x)
@@ -56,7 +56,7 @@ def test_prefix_invariance_and_determinism(gpu):
     m, n = 300, 4096
     layer = syn.make_layer(m, n, seed=(210, 0))
     x = gpu.to_dev(syn.make_x(2, n, seed=(210, 0)))
-    for kernel in ("plane_mfma", "sign_select", "dequant_mfma"):
+    for kernel in ("plane_mfma", "sign_select", "dequant_mfma", "plane_f16"):
         bcq.select_kernel(kernel)
         try:
             for p in (1, 2, 3):
@@ -89,7 +89,7 @@ def test_one_hot_readout_and_symmetries(gpu, oracle):
     for b, j in enumerate(cols):
         x[b, j] = 1.0
     xr = syn.make_x(4, n, seed=(220, 1))
-    for kernel in ("plane_mfma", "sign_select", "dequant_mfma"):
+    for kernel in ("plane_mfma", "sign_select", "dequant_mfma", "plane_f16"):
         bcq.select_kernel(kernel)
         try:
             y = bcq.bcq_gemv(gpu.to_dev(planes), gpu.to_dev(scales), p, gpu.to_dev(x)).cpu().numpy().astype(np.float64)
@@ -184,7 +184,7 @@ def test_extreme_activation_magnitudes(gpu, oracle):
     x[2] = (rng.normal(size=n) * 3e-6).astype(np.float16)                             # mostly subnormal
     x[3] = 0.0
     x[3, ::16] = np.where(rng.random(n // 16) < 0.5, 65504.0, -65504.0)               # the largest finite binary16 values
-    for kernel in ("plane_mfma", "sign_select", "dequant_mfma"):
+    for kernel in ("plane_mfma", "sign_select", "dequant_mfma", "plane_f16"):
         # row 2: |x| < 2^-6 may lose bits below 2^-16 in plane_mfma; the documented bound is 2^-16 per element
         used, worst = gpu.check_gemv(dl, 3, x[[0, 1, 3]], kernel)
     y = __import__("paper_2510_10467_amd").bcq_gemv(dl.planes, dl.scales[3], 3, gpu.to_dev(x[2:3])).cpu().numpy().astype(np.float64)

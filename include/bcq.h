@@ -64,7 +64,7 @@ typedef enum {
     BCQ_KERNEL_SIGN_SELECT = 1,/* generic per-bit add/subtract kernel, any legal shape */
     BCQ_KERNEL_PLANE_MFMA = 2, /* bit-planes fed to the FP4 matrix pipe, small batches */
     BCQ_KERNEL_DEQUANT_MFMA = 3,/* dequantise to fp16 tiles in LDS + fp16 MFMA, large batches */
-    BCQ_KERNEL_PLANE_F16 = 4   /* +-1 planes as fp16 MFMA operands, group sums scaled in fp32; uniform precision, large batches */
+    BCQ_KERNEL_PLANE_F16 = 4   /* +-1 planes as fp16 MFMA operands, group sums scaled in fp32 by each request's own scales; groups >= 128 */
 } bcq_kernel;
 
 /* Static, NUL-terminated description of a status code.  Host call. */

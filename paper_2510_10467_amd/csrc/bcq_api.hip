@@ -31,14 +31,22 @@ int choose(const bcq::GemmArgs &a)
         // of that kernel is flat up to 16 and again up to 64 requests), while the plane-wise FP4 kernel grows with
         // the batch in steps of four requests.  Measured crossovers (Llama-3-8B and 70B shapes, p = 2 and 4): on
         // matrices of at least 8192 rows 9 requests (5 for p <= 2), from 4096 rows on 9; shorter matrices
-        // leave the large-batch kernels too few workgroups.  With per-request precision the weights are rebuilt
-        // once per precision present: from 28 requests (8192 rows and more) or 40 requests on.
+        // leave the large-batch kernels too few workgroups.
         // Up to 16 requests (one tile) multiplying the +-1 planes themselves and scaling the group sums beats
         // rebuilding the weights by 5-15 %; beyond that it is the other way round.
+        const bool f16_ok = a.group >= 128;                     // the fp16 plane-wise variant needs one scale per 128-column step
         int from = a.m >= 8192 && a.uniform_p <= 2 ? 5 : 9;
-        if (a.uniform_p == 0) from = a.m >= 8192 ? 28 : 40;
+        bool tiles16 = f16_ok && a.batch <= 16;
+        // Per-request precision: the plane-wise fp16 variant works in tiles of 16 requests whatever mix of
+        // precisions they hold (from 9 requests on 8192 rows and more, from 17 on 4096); rebuilding the weights
+        // once per precision present takes over from 49 requests (8192 rows and more) or 129 on, and from 28 / 40
+        // requests where the fp16 variant cannot run.
+        if (a.uniform_p == 0) {
+            from = f16_ok ? (a.m >= 8192 ? 9 : 17) : (a.m >= 8192 ? 28 : 40);
+            tiles16 = f16_ok && a.batch <= (a.m >= 8192 ? 48 : 128);
+        }
         const bool pays = a.m >= 4096 && a.batch >= from;
-        if (dequant_mfma_supports(a) && pays) choice = a.uniform_p > 0 && a.batch <= 16 && a.group >= 128 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
+        if (dequant_mfma_supports(a) && pays) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all
         // of its work per request, so the dequantising one wins from the second request on
@@ -70,7 +78,7 @@ int run(const bcq::GemmArgs &a, hipStream_t stream)
         break;
     case BCQ_KERNEL_PLANE_F16:
         // a matrix instruction sums over all 128 columns of a step: one scale per row and step, so groups of 128 or 256
-        if (!dequant_mfma_supports(a) || a.uniform_p == 0 || a.group < 128) return BCQ_ERR_VARIANT;
+        if (!dequant_mfma_supports(a) || a.group < 128) return BCQ_ERR_VARIANT;
         err = dequant_mfma_launch(a, stream, true);
         g_last = "plane_f16";
         break;

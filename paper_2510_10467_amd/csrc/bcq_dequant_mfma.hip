@@ -680,6 +680,296 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
     }
 }
 
+
+// Per-request precision, plane-wise: the group sums B_i x of the planes are the same for every request, only the
+// scale that multiplies them is the request's own (section 3.3: a request at precision q uses planes 0 .. q-1
+// with the scale set of q).  One pass over the planes serves the whole tile whatever mix of precisions it
+// holds; a lane picks, for each of its four requests per tile and each plane, the scale of that request's
+// precision (zero from plane q on) by compare masks formed once.  NT tiles of 16 requests per workgroup.
+template <int NT, int TEAMS, int RW>
+__global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(DequantParams a)
+{
+    constexpr int kTeamThreads = 64 * RW;
+    constexpr int XU = 4 * NT / RW;
+    constexpr int PP = NT <= 2 ? 4 : 2;       // planes per pass
+    static_assert(XU >= 1, "tile does not split over the team");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    unsigned char *lut = lds;
+    unsigned char *preq = lds + 128;          // precision of each of the 16 NT requests, behind the 128-byte table
+
+    const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NT);
+    constexpr int kTile = x_tile_bytes(NT);
+    const int n16 = lane & 15, kq = lane >> 4;
+    const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
+    const int b0 = blockIdx.y * (16 * NT);
+
+    if (threadIdx.x < 16) {
+        uint32_t e[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const uint32_t lo = ((tid >> (2 * c)) & 1) ? 0x3C00u : 0xBC00u;
+            const uint32_t hi = ((tid >> (2 * c + 1)) & 1) ? 0x3C00u : 0xBC00u;
+            e[c] = lo | (hi << 16);
+        }
+        *reinterpret_cast<u32x2 *>(lut + tid * 8) = u32x2{e[0], e[1]};
+    }
+    // which precisions occur: lane l looks at request b0 + l; every wave sees the same requests
+    int p_lane = 0;
+    if (lane < 16 * NT && b0 + lane < a.batch) {
+        const int pr = a.p_req[b0 + lane];
+        p_lane = pr < 1 ? 1 : (pr > a.p_max ? a.p_max : pr);
+        if (!a.scale_sets[p_lane]) p_lane = 0;
+    }
+    bool has[kMaxP + 1];
+    int p_hi = 0;
+    bool any_offset = false;
+#pragma unroll
+    for (int q = 1; q <= kMaxP; ++q) {
+        has[q] = __ballot(p_lane == q) != 0;
+        if (has[q]) p_hi = q;
+        if (has[q] && a.offset_sets[q]) any_offset = true;
+    }
+    // precisions of this lane's own requests: accumulator u, register k holds request 16u + 4kq + k
+    int p_own[NT][4];
+#pragma unroll
+    for (int u = 0; u < NT; ++u)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p_own[u][k] = __shfl(p_lane, 16 * u + 4 * kq + k);
+
+    const unsigned char *const set1 = a.scale_sets[1], *const set2 = a.scale_sets[2], *const set3 = a.scale_sets[3],
+                        *const set4 = a.scale_sets[4];
+    const unsigned char *const off1 = a.offset_sets[1], *const off2 = a.offset_sets[2], *const off3 = a.offset_sets[3],
+                        *const off4 = a.offset_sets[4];
+    auto set_of = [&](int q) { return q == 1 ? set1 : q == 2 ? set2 : q == 3 ? set3 : set4; };
+    auto off_of = [&](int q) { return q == 1 ? off1 : q == 2 ? off2 : q == 3 ? off3 : off4; };
+
+    const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
+    uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
+    uint32_t s_lane = frow * a.scale_row_stride;
+    auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : g * 2); };
+    const int pull = (4 * n16 + kq) * 4;
+    uint32_t xs_src[XU];
+#pragma unroll
+    for (int k = 0; k < XU; ++k) {
+        const int req = 4 * (k * RW + wave) + (lane >> 4);
+        const int part = (lane & 15) ^ (req & 15);
+        xs_src[k] = (uint32_t)min(b0 + req, a.batch - 1) * a.x_stride + part * 16;
+    }
+    const unsigned char *xa_lane = xt0 + n16 * kXRowBytes;
+    uint32_t xa_off[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) xa_off[t] = (uint32_t)(((4 * kq + t) ^ n16) * 16);
+
+    auto fetch_w = [&](AheadMixed &ah, int g) {
+#pragma unroll
+        for (int i = 0; i < kMaxP; ++i) {
+            if (i < p_hi) {
+                const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
+                ah.w[i] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);
+            }
+        }
+#pragma unroll
+        for (int q = 1; q <= kMaxP; ++q) {
+            if (has[q]) {
+#pragma unroll
+                for (int i = 0; i < q; ++i) {
+                    const unsigned char *s_base = set_of(q) + (size_t)i * a.scale_plane_stride + scale_col(g);
+                    ah.alpha[q * (q - 1) / 2 + i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
+                }
+                if (off_of(q)) ah.z[q - 1] = *reinterpret_cast<const _Float16 *>(off_of(q) + scale_col(g) + s_lane);
+            }
+        }
+    };
+    auto stage_x_unit = [&](int g, int buf, int k) {
+        const unsigned char *x_base = a.x + (uint32_t)g * 256;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
+                                         (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
+    };
+
+    uint32_t lut_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lut;
+    asm volatile("" : "+s"(lut_base));
+
+    v4f acc[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
+    const v4f zero4 = v4f{0.f, 0.f, 0.f, 0.f};
+
+    auto step = [&](AheadMixed &cur, AheadMixed &nxt, int g, int buf) {
+        if (g < a.ngroups) {
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.w[i]));
+#pragma unroll
+            for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(cur.alpha[i]));
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.z[i]));
+            asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+#pragma unroll
+            for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
+            auto handed = [&](_Float16 v) {
+                const uint32_t bits = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, v));
+                return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
+            };
+            uint32_t w[kMaxP];
+            float alpha[10], z[kMaxP];
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) w[i] = i < p_hi ? (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)cur.w[i]) : 0u;
+#pragma unroll
+            for (int q = 1; q <= kMaxP; ++q) {
+                z[q - 1] = 0.f;
+                if (has[q]) {
+#pragma unroll
+                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = handed(cur.alpha[q * (q - 1) / 2 + i]);
+                    if (off_of(q)) z[q - 1] = handed(cur.z[q - 1]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = 0.f;
+                }
+            }
+            const bool more = g + TEAMS < a.ngroups;
+            if (more) fetch_w(nxt, g + TEAMS);
+            const unsigned char *xa_cur = xa_lane + buf * kTile;
+            uint32_t lo8[kMaxP], hi8[kMaxP];
+#pragma unroll
+            for (int i = 0; i < kMaxP; ++i) {
+                lo8[i] = (w[i] << 3) & 0x78787878u;
+                hi8[i] = (w[i] >> 1) & 0x78787878u;
+                if (i < p_hi) asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
+            }
+            // scale of plane i for the request in (u, k): that of the request's own precision, zero from plane p on
+            auto own_scale = [&](int i, int u, int k) {
+                float v = 0.f;
+#pragma unroll
+                for (int q = 1; q <= kMaxP; ++q)
+                    if (q > i) v = p_own[u][k] == q ? alpha[q * (q - 1) / 2 + i] : v;       // (zero for a precision no request has)
+                return v;
+            };
+            constexpr int NPASS = kMaxP / PP;
+#pragma unroll
+            for (int pass = 0; pass < NPASS; ++pass) {
+                if (pass * PP < p_hi) {
+                    v4f tmp[PP][NT];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        v8h bw[PP];
+#pragma unroll
+                        for (int ii = 0; ii < PP; ++ii) {
+                            const int i = pass * PP + ii;
+                            if (i < p_hi) {
+                                const v4h lo = *lds_at<v4h>(lut_base + ((lo8[i] >> (8 * t)) & 0xffu));
+                                const v4h hi = *lds_at<v4h>(lut_base + ((hi8[i] >> (8 * t)) & 0xffu));
+                                bw[ii] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                            }
+                        }
+                        if (more && pass == 0) {
+#pragma unroll
+                            for (int k = 0; k < XU; ++k)
+                                if (k * 4 / XU == t) stage_x_unit(g + TEAMS, buf ^ 1, k);
+                        }
+#pragma unroll
+                        for (int u = 0; u < NT; ++u) {
+                            const v8h xa = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
+#pragma unroll
+                            for (int ii = 0; ii < PP; ++ii)
+                                if (pass * PP + ii < p_hi)
+                                    tmp[ii][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, bw[ii], t == 0 ? zero4 : tmp[ii][u], 0, 0, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int ii = 0; ii < PP; ++ii)
+                        if (pass * PP + ii < p_hi) {
+#pragma unroll
+                            for (int u = 0; u < NT; ++u)
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) acc[u][k] = fmaf(own_scale(pass * PP + ii, u, k), tmp[ii][u][k], acc[u][k]);
+                        }
+                }
+            }
+            if (any_offset) {
+                v8h ones;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
+                v4f tz[NT];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) {
+                        const v8h xo = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
+                        tz[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xo, ones, t == 0 ? zero4 : tz[u], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int u = 0; u < NT; ++u)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        float zv = 0.f;
+#pragma unroll
+                        for (int q = 1; q <= kMaxP; ++q) zv = p_own[u][k] == q ? z[q - 1] : zv;
+                        acc[u][k] = fmaf(zv, tz[u][k], acc[u][k]);
+                    }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
+        __syncthreads();
+    };
+
+    AheadMixed ah0{}, ah1{};
+    if (team < a.ngroups) {
+#pragma unroll
+        for (int k = 0; k < XU; ++k) stage_x_unit(team, 0, k);
+        fetch_w(ah0, team);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
+    for (int it = 0; it < npairs; ++it) {
+        const int g = 2 * it * TEAMS + team;
+        step(ah0, ah1, g, 0);
+        step(ah1, ah0, g + TEAMS, 1);
+    }
+
+    if constexpr (TEAMS > 1) {
+        v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
+        if (team > 0) {
+#pragma unroll
+            for (int u = 0; u < NT; ++u) xchg[(((team - 1) * RW + wave) * NT + u) * 64 + lane] = acc[u];
+        }
+        __syncthreads();
+        if (team > 0) return;
+#pragma unroll
+        for (int k = 1; k < TEAMS; ++k)
+#pragma unroll
+            for (int u = 0; u < NT; ++u) acc[u] += xchg[(((k - 1) * RW + wave) * NT + u) * 64 + lane];
+    }
+
+    const uint32_t row = row0 + n16;
+    if (row < a.m) {
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int b = b0 + 16 * u + 4 * kq + k;
+                if (b < a.batch) a.y[(size_t)b * a.m + row] = (_Float16)acc[u][k];
+            }
+    }
+    (void)preq;
+}
+
+template <int NT, int TEAMS, int RW>
+hipError_t launch_planewise_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
+{
+    static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
+    auto kernel = planewise_mixed_kernel<NT, TEAMS, RW>;
+    if (lds_bytes(NT, TEAMS) > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           lds_bytes(NT, TEAMS));
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, TEAMS), stream, pr);
+    return hipGetLastError();
+}
+
 template <int TEAMS, int RW>
 hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
@@ -718,13 +1008,13 @@ hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t st
 // that small.  The cheapest product wins; dequant_mfma_force_shape overrides the choice (benchmarks, tests).
 struct WgShape {
     int nt, rw;
-    float us_p4, us_p2;         // one workgroup per CU or fewer
-    float many_p4, many_p2;     // per workgroup when the grid exceeds the chip (0: whole rounds of the above)
+    float us_p4, us_p2;         // a grid far below one workgroup per CU
+    float many_p4, many_p2;     // per workgroup and 256 workgroups of the grid when that is more (0: whole rounds of the above)
 };
 // The 16-request shapes need 32 KiB of LDS and few registers, so several of their workgroups share a CU and a
 // grid beyond 256 workgroups costs less than whole rounds; they are used up to 16 requests only (two such tiles
 // never beat one 64-request tile).
-constexpr WgShape kShapes[] = {{1, 4, 0.62f, 0.40f, 0.62f, 0.40f}, {1, 2, 0.40f, 0.28f, 0.36f, 0.235f}, {1, 1, 0.36f, 0.28f, 0.19f, 0.13f},
+constexpr WgShape kShapes[] = {{1, 4, 0.51f, 0.32f, 0.78f, 0.39f}, {1, 2, 0.36f, 0.26f, 0.34f, 0.19f}, {1, 1, 0.31f, 0.28f, 0.175f, 0.11f},
                                {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
                                {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
 
@@ -738,7 +1028,8 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
         const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * (float)((a.batch + 16 * c.nt - 1) / (16 * c.nt));
         const float one = P >= 3 ? c.us_p4 : c.us_p2, many = P >= 3 ? c.many_p4 : c.many_p2;
         float cost = one;
-        if (wgs > 256.f) cost = many > 0.f ? (wgs / 256.f * many > one ? wgs / 256.f * many : one) : __builtin_ceilf(wgs / 256.f) * one;
+        if (many > 0.f) cost = wgs / 256.f * many > one ? wgs / 256.f * many : one;
+        else if (wgs > 256.f) cost = __builtin_ceilf(wgs / 256.f) * one;
         if (best == 0.f || cost < best) {
             best = cost;
             nt = c.nt;
@@ -814,6 +1105,25 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
         }
         pr.p_req = a.p_req;
         pr.p_max = a.p_max;
+        if (planewise) {
+            // tiles of 16 requests, row blocks by the cost rule of the 16-request shapes
+            const float tiles16 = (float)((a.batch + 15) / 16);
+            int rw16 = 4;
+            float best16 = 0.f;
+            for (const WgShape &c : kShapes) {
+                if (c.nt != 1) continue;
+                const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * tiles16;
+                const float cost = wgs / 256.f * c.many_p4 > c.us_p4 ? wgs / 256.f * c.many_p4 : c.us_p4;
+                if (best16 == 0.f || cost < best16) {
+                    best16 = cost;
+                    rw16 = c.rw;
+                }
+            }
+            // (workgroups of 64 requests were measured too: 1.5-3x slower than four workgroups of 16)
+            if (g_forced_nt > 0) rw16 = g_forced_rw;
+            return rw16 == 4 ? launch_planewise_mixed<1, 4, 4>(pr, a, stream)
+                 : rw16 == 2 ? launch_planewise_mixed<1, 4, 2>(pr, a, stream) : launch_planewise_mixed<1, 4, 1>(pr, a, stream);
+        }
         // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured with three
         // precisions present: 1.8, 1.43 and 0.94 microseconds per workgroup and group of columns; two of the
         // 32-row workgroups fit a CU side by side, which is worth about 40 % once there are that many)

@@ -51,7 +51,7 @@ hipError_t plane_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t 
 bool dequant_mfma_supports(const GemmArgs &a);
 // benchmarks and tests: force the workgroup shape (request tiles of 64, or 0 for one tile of 16; blocks of 16 rows); (0, 0) = automatic
 bool dequant_mfma_force_shape(int request_tiles, int row_blocks);
-// planewise: the variant that multiplies the +-1 planes themselves and scales group sums (uniform precision only)
+// planewise: the variant that multiplies the +-1 planes themselves and scales the group sums (groups of 128 or 256)
 hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool planewise = false);
 
 // Offline quantiser (Algorithm 1): group must be 32, 64, 128 or 256; 1 <= p_low <= p_high <= 4.

@@ -203,30 +203,37 @@ def test_dequant_mfma_other_group_sizes(gpu, group, kernel):
         gpu.check_gemv(dl, 2, x, kernel, group, offsets=offsets)
 
 
+@pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
 @pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1"])
-def test_dequant_mfma_mixed(gpu, rows, forced_shape):
-    """Per-request precision on the dequantising kernel: every workgroup shape, ragged rows and request
-    tiles, tiles in which one, some or all precisions occur, a precision without a scale set (zeros),
-    precisions outside [1, p_max] (clamped), offsets for some precisions only."""
+def test_dequant_mfma_mixed(gpu, rows, forced_shape, kernel):
+    """Per-request precision on the large-batch kernels (weights rebuilt per precision present, or the planes
+    multiplied once and every request's own scales applied to the group sums): every workgroup shape, ragged
+    rows and request tiles, tiles in which one, some or all precisions occur, a precision without a scale set
+    (zeros), precisions outside [1, p_max] (clamped), offsets for some precisions only."""
     forced_shape(rows)
     m, n = 150, 1536
     layer = syn.make_layer(m, n, seed=(154, 0), signed=True)
     dl = gpu.DeviceLayer(layer)
-    for batch in (5, 64, 130):
+    for batch in (5, 16, 64, 130):
         x = syn.make_x(batch, n, seed=(154, batch))
         p_req = syn.make_p_req(batch, 1, 4, seed=(154, batch))
-        used, _ = gpu.check_mixed(dl, p_req, x, "dequant_mfma")
-        assert used == "dequant_mfma"
-        gpu.check_mixed(dl, np.full(batch, 3, dtype=np.int32), x, "dequant_mfma")           # one precision only
+        used, _ = gpu.check_mixed(dl, p_req, x, kernel)
+        assert used == kernel
+        gpu.check_mixed(dl, np.full(batch, 3, dtype=np.int32), x, kernel)           # one precision only
         two = np.where(np.arange(batch) % 2 == 0, 2, 4).astype(np.int32)
-        gpu.check_mixed(dl, two, x, "dequant_mfma")
+        gpu.check_mixed(dl, two, x, kernel)
     zs = {p: syn.make_offsets(p, m, n, seed=(154, p)) for p in (2, 4)}
     x = syn.make_x(70, n, seed=(154, 70))
     p_req = syn.make_p_req(70, 1, 4, seed=(154, 71))
-    gpu.check_mixed(dl, p_req, x, "dequant_mfma", offsets_by_p=zs)
+    gpu.check_mixed(dl, p_req, x, kernel, offsets_by_p=zs)
+    if kernel == "plane_f16":
+        wide = gpu.DeviceLayer(syn.make_layer(70, 2048, group=256, seed=(154, 9), signed=True))
+        zw = {p: syn.make_offsets(p, 70, 2048, 256, seed=(154, p)) for p in (3,)}
+        gpu.check_mixed(wide, syn.make_p_req(13, 1, 4, seed=(154, 13)), syn.make_x(13, 2048, seed=(154, 13)), kernel, 256, offsets_by_p=zw)
 
 
-def test_dequant_mfma_mixed_clamps_and_missing_sets(gpu):
+@pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
+def test_dequant_mfma_mixed_clamps_and_missing_sets(gpu, kernel):
     import torch
 
     import paper_2510_10467_amd as bcq
@@ -236,14 +243,14 @@ def test_dequant_mfma_mixed_clamps_and_missing_sets(gpu):
     x = syn.make_x(batch, n, seed=(155, 1))
     wild = np.array([0, -3, 9, 2, 3] * 8, dtype=np.int32)                 # clamped to 1, 1, 4, 2, 3
     clamped = np.clip(wild, 1, 4).astype(np.int32)
-    bcq.select_kernel("dequant_mfma")
+    bcq.select_kernel(kernel)
     try:
         y_wild = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(wild), gpu.to_dev(x))
         y_ok = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(clamped), gpu.to_dev(x))
         some = {p: s for p, s in dl.scales.items() if p != 3}              # no scale set for precision 3
         y_some = bcq.bcq_gemm_mixed(dl.planes, some, gpu.to_dev(clamped), gpu.to_dev(x))
         torch.cuda.synchronize()
-        assert bcq.last_kernel() == "dequant_mfma"
+        assert bcq.last_kernel() == kernel
     finally:
         bcq.select_kernel("auto")
     assert torch.equal(y_wild, y_ok)
@@ -286,7 +293,10 @@ def test_auto_dispatch_by_batch(gpu):
     p_req = syn.make_p_req(40, 1, 4, seed=(170, 4))
     used, _ = gpu.check_mixed(dl, p_req, syn.make_x(40, 2048, seed=(170, 4)), "auto")
     assert used == "plane_mfma"            # 96 rows: too short for the dequantising kernel
-    used, _ = gpu.check_mixed(big, p_req, syn.make_x(40, 1024, seed=(171, 4)), "auto")  # 40 requests
+    used, _ = gpu.check_mixed(big, p_req, syn.make_x(40, 1024, seed=(171, 4)), "auto")  # 40 requests: tiles of 16
+    assert used == "plane_f16"
+    p_many = syn.make_p_req(130, 1, 4, seed=(171, 7))
+    used, _ = gpu.check_mixed(big, p_many, syn.make_x(130, 1024, seed=(171, 7)), "auto")
     assert used == "dequant_mfma"
     used, _ = gpu.check_mixed(big, p_req[:16], syn.make_x(16, 1024, seed=(171, 5)), "auto")
     assert used == "plane_mfma"
@@ -302,7 +312,11 @@ def test_auto_dispatch_by_batch(gpu):
     used, _ = gpu.check_gemv(tall, 2, syn.make_x(5, 1024, seed=(172, 5)), "auto")
     assert used == "plane_f16"
     used, _ = gpu.check_mixed(tall, p_req[:30], syn.make_x(30, 1024, seed=(172, 3)), "auto")
+    assert used == "plane_f16"
+    used, _ = gpu.check_mixed(tall, p_many[:49], syn.make_x(49, 1024, seed=(172, 7)), "auto")
     assert used == "dequant_mfma"
+    used, _ = gpu.check_mixed(tall, p_req[:8], syn.make_x(8, 1024, seed=(172, 8)), "auto")
+    assert used == "plane_mfma"
 
 
 # ----------------------------------------------------------------------------

@@ -106,8 +106,8 @@ def test_one_hot_readout_and_symmetries(gpu, oracle):
 
 @pytest.mark.parametrize("m,n,batch", [(14336, 4096, 16), (14336, 4096, 96), (4096, 14336, 200)])
 def test_full_size_mixed_precision_sampled_rows(gpu, oracle, m, n, batch):
-    """Per-request precision at the benchmark's shapes: the paper-sized batch on the plane-wise kernel, serving-sized
-    ones on the dequantising kernel."""
+    """Per-request precision at the benchmark's shapes: the paper-sized batch on the plane-wise fp16 kernel,
+    serving-sized ones on the dequantising kernel."""
     import torch
 
     import paper_2510_10467_amd as bcq
@@ -117,7 +117,7 @@ def test_full_size_mixed_precision_sampled_rows(gpu, oracle, m, n, batch):
     p_req = syn.make_p_req(batch, 2, 4, seed=(231, batch))
     y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req), gpu.to_dev(x))
     torch.cuda.synchronize()
-    assert bcq.last_kernel() == ("plane_mfma" if batch < 40 else "dequant_mfma")
+    assert bcq.last_kernel() == {16: "plane_f16", 96: "dequant_mfma", 200: "dequant_mfma"}[batch]
     rng = np.random.default_rng([syn.BASE_SEED, 231, m])
     rows = np.unique(np.concatenate([[0, 15, 16, m - 1], rng.integers(0, m, size=60)]))
     sub = {p: np.ascontiguousarray(s[:, rows, :]) for p, s in layer.scales.items()}

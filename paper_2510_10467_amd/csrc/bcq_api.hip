@@ -38,11 +38,11 @@ int choose(const bcq::GemmArgs &a)
         int from = a.m >= 8192 && a.uniform_p <= 2 ? 5 : 9;
         bool tiles16 = f16_ok && a.batch <= 16;
         // Per-request precision: the plane-wise fp16 variant works in tiles of 16 requests whatever mix of
-        // precisions they hold (from 9 requests on 8192 rows and more, from 17 on 4096); rebuilding the weights
+        // precisions they hold (from 9 requests on); rebuilding the weights
         // once per precision present takes over from 49 requests (8192 rows and more) or 129 on, and from 28 / 40
         // requests where the fp16 variant cannot run.
         if (a.uniform_p == 0) {
-            from = f16_ok ? (a.m >= 8192 ? 9 : 17) : (a.m >= 8192 ? 28 : 40);
+            from = f16_ok ? 9 : (a.m >= 8192 ? 28 : 40);
             tiles16 = f16_ok && a.batch <= (a.m >= 8192 ? 48 : 128);
         }
         const bool pays = a.m >= 4096 && a.batch >= from;

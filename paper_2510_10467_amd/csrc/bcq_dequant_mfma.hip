@@ -35,6 +35,8 @@
 // from measured per-shape costs (launch_p).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "bcq_internal.hpp"
 
 namespace bcq {
@@ -686,8 +688,10 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 // with the scale set of q).  One pass over the planes serves the whole tile whatever mix of precisions it
 // holds; a lane picks, for each of its four requests per tile and each plane, the scale of that request's
 // precision (zero from plane q on) by compare masks formed once.  NT tiles of 16 requests per workgroup.
+// (At least four waves per SIMD: two of the 32-row workgroups then share a CU, which the kernel needs more than
+// the dozen extra registers the compiler would otherwise take.)
 template <int NT, int TEAMS, int RW>
-__global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(DequantParams a)
+__global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(4))) void planewise_mixed_kernel(DequantParams a)
 {
     constexpr int kTeamThreads = 64 * RW;
     constexpr int XU = 4 * NT / RW;
@@ -731,12 +735,17 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
         if (has[q]) p_hi = q;
         if (has[q] && a.offset_sets[q]) any_offset = true;
     }
-    // precisions of this lane's own requests: accumulator u, register k holds request 16u + 4kq + k
-    int p_own[NT][4];
+    // This lane's own requests: accumulator u, register k holds request 16u + 4kq + k.  The scales of a plane
+    // travel as four binary16 values in two registers (sets 1 | 2 and 3 | 4); `pick` is the byte selector that
+    // moves the value of the request's precision into the low half (a precision of 0 selects zero bytes).
+    uint32_t pick[NT][4];
 #pragma unroll
     for (int u = 0; u < NT; ++u)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) p_own[u][k] = __shfl(p_lane, 16 * u + 4 * kq + k);
+        for (int k = 0; k < 4; ++k) {
+            const int pq = __shfl(p_lane, 16 * u + 4 * kq + k);
+            pick[u][k] = pq == 0 ? 0x0C0C0C0Cu : 0x0C0C0000u | (uint32_t)((2 * pq - 1) << 8) | (uint32_t)(2 * pq - 2);
+        }
 
     const unsigned char *const set1 = a.scale_sets[1], *const set2 = a.scale_sets[2], *const set3 = a.scale_sets[3],
                         *const set4 = a.scale_sets[4];
@@ -762,17 +771,30 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
 #pragma unroll
     for (int t = 0; t < 4; ++t) xa_off[t] = (uint32_t)(((4 * kq + t) ^ n16) * 16);
 
+    uint32_t lut_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lut;
+    asm volatile("" : "+s"(lut_base));
+
+    v4f acc[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
+    const v4f zero4 = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // The sweep over the groups, with the number of planes the tile needs (its highest precision) as a
+    // compile-time number: inside, a step is one straight run of instructions.
+    auto sweep = [&](auto ph_tag) {
+    constexpr int PH = decltype(ph_tag)::value;
     auto fetch_w = [&](AheadMixed &ah, int g) {
 #pragma unroll
         for (int i = 0; i < kMaxP; ++i) {
-            if (i < p_hi) {
+            if (i < PH) {
                 const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
                 ah.w[i] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);
             }
         }
 #pragma unroll
-        for (int q = 1; q <= kMaxP; ++q) {
-            if (has[q]) {
+        for (int q = 1; q <= PH; ++q) {
+            if (q == PH || has[q]) {
+                asm volatile("" : "+v"(s_lane));      // (keeps the widening of the offset next to the loads, see the step)
 #pragma unroll
                 for (int i = 0; i < q; ++i) {
                     const unsigned char *s_base = set_of(q) + (size_t)i * a.scale_plane_stride + scale_col(g);
@@ -788,14 +810,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
                                          (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
     };
 
-    uint32_t lut_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lut;
-    asm volatile("" : "+s"(lut_base));
-
-    v4f acc[NT];
-#pragma unroll
-    for (int u = 0; u < NT; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
-    const v4f zero4 = v4f{0.f, 0.f, 0.f, 0.f};
-
     auto step = [&](AheadMixed &cur, AheadMixed &nxt, int g, int buf) {
         if (g < a.ngroups) {
 #pragma unroll
@@ -807,25 +821,26 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
             asm volatile("" : "+v"(w_lane), "+v"(s_lane));
 #pragma unroll
             for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
-            auto handed = [&](_Float16 v) {
-                const uint32_t bits = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, v));
-                return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
+            // (scales of a precision no request of the tile has were never fetched: they are still zero)
+            auto half_bits = [](_Float16 v) { return (uint32_t)__builtin_bit_cast(unsigned short, v); };
+            auto own_value = [](uint32_t hi, uint32_t lo, uint32_t sel) {
+                return (float)__builtin_bit_cast(_Float16, (unsigned short)__builtin_amdgcn_perm(hi, lo, sel));
             };
-            uint32_t w[kMaxP];
-            float alpha[10], z[kMaxP];
+            uint32_t w[kMaxP], s_lo[kMaxP], s_hi[kMaxP];
 #pragma unroll
-            for (int i = 0; i < kMaxP; ++i) w[i] = i < p_hi ? (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)cur.w[i]) : 0u;
+            for (int i = 0; i < kMaxP; ++i) w[i] = i < PH ? (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)cur.w[i]) : 0u;
 #pragma unroll
-            for (int q = 1; q <= kMaxP; ++q) {
-                z[q - 1] = 0.f;
-                if (has[q]) {
-#pragma unroll
-                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = handed(cur.alpha[q * (q - 1) / 2 + i]);
-                    if (off_of(q)) z[q - 1] = handed(cur.z[q - 1]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = 0.f;
-                }
+            for (int i = 0; i < kMaxP; ++i) {
+                // plane i belongs to the sets q > i
+                const uint32_t lo = (i < 1 ? half_bits(cur.alpha[0]) : 0u) | (i < 2 ? half_bits(cur.alpha[1 + i]) << 16 : 0u);
+                const uint32_t hi = (i < 3 ? half_bits(cur.alpha[3 + i]) : 0u) | (half_bits(cur.alpha[6 + i]) << 16);
+                s_lo[i] = i < 2 ? (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)lo) : 0u;
+                s_hi[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)hi);
+            }
+            uint32_t z_lo = 0, z_hi = 0;
+            if (any_offset) {
+                z_lo = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)(half_bits(cur.z[0]) | half_bits(cur.z[1]) << 16));
+                z_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)(half_bits(cur.z[2]) | half_bits(cur.z[3]) << 16));
             }
             const bool more = g + TEAMS < a.ngroups;
             if (more) fetch_w(nxt, g + TEAMS);
@@ -835,20 +850,14 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
             for (int i = 0; i < kMaxP; ++i) {
                 lo8[i] = (w[i] << 3) & 0x78787878u;
                 hi8[i] = (w[i] >> 1) & 0x78787878u;
-                if (i < p_hi) asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
+                if (i < PH) asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
             }
             // scale of plane i for the request in (u, k): that of the request's own precision, zero from plane p on
-            auto own_scale = [&](int i, int u, int k) {
-                float v = 0.f;
-#pragma unroll
-                for (int q = 1; q <= kMaxP; ++q)
-                    if (q > i) v = p_own[u][k] == q ? alpha[q * (q - 1) / 2 + i] : v;       // (zero for a precision no request has)
-                return v;
-            };
+            auto own_scale = [&](int i, int u, int k) { return own_value(s_hi[i], s_lo[i], pick[u][k]); };
             constexpr int NPASS = kMaxP / PP;
 #pragma unroll
             for (int pass = 0; pass < NPASS; ++pass) {
-                if (pass * PP < p_hi) {
+                if (pass * PP < PH) {
                     v4f tmp[PP][NT];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
@@ -856,7 +865,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
 #pragma unroll
                         for (int ii = 0; ii < PP; ++ii) {
                             const int i = pass * PP + ii;
-                            if (i < p_hi) {
+                            if (i < PH) {
                                 const v4h lo = *lds_at<v4h>(lut_base + ((lo8[i] >> (8 * t)) & 0xffu));
                                 const v4h hi = *lds_at<v4h>(lut_base + ((hi8[i] >> (8 * t)) & 0xffu));
                                 bw[ii] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -872,13 +881,13 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
                             const v8h xa = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
 #pragma unroll
                             for (int ii = 0; ii < PP; ++ii)
-                                if (pass * PP + ii < p_hi)
+                                if (pass * PP + ii < PH)
                                     tmp[ii][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, bw[ii], t == 0 ? zero4 : tmp[ii][u], 0, 0, 0);
                         }
                     }
 #pragma unroll
                     for (int ii = 0; ii < PP; ++ii)
-                        if (pass * PP + ii < p_hi) {
+                        if (pass * PP + ii < PH) {
 #pragma unroll
                             for (int u = 0; u < NT; ++u)
 #pragma unroll
@@ -901,12 +910,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
 #pragma unroll
                 for (int u = 0; u < NT; ++u)
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        float zv = 0.f;
-#pragma unroll
-                        for (int q = 1; q <= kMaxP; ++q) zv = p_own[u][k] == q ? z[q - 1] : zv;
-                        acc[u][k] = fmaf(zv, tz[u][k], acc[u][k]);
-                    }
+                    for (int k = 0; k < 4; ++k) acc[u][k] = fmaf(own_value(z_hi, z_lo, pick[u][k]), tz[u][k], acc[u][k]);
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
@@ -926,6 +930,14 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void planewise_mixed_kernel(Dequan
         const int g = 2 * it * TEAMS + team;
         step(ah0, ah1, g, 0);
         step(ah1, ah0, g + TEAMS, 1);
+    }
+    };
+    switch (p_hi) {       // the same in every wave of the workgroup: all of them take the same barriers
+    case 1: sweep(std::integral_constant<int, 1>{}); break;
+    case 2: sweep(std::integral_constant<int, 2>{}); break;
+    case 3: sweep(std::integral_constant<int, 3>{}); break;
+    case 4: sweep(std::integral_constant<int, 4>{}); break;
+    default: break;       // no request of the tile has a scale set: zeros
     }
 
     if constexpr (TEAMS > 1) {

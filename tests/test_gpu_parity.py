@@ -299,6 +299,8 @@ def test_auto_dispatch_by_batch(gpu):
     used, _ = gpu.check_mixed(big, p_many, syn.make_x(130, 1024, seed=(171, 7)), "auto")
     assert used == "dequant_mfma"
     used, _ = gpu.check_mixed(big, p_req[:16], syn.make_x(16, 1024, seed=(171, 5)), "auto")
+    assert used == "plane_f16"
+    used, _ = gpu.check_mixed(big, p_req[:8], syn.make_x(8, 1024, seed=(171, 8)), "auto")
     assert used == "plane_mfma"
     tall = gpu.DeviceLayer(syn.make_layer(8192, 1024, seed=(172, 0)))          # 8192 rows: the crossover sits at 9 requests (5 for p <= 2)
     used, _ = gpu.check_gemv(tall, 3, syn.make_x(8, 1024, seed=(172, 1)), "auto")

@@ -1,10 +1,18 @@
+// The kernels for more than a handful of requests, all built on one skeleton (activation tiles staged in LDS,
+// plane words expanded to +-1.0 binary16 through a 16-entry table, fp16 matrix instructions):
+//   dequant_mfma_kernel      uniform precision; rebuilds W_p in registers (below), or with PW = true multiplies the
+//                            +-1 planes themselves and scales the group sums ("plane_f16", one tile of 16 requests)
+//   planewise_mixed_kernel   per-request precision in tiles of 16 requests: one pass over the planes, each request's
+//                            own scales applied to the group sums
+//   dequant_mixed_kernel     per-request precision at 64 requests per workgroup: W_q rebuilt once per precision present
+//
 // Large-batch kernel: dequantise W_p = sum_i alpha_i B_i tile by tile (Fig. 1(b): p-bit inference
 // reconstructs the weights from the first p planes and the scale set of precision p) and feed the
 // binary16 tiles to the fp16 matrix pipe.  Once a plane word serves dozens of requests the product
 // is no longer bound by HBM but by arithmetic, and one dense fp16 MFMA over dequantised weights
 // costs p times fewer matrix instructions than p plane-wise products.
 //
-// A team of RW waves (RW = 4, 2 or 1) owns 16 RW weight rows (16 per wave) and TB = 64, 128 or 256 requests.
+// A team of RW waves (RW = 4, 2 or 1) owns 16 RW weight rows (16 per wave) and TB = 16, 64, 128 or 256 requests.
 // Per group of 128 columns
 //   * the team stages the TB x 128 activation tile of the NEXT group in LDS with loads that write LDS
 //     directly (global_load_lds_dwordx4: 64 lanes deliver 1 KiB = four requests' rows, no registers, no

@@ -441,3 +441,22 @@ def test_benchmark_reference_kernels(gpu):
     bcq.bench_stream_read(buf, sink)
     torch.cuda.synchronize()
     assert int(sink.abs().sum()) == 0
+
+
+@pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
+@pytest.mark.parametrize("n", [128, 256, 384])
+def test_large_batch_kernels_on_one_to_three_groups(gpu, kernel, n):
+    """Fewer 128-column groups than teams in a workgroup: some teams have nothing to do but still take every
+    barrier; uniform and per-request precision, offsets, all three batch regimes."""
+    m = 50
+    layer = syn.make_layer(m, n, seed=(157, n), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    z = syn.make_offsets(3, m, n, seed=(157, 1))
+    for batch in (1, 16, 70, 257):
+        x = syn.make_x(batch, n, seed=(157, batch))
+        for p in (1, 4):
+            used, _ = gpu.check_gemv(dl, p, x, kernel)
+            assert used == kernel
+        gpu.check_gemv(dl, 3, x, kernel, offsets=z)
+        used, _ = gpu.check_mixed(dl, syn.make_p_req(batch, 1, 4, seed=(157, batch)), x, kernel)
+        assert used == kernel

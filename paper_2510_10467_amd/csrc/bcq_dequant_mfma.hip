@@ -707,7 +707,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     static_assert(XU >= 1, "tile does not split over the team");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     unsigned char *lut = lds;
-    unsigned char *preq = lds + 128;          // precision of each of the 16 NT requests, behind the 128-byte table
 
     const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -972,7 +971,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
                 if (b < a.batch) a.y[(size_t)b * a.m + row] = (_Float16)acc[u][k];
             }
     }
-    (void)preq;
 }
 
 template <int NT, int TEAMS, int RW>

@@ -198,32 +198,35 @@ def run_suite(args, torch, bcq, syn, dev):
                          "seven_calls_GBps": round(by / us_sep / 1e3, 1), "four_calls_GBps": round(by / us_fus / 1e3, 1),
                          "pct_of_hbm_peak_four_calls": round(100 * by / us_fus / 1e3 / HBM_PEAK_GBS, 2)})
     elif args.suite == "step":
-        # The linear layers of one whole decoding step of a Llama-3-8B-shaped model (32 decoder layers, batch 1) as
-        # ONE HIP graph of 128 launches: per layer q/k/v together, o, gate/up together, down.  Every layer has its
+        # The linear layers of one whole decoding step of a Llama-3-8B-shaped model (32 decoder layers; batches 1, 16
+        # and 64) as ONE HIP graph (128 launches at batch 1): per layer q/k/v together, o, gate/up together, down.  Every layer has its
         # own planes and scale sets (3.5 GB of planes), so nothing is warm.  Attention, norms and the vocabulary
         # projection are not part of the library and not in the figure: the tokens/s is an upper bound.
         shapes = {"q": (4096, 4096), "k": (1024, 4096), "v": (1024, 4096), "o": (4096, 4096),
                   "gate": (14336, 4096), "up": (14336, 4096), "down": (4096, 14336)}
         n_layers = 32
         model = [{name: device_layer(m, n) for name, (m, n) in shapes.items()} for _ in range(n_layers)]
-        x4k = torch.randn((1, 4096), device=dev, generator=gen).half()
-        x14k = torch.randn((1, 14336), device=dev, generator=gen).half()
-        ys = {name: torch.empty((1, m), dtype=torch.float16, device=dev) for name, (m, n) in shapes.items()}
-        for p in PRECISIONS:
-            def step():
-                for L in model:
-                    bcq.bcq_gemv_multi([L[k][0] for k in ("q", "k", "v")], [L[k][1][p] for k in ("q", "k", "v")], p, x4k,
-                                       [ys[k] for k in ("q", "k", "v")])
-                    bcq.bcq_gemv(L["o"][0], L["o"][1][p], p, x4k, ys["o"])
-                    bcq.bcq_gemv_multi([L[k][0] for k in ("gate", "up")], [L[k][1][p] for k in ("gate", "up")], p, x4k,
-                                       [ys[k] for k in ("gate", "up")])
-                    bcq.bcq_gemv(L["down"][0], L["down"][1][p], p, x14k, ys["down"])
-            by = n_layers * sum(syn.algorithmic_bytes(m, n, p, 1) for (m, n) in shapes.values())
-            ms = timed_graph(step)
-            rows.append({"workload": "linear layers of one decoding step, Llama-3-8B shapes, 32 layers, batch 1", "p": p,
-                         "launches": 4 * n_layers, "ms_per_token": round(ms, 4), "GBps": round(by / ms / 1e6, 1),
-                         "pct_of_hbm_peak": round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 2),
-                         "tokens_per_s_upper_bound": round(1e3 / ms, 1)})
+        for batch in (1, 16, 64):
+            x4k = torch.randn((batch, 4096), device=dev, generator=gen).half()
+            x14k = torch.randn((batch, 14336), device=dev, generator=gen).half()
+            ys = {name: torch.empty((batch, m), dtype=torch.float16, device=dev) for name, (m, n) in shapes.items()}
+            for p in PRECISIONS:
+                def step():
+                    for L in model:
+                        bcq.bcq_gemv_multi([L[k][0] for k in ("q", "k", "v")], [L[k][1][p] for k in ("q", "k", "v")], p, x4k,
+                                           [ys[k] for k in ("q", "k", "v")])
+                        bcq.bcq_gemv(L["o"][0], L["o"][1][p], p, x4k, ys["o"])
+                        bcq.bcq_gemv_multi([L[k][0] for k in ("gate", "up")], [L[k][1][p] for k in ("gate", "up")], p, x4k,
+                                           [ys[k] for k in ("gate", "up")])
+                        bcq.bcq_gemv(L["down"][0], L["down"][1][p], p, x14k, ys["down"])
+                by = n_layers * sum(syn.algorithmic_bytes(m, n, p, batch) for (m, n) in shapes.values())
+                ms = timed_graph(step)
+                # (beyond eight requests the several-matrices call launches its matrices one by one: 7 launches per layer)
+                rows.append({"workload": f"linear layers of one decoding step, Llama-3-8B shapes, 32 layers, batch {batch}", "p": p,
+                             "batch": batch, "launches": (4 if batch <= 8 else 7) * n_layers, "ms_per_step": round(ms, 4),
+                             "ms_per_token": round(ms / batch, 4), "GBps": round(by / ms / 1e6, 1),
+                             "pct_of_hbm_peak": round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 2),
+                             "tokens_per_s_upper_bound": round(batch * 1e3 / ms, 1)})
     elif args.suite == "quant":
         # The offline quantiser (Algorithm 1, p_L = 2, p_H = 4, T = 20, g = 128) on Llama-3-8B layer shapes.
         # Bound by double-precision vector arithmetic: per weight and cycle the base stage adds p signed terms

@@ -45,7 +45,11 @@ int choose(const bcq::GemmArgs &a)
             from = f16_ok ? 9 : (a.m >= 8192 ? 28 : 40);
             tiles16 = f16_ok && a.batch <= (a.m >= 8192 ? 48 : 128);
         }
-        const bool pays = a.m >= 4096 && a.batch >= from;
+        bool pays = a.m >= 4096 && a.batch >= from;
+        // Shorter matrices give the large-batch kernel few workgroups, but the FP4 kernel's time still grows with
+        // the batch: measured crossovers at 24 / 40 / 70 requests for 3072 / 2048 / 1024 rows (p = 4; a fifth later
+        // for p = 2), i.e. at about 80 000 (90 000) rows x requests.  Uniform precision only.
+        if (a.m < 4096 && a.m >= 1024 && a.uniform_p > 0) pays = a.batch * a.m >= (a.uniform_p >= 3 ? 80000 : 90000);
         if (dequant_mfma_supports(a) && pays) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all

@@ -302,6 +302,11 @@ def test_auto_dispatch_by_batch(gpu):
     assert used == "plane_f16"
     used, _ = gpu.check_mixed(big, p_req[:8], syn.make_x(8, 1024, seed=(171, 8)), "auto")
     assert used == "plane_mfma"
+    short = gpu.DeviceLayer(syn.make_layer(2048, 1024, seed=(173, 0)))         # 2048 rows: the large-batch kernel from 40 requests on
+    used, _ = gpu.check_gemv(short, 4, syn.make_x(32, 1024, seed=(173, 1)), "auto")
+    assert used == "plane_mfma"
+    used, _ = gpu.check_gemv(short, 4, syn.make_x(48, 1024, seed=(173, 2)), "auto")
+    assert used == "dequant_mfma"
     tall = gpu.DeviceLayer(syn.make_layer(8192, 1024, seed=(172, 0)))          # 8192 rows: the crossover sits at 9 requests (5 for p <= 2)
     used, _ = gpu.check_gemv(tall, 3, syn.make_x(8, 1024, seed=(172, 1)), "auto")
     assert used == "plane_mfma"

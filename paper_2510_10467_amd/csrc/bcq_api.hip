@@ -50,6 +50,12 @@ int choose(const bcq::GemmArgs &a)
         // the batch: measured crossovers at 24 / 40 / 70 requests for 3072 / 2048 / 1024 rows (p = 4; a fifth later
         // for p = 2), i.e. at about 80 000 (90 000) rows x requests.  Uniform precision only.
         if (a.m < 4096 && a.m >= 1024 && a.uniform_p > 0) pays = a.batch * a.m >= (a.uniform_p >= 3 ? 80000 : 90000);
+        // ... and with per-request precision the tiles of 16 from about 70 000 rows x requests on (2048 rows: 32 requests),
+        // up to 256 requests
+        if (a.m < 4096 && a.m >= 1024 && a.uniform_p == 0 && f16_ok) {
+            pays = a.batch * a.m >= 70000;
+            tiles16 = a.batch <= 256;
+        }
         if (dequant_mfma_supports(a) && pays) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all

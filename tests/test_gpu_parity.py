@@ -307,6 +307,10 @@ def test_auto_dispatch_by_batch(gpu):
     assert used == "plane_mfma"
     used, _ = gpu.check_gemv(short, 4, syn.make_x(48, 1024, seed=(173, 2)), "auto")
     assert used == "dequant_mfma"
+    used, _ = gpu.check_mixed(short, p_req[:30], syn.make_x(30, 1024, seed=(173, 3)), "auto")
+    assert used == "plane_mfma"
+    used, _ = gpu.check_mixed(short, p_req, syn.make_x(40, 1024, seed=(173, 4)), "auto")
+    assert used == "plane_f16"
     tall = gpu.DeviceLayer(syn.make_layer(8192, 1024, seed=(172, 0)))          # 8192 rows: the crossover sits at 9 requests (5 for p <= 2)
     used, _ = gpu.check_gemv(tall, 3, syn.make_x(8, 1024, seed=(172, 1)), "auto")
     assert used == "plane_mfma"

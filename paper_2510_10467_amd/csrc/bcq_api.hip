@@ -32,11 +32,11 @@ int choose(const bcq::GemmArgs &a)
         // the batch in steps of four requests.  Measured crossovers (Llama-3-8B and 70B shapes, p = 2 and 4): on
         // matrices of at least 8192 rows 9 requests (5 for p <= 2), from 4096 rows on 9; shorter matrices
         // leave the large-batch kernels too few workgroups.
-        // Up to 16 requests (one tile) multiplying the +-1 planes themselves and scaling the group sums beats
-        // rebuilding the weights by 5-15 %; beyond that it is the other way round.
+        // Up to 32 requests (one tile of 16 or 32) multiplying the +-1 planes themselves and scaling the group sums
+        // beats rebuilding the weights by up to 15 %; beyond that it is the other way round.
         const bool f16_ok = a.group >= 128;                     // the fp16 plane-wise variant needs one scale per 128-column step
         int from = a.m >= 8192 && a.uniform_p <= 2 ? 5 : 9;
-        bool tiles16 = f16_ok && a.batch <= 16;
+        bool tiles16 = f16_ok && a.batch <= 32;                 // one tile of 16 or 32 requests
         // Per-request precision: the plane-wise fp16 variant works in tiles of 16 requests whatever mix of
         // precisions they hold (from 9 requests on); rebuilding the weights
         // once per precision present takes over from 49 requests (8192 rows and more) or 129 on, and from 28 / 40

@@ -699,7 +699,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 // (At least four waves per SIMD: two of the 32-row workgroups then share a CU, which the kernel needs more than
 // the dozen extra registers the compiler would otherwise take.)
 template <int NT, int TEAMS, int RW>
-__global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(4))) void planewise_mixed_kernel(DequantParams a)
+__global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 4 : 2))) void planewise_mixed_kernel(DequantParams a)
 {
     constexpr int kTeamThreads = 64 * RW;
     constexpr int XU = 4 * NT / RW;
@@ -1029,10 +1029,11 @@ struct WgShape {
     float us_p4, us_p2;         // a grid far below one workgroup per CU
     float many_p4, many_p2;     // per workgroup and 256 workgroups of the grid when that is more (0: whole rounds of the above)
 };
-// The 16-request shapes need 32 KiB of LDS and few registers, so several of their workgroups share a CU and a
-// grid beyond 256 workgroups costs less than whole rounds; they are used up to 16 requests only (two such tiles
-// never beat one 64-request tile).
+// The 16- and 32-request shapes need 32 or 64 KiB of LDS and few registers, so several of their workgroups share a
+// CU and a grid beyond 256 workgroups costs less than whole rounds; they are used for a single tile only (two
+// such tiles never beat one 64-request tile).
 constexpr WgShape kShapes[] = {{1, 4, 0.51f, 0.32f, 0.78f, 0.39f}, {1, 2, 0.36f, 0.26f, 0.34f, 0.19f}, {1, 1, 0.31f, 0.28f, 0.175f, 0.11f},
+                               {2, 4, 0.62f, 0.40f, 0.89f, 0.48f}, {2, 2, 0.41f, 0.30f, 0.44f, 0.25f}, {2, 1, 0.37f, 0.37f, 0.26f, 0.175f},
                                {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
                                {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
 
@@ -1042,7 +1043,7 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
     int nt = 4, rw = 4;
     float best = 0.f;
     for (const WgShape &c : kShapes) {
-        if (c.nt == 1 && a.batch > 16) continue;
+        if (c.nt <= 2 && a.batch > 16 * c.nt) continue;
         const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * (float)((a.batch + 16 * c.nt - 1) / (16 * c.nt));
         const float one = P >= 3 ? c.us_p4 : c.us_p2, many = P >= 3 ? c.many_p4 : c.many_p2;
         float cost = one;
@@ -1062,6 +1063,9 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
     case 14: return launch_one<P, 1, 4, 4, PW>(pr, a, stream);
     case 12: return launch_one<P, 1, 4, 2, PW>(pr, a, stream);
     case 11: return launch_one<P, 1, 4, 1, PW>(pr, a, stream);
+    case 24: return launch_one<P, 2, 4, 4, PW>(pr, a, stream);
+    case 22: return launch_one<P, 2, 4, 2, PW>(pr, a, stream);
+    case 21: return launch_one<P, 2, 4, 1, PW>(pr, a, stream);
     case 44: return launch_one<P, 4, 4, 4, PW>(pr, a, stream);
     case 42: return launch_one<P, 4, 4, 2, PW>(pr, a, stream);
     case 41: return launch_one<P, 4, 4, 1, PW>(pr, a, stream);
@@ -1081,9 +1085,10 @@ bool dequant_mfma_force_shape(int request_tiles, int row_blocks)
         g_forced_nt = g_forced_rw = 0;
         return true;
     }
-    const int nt = request_tiles == 0 ? 1 : 4 * request_tiles;
+    const int nt = request_tiles == 0 ? 1 : request_tiles == 32 ? 2 : 4 * request_tiles;      // 32: a tile of 32 requests
     const int key = nt * 10 + row_blocks;
-    const bool known = key == 14 || key == 12 || key == 11 || key == 44 || key == 42 || key == 41 || key == 84 || key == 82 || key == 164;
+    const bool known = key == 14 || key == 12 || key == 11 || key == 24 || key == 22 || key == 21 || key == 44 || key == 42 || key == 41 ||
+                       key == 84 || key == 82 || key == 164;
     if (!known || request_tiles < 0 || (row_blocks != 1 && row_blocks != 2 && row_blocks != 4)) return false;
     g_forced_nt = nt;
     g_forced_rw = row_blocks;
@@ -1138,7 +1143,16 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
                 }
             }
             // (workgroups of 64 requests were measured too: 1.5-3x slower than four workgroups of 16)
-            if (g_forced_nt > 0) rw16 = g_forced_rw;
+            // beyond 16 requests tiles of 32 (16 rows per workgroup, 32 on the tallest matrices): 14336x4096 at 32 requests
+            // 42 -> 33 us
+            bool pairs = a.batch > 16;
+            if (pairs) rw16 = a.m >= 16384 ? 2 : 1;
+            if (g_forced_nt > 0) {
+                rw16 = g_forced_rw;
+                pairs = g_forced_nt == 2;
+            }
+            if (pairs)      // (with 64 rows per workgroup such a tile would not fit the registers of sixteen waves)
+                return rw16 >= 2 ? launch_planewise_mixed<2, 4, 2>(pr, a, stream) : launch_planewise_mixed<2, 4, 1>(pr, a, stream);
             return rw16 == 4 ? launch_planewise_mixed<1, 4, 4>(pr, a, stream)
                  : rw16 == 2 ? launch_planewise_mixed<1, 4, 2>(pr, a, stream) : launch_planewise_mixed<1, 4, 1>(pr, a, stream);
         }

@@ -120,16 +120,16 @@ def test_dequant_mfma_uniform(gpu, m, n, kernel):
 
 
 @pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
-@pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
+@pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "32,4", "32,2", "32,1", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
 def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape, kernel):
     """The kernel picks its workgroup shape (request tiles, row blocks) from m and the batch; small test
     matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles;
-    "0" is the single tile of 16 requests)."""
+    "0" is the tile of 16 requests, "32" that of 32)."""
     forced_shape(shape)
     layer = syn.make_layer(200, 1536, seed=(151, 0), signed=True)
     dl = gpu.DeviceLayer(layer)
     offsets = syn.make_offsets(3, 200, 1536, seed=(151, 1))
-    for batch in (3, 16, 64, 100, 257):
+    for batch in (3, 16, 32, 64, 100, 257):
         x = syn.make_x(batch, 1536, seed=(151, batch))
         for p in (2, 4):
             used, _ = gpu.check_gemv(dl, p, x, kernel)
@@ -204,7 +204,7 @@ def test_dequant_mfma_other_group_sizes(gpu, group, kernel):
 
 
 @pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
-@pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1"])
+@pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1", "32,2", "32,1"])
 def test_dequant_mfma_mixed(gpu, rows, forced_shape, kernel):
     """Per-request precision on the large-batch kernels (weights rebuilt per precision present, or the planes
     multiplied once and every request's own scales applied to the group sums): every workgroup shape, ragged
@@ -214,7 +214,7 @@ def test_dequant_mfma_mixed(gpu, rows, forced_shape, kernel):
     m, n = 150, 1536
     layer = syn.make_layer(m, n, seed=(154, 0), signed=True)
     dl = gpu.DeviceLayer(layer)
-    for batch in (5, 16, 64, 130):
+    for batch in (5, 16, 32, 64, 130):
         x = syn.make_x(batch, n, seed=(154, batch))
         p_req = syn.make_p_req(batch, 1, 4, seed=(154, batch))
         used, _ = gpu.check_mixed(dl, p_req, x, kernel)
@@ -316,7 +316,9 @@ def test_auto_dispatch_by_batch(gpu):
     assert used == "plane_mfma"
     used, _ = gpu.check_gemv(tall, 3, syn.make_x(9, 1024, seed=(172, 2)), "auto")
     assert used == "plane_f16"
-    used, _ = gpu.check_gemv(tall, 3, syn.make_x(17, 1024, seed=(172, 6)), "auto")
+    used, _ = gpu.check_gemv(tall, 3, syn.make_x(17, 1024, seed=(172, 6)), "auto")      # one tile of 32
+    assert used == "plane_f16"
+    used, _ = gpu.check_gemv(tall, 3, syn.make_x(33, 1024, seed=(172, 9)), "auto")
     assert used == "dequant_mfma"
     used, _ = gpu.check_gemv(tall, 2, syn.make_x(4, 1024, seed=(172, 4)), "auto")
     assert used == "plane_mfma"

@@ -790,26 +790,28 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     // compile-time number: inside, a step is one straight run of instructions.
     auto sweep = [&](auto ph_tag) {
     constexpr int PH = decltype(ph_tag)::value;
-    auto fetch_w = [&](AheadMixed &ah, int g) {
-#pragma unroll
-        for (int i = 0; i < kMaxP; ++i) {
-            if (i < PH) {
-                const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
-                ah.w[i] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);
-            }
+    // The fetches of a group in four parts (the step issues one per matrix sub-step, see dequant_mfma_kernel): part t
+    // brings plane t and the scale set of precision PH - t, the deepest set first.
+    auto fetch_part = [&](AheadMixed &ah, int g, int part) {
+        if (part < PH) {
+            const unsigned char *w_base = a.planes + (size_t)part * a.plane_stride + (uint32_t)g * 16;
+            ah.w[part] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);
         }
+        const int q = PH - part;
+        if (q >= 1 && (q == PH || has[q])) {
+            asm volatile("" : "+v"(s_lane));      // (keeps the widening of the offset next to the loads, see the step)
 #pragma unroll
-        for (int q = 1; q <= PH; ++q) {
-            if (q == PH || has[q]) {
-                asm volatile("" : "+v"(s_lane));      // (keeps the widening of the offset next to the loads, see the step)
-#pragma unroll
-                for (int i = 0; i < q; ++i) {
+            for (int i = 0; i < kMaxP; ++i)
+                if (i < q) {
                     const unsigned char *s_base = set_of(q) + (size_t)i * a.scale_plane_stride + scale_col(g);
                     ah.alpha[q * (q - 1) / 2 + i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
                 }
-                if (off_of(q)) ah.z[q - 1] = *reinterpret_cast<const _Float16 *>(off_of(q) + scale_col(g) + s_lane);
-            }
+            if (off_of(q)) ah.z[q - 1] = *reinterpret_cast<const _Float16 *>(off_of(q) + scale_col(g) + s_lane);
         }
+    };
+    auto fetch_w = [&](AheadMixed &ah, int g) {
+#pragma unroll
+        for (int part = 0; part < 4; ++part) fetch_part(ah, g, part);
     };
     auto stage_x_unit = [&](int g, int buf, int k) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
@@ -850,7 +852,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
                 z_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)(half_bits(cur.z[2]) | half_bits(cur.z[3]) << 16));
             }
             const bool more = g + TEAMS < a.ngroups;
-            if (more) fetch_w(nxt, g + TEAMS);
             const unsigned char *xa_cur = xa_lane + buf * kTile;
             uint32_t lo8[kMaxP], hi8[kMaxP];
 #pragma unroll
@@ -879,6 +880,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
                             }
                         }
                         if (more && pass == 0) {
+                            fetch_part(nxt, g + TEAMS, t);
 #pragma unroll
                             for (int k = 0; k < XU; ++k)
                                 if (k * 4 / XU == t) stage_x_unit(g + TEAMS, buf ^ 1, k);

@@ -98,8 +98,6 @@ struct DequantParams {
 template <int P, int XU>
 struct Ahead {
     uint32_t w[P];
-    _Float16 alpha[P];
-    _Float16 z;
 };
 
 // NT: 16-request tiles per workgroup (1, 4, 8 or 16); TEAMS: teams of waves (K split inside the workgroup); RW: waves per
@@ -110,8 +108,10 @@ struct Ahead {
 // That trades the P fused multiply-adds per weight for P times the matrix instructions, which the matrix pipe
 // has room for; the offset of the asymmetric scheme multiplies the group's plain activation sum, formed by
 // one more pass with an all-ones operand.
+// (The small-tile shapes leave LDS for several workgroups per CU: at least four waves per SIMD keeps the compiler
+// from spending the few registers that would forbid it.)
 template <int P, int NT, int TEAMS, int RW, bool PW = false>
-__global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantParams a)
+__global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(NT <= 2 ? 4 : 1))) void dequant_mfma_kernel(DequantParams a)
 {
     constexpr int kTeamThreads = 64 * RW;
     constexpr int XU = 4 * NT / RW;           // 16-byte units of an activation tile per thread of a team
@@ -149,10 +149,30 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     // that uses them (row l & 15, word l >> 4) by a lane permute.
     const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
     uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
-    // the scale group of (step g, word kq): g with 128 columns per group, g >> 1 with 256, 2g + (kq >> 1) with 64
-    uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
+    // Scales and offsets are fetched for FOUR of the team's steps at once: the four lanes of a row take the
+    // groups of the steps 4M .. 4M + 3 (eight bytes apart, one 64-byte sector), so a load instruction asks
+    // for sixteen lines once in four steps instead of every step; these requests, not the bytes, were up to a
+    // sixth of the kernel's time.  With groups of 64 columns a step has two scales, fetched as one dword.
+    const uint32_t s_row = frow * a.scale_row_stride;
     auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;      // byte index of the lane to take from
+    const int pull_row = 4 * n16 * 4;         // first of the four lanes that hold the scales of row n16
+    const uint32_t half_shift = a.gshift < 0 && kq >= 2 ? 16u : 0u;      // groups of 64: columns 64..127 of a step use the upper scale
+    uint32_t sc[P], zc = 0;                   // this lane's share of the scales in flight / in use (binary16 bits)
+    auto fetch_scales = [&](int block) {      // for the team's steps 4 block .. 4 block + 3
+        const int gj = min(team + TEAMS * (4 * block + (lane & 3)), a.ngroups - 1);
+        uint32_t off = s_row + scale_col(gj);
+        asm volatile("" : "+v"(off));
+        if (a.gshift < 0) {
+#pragma unroll
+            for (int i = 0; i < P; ++i) sc[i] = *reinterpret_cast<const uint32_t *>(a.scales + (size_t)i * a.scale_plane_stride + off);
+            if (a.has_offsets) zc = *reinterpret_cast<const uint32_t *>(a.offsets + off);
+        } else {
+#pragma unroll
+            for (int i = 0; i < P; ++i) sc[i] = *reinterpret_cast<const unsigned short *>(a.scales + (size_t)i * a.scale_plane_stride + off);
+            if (a.has_offsets) zc = *reinterpret_cast<const unsigned short *>(a.offsets + off);
+        }
+    };
     // staging: unit tid + kTeamThreads * k of the tile = request (unit >> 4), 16-byte part (unit & 15) of its 256 bytes
     // Staging straight into LDS: load instruction i of a tile (i = k * RW + wave) brings the 1 KiB of requests
     // 4i .. 4i+3; lane l delivers the 16 bytes that land at chunk l of that KiB, which is part
@@ -178,14 +198,10 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
         // wave-uniform 64-bit base plus 32-bit lane offset: an addressing mode of the load instruction
         const unsigned char *w_base = a.planes + (size_t)i * a.plane_stride + (uint32_t)g * 16;
         ah.w[i] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);
-        const unsigned char *s_base = a.scales + (size_t)i * a.scale_plane_stride + scale_col(g);
-        ah.alpha[i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
     };
-    auto fetch_offset = [&](Ahead<P, XU> &ah, int g) { ah.z = *reinterpret_cast<const _Float16 *>(a.offsets + scale_col(g) + s_lane); };
     auto fetch_w = [&](Ahead<P, XU> &ah, int g) {
 #pragma unroll
         for (int i = 0; i < P; ++i) fetch_plane(ah, g, i);
-        fetch_offset(ah, g);
     };
     auto stage_x_unit = [&](int g, int buf, int k) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
@@ -209,29 +225,33 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     // Group g, the team's next being g + TEAMS.  On entry `cur` holds the plane words and scales of group g
     // and the activation tile of the next group; the team's LDS tile `buf` holds the activations of group g.
     // Every wave of the workgroup passes the barrier of every step, with or without a group of its own.
-    auto step = [&](Ahead<P, XU> &cur, Ahead<P, XU> &nxt, int g, int buf) {
+    // `mine` counts the team's steps (g = team + TEAMS * mine).
+    auto step = [&](Ahead<P, XU> &cur, Ahead<P, XU> &nxt, int g, int mine, int buf) {
         if (g < a.ngroups) {
         // Everything fetched ahead is claimed here, while it is all that is outstanding: the wait is
         // then exact.  (Claimed after the next loads have been issued, it would cover those too.)
 #pragma unroll
-        for (int i = 0; i < P; ++i) asm volatile("" : "+v"(cur.w[i]), "+v"(cur.alpha[i]));
-        asm volatile("" : "+v"(cur.z));
+        for (int i = 0; i < P; ++i) asm volatile("" : "+v"(cur.w[i]), "+v"(sc[i]));
+        asm volatile("" : "+v"(zc));
         // The lane offsets are made new values in every step: hoisted out of the loop as 64-bit numbers they
         // cost a register pair and a 64-bit add per load; widened where they are used they ride in the load's
         // own addressing mode (scalar base + 32-bit lane offset).
-        asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+        asm volatile("" : "+v"(w_lane));
 #pragma unroll
         for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
-        const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.z));
+        const int pull_scale = pull_row + (mine & 3) * 4;       // the lane that fetched this step's scales of row n16
+        const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)zc) >> half_shift;
         const float z = a.has_offsets ? (float)__builtin_bit_cast(_Float16, (unsigned short)zb) : 0.f;
         uint32_t w[P];
         float alpha[P];
 #pragma unroll
         for (int i = 0; i < P; ++i) {
             w[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)cur.w[i]);
-            const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, cur.alpha[i]));
+            const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)sc[i]) >> half_shift;
             alpha[i] = (float)__builtin_bit_cast(_Float16, (unsigned short)ab);
         }
+        // the scales of the next four steps, once the last of these four has handed its own over
+        if ((mine & 3) == 3 && g + TEAMS < a.ngroups) fetch_scales((mine >> 2) + 1);
         // The loads for the team's next group are spread over the four matrix steps below: issued all at once
         // right after the barrier, by every wave of the workgroup, they queue up in the memory pipe while
         // no wave has arithmetic to do.  With three or four planes the plane words go two planes per
@@ -274,7 +294,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
                     if (more) {
                         const int slot = pass * 4 + t;
                         if (kSpreadPlanes) {
-                            if (slot == 0) fetch_offset(nxt, g + TEAMS);
 #pragma unroll
                             for (int i = 0; i < P; ++i)
                                 if (i / 2 == slot) fetch_plane(nxt, g + TEAMS, i);
@@ -340,7 +359,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
             for (int u = 0; u < UT; ++u) xa[u] = *reinterpret_cast<const v8h *>(xa_cur + u * (16 * kXRowBytes) + xa_off[t]);
             if (more) {
                 if (kSpreadPlanes) {
-                    if (t == 0) fetch_offset(nxt, g + TEAMS);
 #pragma unroll
                     for (int i = 0; i < P; ++i)
                         if (i / 2 == t) fetch_plane(nxt, g + TEAMS, i);
@@ -389,17 +407,20 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mfma_kernel(DequantPa
     };
 
     Ahead<P, XU> ah0, ah1;
+#pragma unroll
+    for (int i = 0; i < P; ++i) sc[i] = 0;
     if (team < a.ngroups) {
         stage_x(team, 0);
         fetch_w(ah0, team);
+        fetch_scales(0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();                            // table and first tiles complete
     const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
     for (int it = 0; it < npairs; ++it) {
         const int g = 2 * it * TEAMS + team;
-        step(ah0, ah1, g, 0);
-        step(ah1, ah0, g + TEAMS, 1);
+        step(ah0, ah1, g, 2 * it, 0);
+        step(ah1, ah0, g + TEAMS, 2 * it + 1, 1);
     }
 
     if constexpr (TEAMS > 1) {

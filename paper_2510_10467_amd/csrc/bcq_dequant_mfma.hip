@@ -807,32 +807,41 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     for (int u = 0; u < NT; ++u) acc[u] = v4f{0.f, 0.f, 0.f, 0.f};
     const v4f zero4 = v4f{0.f, 0.f, 0.f, 0.f};
 
+    uint32_t sc[10], zc[kMaxP];               // scales and offsets in flight / in use: binary16 bits, set q plane i at q (q - 1) / 2 + i
+#pragma unroll
+    for (int i = 0; i < 10; ++i) sc[i] = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxP; ++i) zc[i] = 0;
+
     // The sweep over the groups, with the number of planes the tile needs (its highest precision) as a
     // compile-time number: inside, a step is one straight run of instructions.
     auto sweep = [&](auto ph_tag) {
     constexpr int PH = decltype(ph_tag)::value;
-    // The fetches of a group in four parts (the step issues one per matrix sub-step, see dequant_mfma_kernel): part t
-    // brings plane t and the scale set of precision PH - t, the deepest set first.
+    // Plane t of a group is fetched at matrix sub-step t of the step before (see dequant_mfma_kernel).  The scale sets
+    // are fetched for four of the team's steps at once, as there: the four lanes of a row take the groups of the
+    // steps 4 block .. 4 block + 3; sets of precisions no request of the tile has are never fetched and stay zero.
     auto fetch_part = [&](AheadMixed &ah, int g, int part) {
         if (part < PH) {
             const unsigned char *w_base = a.planes + (size_t)part * a.plane_stride + (uint32_t)g * 16;
             ah.w[part] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);
         }
-        const int q = PH - part;
-        if (q >= 1 && (q == PH || has[q])) {
-            asm volatile("" : "+v"(s_lane));      // (keeps the widening of the offset next to the loads, see the step)
-#pragma unroll
-            for (int i = 0; i < kMaxP; ++i)
-                if (i < q) {
-                    const unsigned char *s_base = set_of(q) + (size_t)i * a.scale_plane_stride + scale_col(g);
-                    ah.alpha[q * (q - 1) / 2 + i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
-                }
-            if (off_of(q)) ah.z[q - 1] = *reinterpret_cast<const _Float16 *>(off_of(q) + scale_col(g) + s_lane);
-        }
     };
     auto fetch_w = [&](AheadMixed &ah, int g) {
 #pragma unroll
         for (int part = 0; part < 4; ++part) fetch_part(ah, g, part);
+    };
+    auto fetch_scales = [&](int block) {
+        const int gj = min(team + TEAMS * (4 * block + (lane & 3)), a.ngroups - 1);
+        uint32_t off = s_lane + scale_col(gj);
+#pragma unroll
+        for (int q = 1; q <= PH; ++q)
+            if (q == PH || has[q]) {
+                asm volatile("" : "+v"(off));     // (keeps the widening of the offset next to the loads, see the step)
+#pragma unroll
+                for (int i = 0; i < kMaxP; ++i)
+                    if (i < q) sc[q * (q - 1) / 2 + i] = *reinterpret_cast<const unsigned short *>(set_of(q) + (size_t)i * a.scale_plane_stride + off);
+                if (off_of(q)) zc[q - 1] = *reinterpret_cast<const unsigned short *>(off_of(q) + off);
+            }
     };
     auto stage_x_unit = [&](int g, int buf, int k) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
@@ -840,19 +849,19 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
                                          (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
     };
 
-    auto step = [&](AheadMixed &cur, AheadMixed &nxt, int g, int buf) {
+    auto step = [&](AheadMixed &cur, AheadMixed &nxt, int g, int mine, int buf) {
         if (g < a.ngroups) {
 #pragma unroll
             for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.w[i]));
 #pragma unroll
-            for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(cur.alpha[i]));
+            for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(sc[i]));
 #pragma unroll
-            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.z[i]));
-            asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(zc[i]));
+            asm volatile("" : "+v"(w_lane));
+            const int pull_scale = 4 * n16 * 4 + (mine & 3) * 4;    // the lane that fetched this step's scales of row n16
 #pragma unroll
             for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
             // (scales of a precision no request of the tile has were never fetched: they are still zero)
-            auto half_bits = [](_Float16 v) { return (uint32_t)__builtin_bit_cast(unsigned short, v); };
             auto own_value = [](uint32_t hi, uint32_t lo, uint32_t sel) {
                 return (float)__builtin_bit_cast(_Float16, (unsigned short)__builtin_amdgcn_perm(hi, lo, sel));
             };
@@ -862,16 +871,18 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
             for (int i = 0; i < kMaxP; ++i) {
                 // plane i belongs to the sets q > i
-                const uint32_t lo = (i < 1 ? half_bits(cur.alpha[0]) : 0u) | (i < 2 ? half_bits(cur.alpha[1 + i]) << 16 : 0u);
-                const uint32_t hi = (i < 3 ? half_bits(cur.alpha[3 + i]) : 0u) | (half_bits(cur.alpha[6 + i]) << 16);
-                s_lo[i] = i < 2 ? (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)lo) : 0u;
-                s_hi[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)hi);
+                const uint32_t lo = (i < 1 ? sc[0] : 0u) | (i < 2 ? sc[1 + i] << 16 : 0u);
+                const uint32_t hi = (i < 3 ? sc[3 + i] : 0u) | (sc[6 + i] << 16);
+                s_lo[i] = i < 2 ? (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)lo) : 0u;
+                s_hi[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)hi);
             }
             uint32_t z_lo = 0, z_hi = 0;
             if (any_offset) {
-                z_lo = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)(half_bits(cur.z[0]) | half_bits(cur.z[1]) << 16));
-                z_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)(half_bits(cur.z[2]) | half_bits(cur.z[3]) << 16));
+                z_lo = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)(zc[0] | zc[1] << 16));
+                z_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)(zc[2] | zc[3] << 16));
             }
+            // the scale sets of the next four steps, once the last of these four has handed its own over
+            if ((mine & 3) == 3 && g + TEAMS < a.ngroups) fetch_scales((mine >> 2) + 1);
             const bool more = g + TEAMS < a.ngroups;
             const unsigned char *xa_cur = xa_lane + buf * kTile;
             uint32_t lo8[kMaxP], hi8[kMaxP];
@@ -952,14 +963,15 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
         for (int k = 0; k < XU; ++k) stage_x_unit(team, 0, k);
         fetch_w(ah0, team);
+        fetch_scales(0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
     for (int it = 0; it < npairs; ++it) {
         const int g = 2 * it * TEAMS + team;
-        step(ah0, ah1, g, 0);
-        step(ah1, ah0, g + TEAMS, 1);
+        step(ah0, ah1, g, 2 * it, 0);
+        step(ah1, ah0, g + TEAMS, 2 * it + 1, 1);
     }
     };
     switch (p_hi) {       // the same in every wave of the workgroup: all of them take the same barriers

@@ -460,8 +460,6 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 // [1, p_max] is clamped; a request whose precision has no scale set yields zeros.
 struct AheadMixed {
     uint32_t w[kMaxP];
-    _Float16 alpha[10];                     // set q, plane i at q (q - 1) / 2 + i
-    _Float16 z[kMaxP];
 };
 
 template <int TEAMS, int RW>
@@ -515,7 +513,15 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 
     const uint32_t frow = min(row0 + (lane >> 2), a.m - 1);
     uint32_t w_lane = frow * a.row_stride + (lane & 3) * 4;
-    uint32_t s_lane = frow * a.scale_row_stride + (a.gshift < 0 ? ((lane & 3) >> 1) * 2 : 0);
+    const uint32_t s_row = frow * a.scale_row_stride;
+    const uint32_t half_shift = a.gshift < 0 && kq >= 2 ? 16u : 0u;     // groups of 64: columns 64..127 of a step use the upper scale
+    // scales and offsets in flight / in use (binary16 bits, two of them with groups of 64), fetched for four of the
+    // team's steps at once as in dequant_mfma_kernel; set q plane i at q (q - 1) / 2 + i
+    uint32_t sc[10], zc[kMaxP];
+#pragma unroll
+    for (int i = 0; i < 10; ++i) sc[i] = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxP; ++i) zc[i] = 0;
     auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;
     // staging straight into LDS and the XOR placement of the parts: as in dequant_mfma_kernel
@@ -539,15 +545,23 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
                 ah.w[i] = *reinterpret_cast<const uint32_t *>(w_base + w_lane);     // cached, as in dequant_mfma_kernel
             }
         }
+    };
+    auto fetch_scales = [&](int block) {      // for the team's steps 4 block .. 4 block + 3
+        const int gj = min(team + TEAMS * (4 * block + (lane & 3)), a.ngroups - 1);
+        uint32_t off = s_row + scale_col(gj);
 #pragma unroll
         for (int q = 1; q <= kMaxP; ++q) {
             if (has[q]) {
+                asm volatile("" : "+v"(off));
+                if (a.gshift < 0) {
 #pragma unroll
-                for (int i = 0; i < q; ++i) {
-                    const unsigned char *s_base = set_of(q) + (size_t)i * a.scale_plane_stride + scale_col(g);
-                    ah.alpha[q * (q - 1) / 2 + i] = *reinterpret_cast<const _Float16 *>(s_base + s_lane);
+                    for (int i = 0; i < q; ++i) sc[q * (q - 1) / 2 + i] = *reinterpret_cast<const uint32_t *>(set_of(q) + (size_t)i * a.scale_plane_stride + off);
+                    if (off_of(q)) zc[q - 1] = *reinterpret_cast<const uint32_t *>(off_of(q) + off);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < q; ++i) sc[q * (q - 1) / 2 + i] = *reinterpret_cast<const unsigned short *>(set_of(q) + (size_t)i * a.scale_plane_stride + off);
+                    if (off_of(q)) zc[q - 1] = *reinterpret_cast<const unsigned short *>(off_of(q) + off);
                 }
-                if (off_of(q)) ah.z[q - 1] = *reinterpret_cast<const _Float16 *>(off_of(q) + scale_col(g) + s_lane);
             }
         }
     };
@@ -570,20 +584,21 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc[q][u] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    auto step = [&](AheadMixed &cur, AheadMixed &nxt, int g, int buf) {
+    auto step = [&](AheadMixed &cur, AheadMixed &nxt, int g, int mine, int buf) {
         if (g < a.ngroups) {
 #pragma unroll
             for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.w[i]));
 #pragma unroll
-            for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(cur.alpha[i]));
+            for (int i = 0; i < 10; ++i) asm volatile("" : "+v"(sc[i]));
 #pragma unroll
-            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(cur.z[i]));
+            for (int i = 0; i < kMaxP; ++i) asm volatile("" : "+v"(zc[i]));
             // lane offsets made new in every step, table look-ups by byte pick: as in dequant_mfma_kernel
-            asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+            asm volatile("" : "+v"(w_lane));
+            const int pull_scale = 4 * n16 * 4 + (mine & 3) * 4;    // the lane that fetched this step's scales of row n16
 #pragma unroll
             for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
-            auto handed = [&](_Float16 v) {
-                const uint32_t bits = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)__builtin_bit_cast(unsigned short, v));
+            auto handed = [&](uint32_t v) {
+                const uint32_t bits = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)v) >> half_shift;
                 return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
             };
             uint32_t w[kMaxP];
@@ -595,8 +610,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
                 z[q - 1] = 0.f;
                 if (has[q]) {
 #pragma unroll
-                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = handed(cur.alpha[q * (q - 1) / 2 + i]);
-                    if (off_of(q)) z[q - 1] = handed(cur.z[q - 1]);
+                    for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = handed(sc[q * (q - 1) / 2 + i]);
+                    if (off_of(q)) z[q - 1] = handed(zc[q - 1]);
                 } else {
 #pragma unroll
                     for (int i = 0; i < q; ++i) alpha[q * (q - 1) / 2 + i] = 0.f;
@@ -604,6 +619,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
             }
             const bool more = g + TEAMS < a.ngroups;
             if (more) fetch_w(nxt, g + TEAMS);
+            if ((mine & 3) == 3 && more) fetch_scales((mine >> 2) + 1);
             const unsigned char *xa_cur = xa_lane + buf * kTile;
             uint32_t lo8[kMaxP], hi8[kMaxP];
 #pragma unroll
@@ -664,14 +680,15 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
     if (team < a.ngroups) {
         stage_x(team, 0);
         fetch_w(ah0, team);
+        fetch_scales(0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
     for (int it = 0; it < npairs; ++it) {
         const int g = 2 * it * TEAMS + team;
-        step(ah0, ah1, g, 0);
-        step(ah1, ah0, g + TEAMS, 1);
+        step(ah0, ah1, g, 2 * it, 0);
+        step(ah1, ah0, g + TEAMS, 2 * it + 1, 1);
     }
 
     if constexpr (TEAMS > 1) {

@@ -93,14 +93,14 @@ struct DequantParams {
     int p_max;
 };
 
-// What a thread fetches ahead: plane words and scales of its row for one group, and its share of the
-// activation tile of the group after (XU units of 16 bytes).
+// What a thread fetches one group ahead into registers: the plane words of its row (its share of the next
+// activation tile goes straight to LDS, the scales come in blocks of four steps).
 template <int P, int XU>
 struct Ahead {
     uint32_t w[P];
 };
 
-// NT: 16-request tiles per workgroup (1, 4, 8 or 16); TEAMS: teams of waves (K split inside the workgroup); RW: waves per
+// NT: 16-request tiles per workgroup (1, 2, 4, 8 or 16); TEAMS: teams of waves (K split inside the workgroup); RW: waves per
 // team = 16-row blocks per workgroup.
 // PW (plane-wise): instead of rebuilding W_p, the +-1.0 values from the table are themselves the matrix operand:
 //   tmp_i = B_i x over the group's 128 columns (fp16 matrix instructions, exact products, fp32 sums), then
@@ -458,7 +458,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 // accumulator set of its own (the matrix pipe has room to spare); at the end every request keeps the
 // result of its own precision.  Requests are not sorted and nothing is masked.  A precision outside
 // [1, p_max] is clamped; a request whose precision has no scale set yields zeros.
-struct AheadMixed {
+struct AheadMixed {                         // the plane words fetched one group ahead
     uint32_t w[kMaxP];
 };
 

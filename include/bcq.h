@@ -84,7 +84,9 @@ int bcq_select_kernel(int variant);
  * process (benchmarks and tests only; the library otherwise picks it from m and
  * the batch): `request_tiles` tiles of 64 requests and `row_blocks` blocks of 16
  * rows per workgroup, one of (1,4) (1,2) (1,1) (2,4) (2,2) (4,4), or (0,4) (0,2)
- * (0,1) for a single tile of 16 requests and (32,4) (32,2) (32,1) for one of 32;
+ * (0,1) for a single tile of 16 requests and (32,4) (32,2) (32,1) for one of 32,
+ * (0,8) and (32,8) for those tiles with one row block whose columns are split
+ * over eight teams of waves instead of four;
  * per-request precision uses the row blocks and whether the tile has 32
  * requests only.  (0, 0) restores the automatic choice.
  * Returns BCQ_OK, or BCQ_ERR_VARIANT for any other pair.  Host call, not

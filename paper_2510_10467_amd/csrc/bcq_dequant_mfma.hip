@@ -1086,6 +1086,9 @@ struct WgShape {
 // such tiles never beat one 64-request tile).
 constexpr WgShape kShapes[] = {{1, 4, 0.51f, 0.32f, 0.78f, 0.39f}, {1, 2, 0.36f, 0.26f, 0.34f, 0.19f}, {1, 1, 0.31f, 0.28f, 0.175f, 0.11f},
                                {2, 4, 0.62f, 0.40f, 0.89f, 0.48f}, {2, 2, 0.41f, 0.30f, 0.44f, 0.25f}, {2, 1, 0.37f, 0.37f, 0.26f, 0.175f},
+                               // row-block code 8: one row block with the K range over EIGHT teams, for matrices of few row
+                               // blocks and long rows (4096x14336 at 16 requests: 30 -> 20 us)
+                               {1, 8, 0.25f, 0.22f, 0.172f, 0.115f}, {2, 8, 0.30f, 0.29f, 0.30f, 0.28f},
                                {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
                                {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
 
@@ -1096,7 +1099,8 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
     float best = 0.f;
     for (const WgShape &c : kShapes) {
         if (c.nt <= 2 && a.batch > 16 * c.nt) continue;
-        const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * (float)((a.batch + 16 * c.nt - 1) / (16 * c.nt));
+        const int blocks = c.rw == 8 ? 1 : c.rw;        // (code 8: one row block, eight teams)
+        const float wgs = (float)((a.m + 16 * blocks - 1) / (16 * blocks)) * (float)((a.batch + 16 * c.nt - 1) / (16 * c.nt));
         const float one = P >= 3 ? c.us_p4 : c.us_p2, many = P >= 3 ? c.many_p4 : c.many_p2;
         float cost = one;
         if (many > 0.f) cost = wgs / 256.f * many > one ? wgs / 256.f * many : one;
@@ -1112,6 +1116,8 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
         rw = g_forced_rw;
     }
     switch (nt * 10 + rw) {
+    case 18: return launch_one<P, 1, 8, 1, PW>(pr, a, stream);      // (row-block code 8: one block, the K range over eight teams)
+    case 28: return launch_one<P, 2, 8, 1, PW>(pr, a, stream);
     case 14: return launch_one<P, 1, 4, 4, PW>(pr, a, stream);
     case 12: return launch_one<P, 1, 4, 2, PW>(pr, a, stream);
     case 11: return launch_one<P, 1, 4, 1, PW>(pr, a, stream);
@@ -1140,8 +1146,8 @@ bool dequant_mfma_force_shape(int request_tiles, int row_blocks)
     const int nt = request_tiles == 0 ? 1 : request_tiles == 32 ? 2 : 4 * request_tiles;      // 32: a tile of 32 requests
     const int key = nt * 10 + row_blocks;
     const bool known = key == 14 || key == 12 || key == 11 || key == 24 || key == 22 || key == 21 || key == 44 || key == 42 || key == 41 ||
-                       key == 84 || key == 82 || key == 164;
-    if (!known || request_tiles < 0 || (row_blocks != 1 && row_blocks != 2 && row_blocks != 4)) return false;
+                       key == 84 || key == 82 || key == 164 || key == 18 || key == 28;
+    if (!known || request_tiles < 0 || (row_blocks != 1 && row_blocks != 2 && row_blocks != 4 && row_blocks != 8)) return false;
     g_forced_nt = nt;
     g_forced_rw = row_blocks;
     return true;
@@ -1187,7 +1193,8 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
             float best16 = 0.f;
             for (const WgShape &c : kShapes) {
                 if (c.nt != 1) continue;
-                const float wgs = (float)((a.m + 16 * c.rw - 1) / (16 * c.rw)) * tiles16;
+                const int blocks = c.rw == 8 ? 1 : c.rw;        // (code 8: one row block, eight teams)
+                const float wgs = (float)((a.m + 16 * blocks - 1) / (16 * blocks)) * tiles16;
                 const float cost = wgs / 256.f * c.many_p4 > c.us_p4 ? wgs / 256.f * c.many_p4 : c.us_p4;
                 if (best16 == 0.f || cost < best16) {
                     best16 = cost;
@@ -1198,14 +1205,16 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
             // beyond 16 requests tiles of 32 (16 rows per workgroup, 32 on the tallest matrices): 14336x4096 at 32 requests
             // 42 -> 33 us
             bool pairs = a.batch > 16;
-            if (pairs) rw16 = a.m >= 16384 ? 2 : 1;
+            if (pairs) rw16 = a.m >= 16384 ? 2 : a.m * ((a.batch + 31) / 32) <= 4096 ? 8 : 1;     // eight teams while the grid is small
             if (g_forced_nt > 0) {
                 rw16 = g_forced_rw;
                 pairs = g_forced_nt == 2;
             }
             if (pairs)      // (with 64 rows per workgroup such a tile would not fit the registers of sixteen waves)
-                return rw16 >= 2 ? launch_planewise_mixed<2, 4, 2>(pr, a, stream) : launch_planewise_mixed<2, 4, 1>(pr, a, stream);
-            return rw16 == 4 ? launch_planewise_mixed<1, 4, 4>(pr, a, stream)
+                return rw16 == 8 ? launch_planewise_mixed<2, 8, 1>(pr, a, stream)
+                     : rw16 >= 2 ? launch_planewise_mixed<2, 4, 2>(pr, a, stream) : launch_planewise_mixed<2, 4, 1>(pr, a, stream);
+            return rw16 == 8 ? launch_planewise_mixed<1, 8, 1>(pr, a, stream)
+                 : rw16 == 4 ? launch_planewise_mixed<1, 4, 4>(pr, a, stream)
                  : rw16 == 2 ? launch_planewise_mixed<1, 4, 2>(pr, a, stream) : launch_planewise_mixed<1, 4, 1>(pr, a, stream);
         }
         // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured with three

@@ -120,11 +120,11 @@ def test_dequant_mfma_uniform(gpu, m, n, kernel):
 
 
 @pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
-@pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "32,4", "32,2", "32,1", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
+@pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "0,8", "32,4", "32,2", "32,1", "32,8", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
 def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape, kernel):
     """The kernel picks its workgroup shape (request tiles, row blocks) from m and the batch; small test
     matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles;
-    "0" is the tile of 16 requests, "32" that of 32)."""
+    "0" is the tile of 16 requests, "32" that of 32; row-block code 8 is one row block with eight teams)."""
     forced_shape(shape)
     layer = syn.make_layer(200, 1536, seed=(151, 0), signed=True)
     dl = gpu.DeviceLayer(layer)
@@ -204,7 +204,7 @@ def test_dequant_mfma_other_group_sizes(gpu, group, kernel):
 
 
 @pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
-@pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1", "32,2", "32,1"])
+@pytest.mark.parametrize("rows", ["1,4", "1,2", "1,1", "0,8", "32,2", "32,1", "32,8"])
 def test_dequant_mfma_mixed(gpu, rows, forced_shape, kernel):
     """Per-request precision on the large-batch kernels (weights rebuilt per precision present, or the planes
     multiplied once and every request's own scales applied to the group sums): every workgroup shape, ragged

@@ -224,7 +224,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 
     // Group g, the team's next being g + TEAMS.  On entry `cur` holds the plane words and scales of group g
     // and the activation tile of the next group; the team's LDS tile `buf` holds the activations of group g.
-    // Every wave of the workgroup passes the barrier of every step, with or without a group of its own.
+    // Every wave of the workgroup passes the barrier of every step (if there is one), with or without a group of its own.
     // `mine` counts the team's steps (g = team + TEAMS * mine).
     auto step = [&](Ahead<P, XU> &cur, Ahead<P, XU> &nxt, int g, int mine, int buf) {
         if (g < a.ngroups) {
@@ -403,7 +403,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
         }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
-        __syncthreads();                        // tile `buf` free, the other tile complete
+        // tile `buf` free, the other tile complete.  A team of ONE wave stages and reads its tiles itself: no barrier,
+        // and the waves of the workgroup drift apart, which lets one compute while another waits.
+        if constexpr (RW > 1) __syncthreads();
     };
 
     Ahead<P, XU> ah0, ah1;
@@ -424,6 +426,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     }
 
     if constexpr (TEAMS > 1) {
+        // (teams of one wave run without step barriers: all of them must have left their tiles before these are reused)
+        if constexpr (RW == 1) __syncthreads();
         // the other teams hand their accumulators over through the (now free) activation tiles
         v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
         if (team > 0) {
@@ -673,7 +677,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
-        __syncthreads();
+        if constexpr (RW > 1) __syncthreads();  // (a team of one wave owns its tiles: see dequant_mfma_kernel)
     };
 
     AheadMixed ah0{}, ah1{};
@@ -692,6 +696,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_mixed_kernel(DequantP
     }
 
     if constexpr (TEAMS > 1) {
+        // (teams of one wave run without step barriers: all of them must have left their tiles before these are reused)
+        if constexpr (RW == 1) __syncthreads();
         v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
         if (team > 0) {
 #pragma unroll
@@ -972,7 +978,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
-        __syncthreads();
+        if constexpr (RW > 1) __syncthreads();  // (a team of one wave owns its tiles: see dequant_mfma_kernel)
     };
 
     AheadMixed ah0{}, ah1{};
@@ -1000,6 +1006,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     }
 
     if constexpr (TEAMS > 1) {
+        // (teams of one wave run without step barriers: all of them must have left their tiles before these are reused)
+        if constexpr (RW == 1) __syncthreads();
         v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
         if (team > 0) {
 #pragma unroll

@@ -5,6 +5,8 @@
 //   planewise_mixed_kernel   per-request precision in tiles of 16 requests: one pass over the planes, each request's
 //                            own scales applied to the group sums
 //   dequant_mixed_kernel     per-request precision at 64 requests per workgroup: W_q rebuilt once per precision present
+//   dequant_mfma_kernel with BYCLASS = true: per-request precision beyond 64 requests, one launch per precision, each
+//                            on the requests of that precision picked out of the batch by rank
 //
 // Large-batch kernel: dequantise W_p = sum_i alpha_i B_i tile by tile (Fig. 1(b): p-bit inference
 // reconstructs the weights from the first p planes and the scale set of precision p) and feed the
@@ -57,6 +59,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxP = 4;
+constexpr int kClassFrom = 64;              // per-request precision: beyond this many requests one launch per precision
 int g_forced_nt = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2;         // LDS row of one request's 128 activations; its sixteen parts sit XOR-permuted
@@ -110,7 +113,12 @@ struct Ahead {
 // one more pass with an all-ones operand.
 // (The small-tile shapes leave LDS for several workgroups per CU: at least four waves per SIMD keeps the compiler
 // from spending the few registers that would forbid it.)
-template <int P, int NT, int TEAMS, int RW, bool PW = false>
+// BYCLASS (per-request precision at large batch): the launch serves the requests whose precision is P, and the
+//   workgroup's 16 NT requests are those of rank b0 .. b0 + 16 NT - 1 among them, in the order of the batch; every
+//   wave ranks the batch itself (ballots over p_req, no memory beyond the inputs), the first one leaves the request
+//   numbers in LDS.  A workgroup whose ranks nobody holds returns at once: the grid is laid out for the case that
+//   every request has precision P.
+template <int P, int NT, int TEAMS, int RW, bool PW = false, bool BYCLASS = false>
 __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(NT <= 2 ? 4 : 1))) void dequant_mfma_kernel(DequantParams a)
 {
     constexpr int kTeamThreads = 64 * RW;
@@ -129,7 +137,38 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
     const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
-    const int b0 = blockIdx.y * (16 * NT);    // first request of the workgroup
+    const int b0 = blockIdx.y * (16 * NT);    // first request of the workgroup (BYCLASS: first rank)
+
+    int nreq = a.batch - b0;                  // requests from b0 on (may be more than the workgroup's 16 NT)
+    const uint32_t *req_of = reinterpret_cast<const uint32_t *>(lds + lds_bytes(NT, TEAMS));
+    if constexpr (BYCLASS) {
+        // Sixteen independent loads at a time (1024 requests), so that a batch costs one memory latency, not one
+        // per 64 requests.  `seen` = requests of precision P so far: the same number in every wave.
+        int seen = 0;
+        for (int blk = 0; blk < a.batch && seen < b0 + 16 * NT; blk += 1024) {
+            int pv[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int b = blk + 64 * j + lane;
+                pv[j] = b < a.batch ? a.p_req[b] : 0;
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int b = blk + 64 * j + lane;
+                const int pc = pv[j] < 1 ? 1 : (pv[j] > a.p_max ? a.p_max : pv[j]);
+                const bool is = b < a.batch && pc == P;
+                const unsigned long long mask = __ballot(is);
+                const int rank = seen + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                if (is && rank >= b0 && rank < b0 + 16 * NT && threadIdx.x < 64)
+                    reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, TEAMS))[rank - b0] = (uint32_t)b;
+                seen += __popcll(mask);
+            }
+        }
+        nreq = seen - b0;
+        if (nreq <= 0) return;                // (every wave of the workgroup: none has reached a barrier yet)
+        if (nreq > 16 * NT) nreq = 16 * NT;
+        __syncthreads();
+    }
 
     // table: nibble -> four binary16 values, +1.0 where the bit is set, -1.0 where it is clear
     if (threadIdx.x < 16) {
@@ -183,7 +222,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     for (int k = 0; k < XU; ++k) {
         const int req = 4 * (k * RW + wave) + (lane >> 4);
         const int part = (lane & 15) ^ (req & 15);
-        xs_src[k] = (uint32_t)min(b0 + req, a.batch - 1) * a.x_stride + part * 16;
+        const uint32_t source = BYCLASS ? req_of[min(req, nreq - 1)] : (uint32_t)min(b0 + req, a.batch - 1);
+        xs_src[k] = source * a.x_stride + part * 16;
     }
     // A operand of request tile u, step t: request 16u + n16, part 4kq + t
     const unsigned char *xa_lane = xt0 + n16 * kXRowBytes;
@@ -449,8 +489,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
         for (int u = 0; u < NT; ++u)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int b = b0 + 16 * u + 4 * kq + i;
-                if (b < a.batch) a.y[(size_t)b * a.m + row] = (_Float16)acc[u][i];
+                const int r = 16 * u + 4 * kq + i;
+                if (r < nreq) a.y[(size_t)(BYCLASS ? req_of[r] : (uint32_t)(b0 + r)) * a.m + row] = (_Float16)acc[u][i];
             }
     }
 }
@@ -1061,19 +1101,19 @@ hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t 
     return hipGetLastError();
 }
 
-template <int P, int NT, int TEAMS, int RW, bool PW>
+template <int P, int NT, int TEAMS, int RW, bool PW, bool BYCLASS = false>
 hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
     static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
-    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW>;
-    if (lds_bytes(NT, TEAMS) > 64 * 1024) {
+    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW, BYCLASS>;
+    constexpr int kLds = lds_bytes(NT, TEAMS) + (BYCLASS ? 16 * NT * 4 : 0);       // (BYCLASS: the request numbers behind the tiles)
+    if (kLds > 64 * 1024) {
         // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           lds_bytes(NT, TEAMS));
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
     }
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
-    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, TEAMS), stream, pr);
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), kLds, stream, pr);
     return hipGetLastError();
 }
 
@@ -1100,16 +1140,16 @@ constexpr WgShape kShapes[] = {{1, 4, 0.51f, 0.32f, 0.78f, 0.39f}, {1, 2, 0.36f,
                                {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
                                {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
 
-template <int P, bool PW>
-hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
+// the cheapest shape for `batch` requests at precision p, among the shapes of at least min_nt tiles
+void cheapest_shape(int p, int64_t m, int batch, int min_nt, int &nt, int &rw)
 {
-    int nt = 4, rw = 4;
+    nt = rw = 4;
     float best = 0.f;
     for (const WgShape &c : kShapes) {
-        if (c.nt <= 2 && a.batch > 16 * c.nt) continue;
+        if (c.nt < min_nt || (c.nt <= 2 && batch > 16 * c.nt)) continue;
         const int blocks = c.rw == 8 ? 1 : c.rw;        // (code 8: one row block, eight teams)
-        const float wgs = (float)((a.m + 16 * blocks - 1) / (16 * blocks)) * (float)((a.batch + 16 * c.nt - 1) / (16 * c.nt));
-        const float one = P >= 3 ? c.us_p4 : c.us_p2, many = P >= 3 ? c.many_p4 : c.many_p2;
+        const float wgs = (float)((m + 16 * blocks - 1) / (16 * blocks)) * (float)((batch + 16 * c.nt - 1) / (16 * c.nt));
+        const float one = p >= 3 ? c.us_p4 : c.us_p2, many = p >= 3 ? c.many_p4 : c.many_p2;
         float cost = one;
         if (many > 0.f) cost = wgs / 256.f * many > one ? wgs / 256.f * many : one;
         else if (wgs > 256.f) cost = __builtin_ceilf(wgs / 256.f) * one;
@@ -1119,6 +1159,44 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
             rw = c.rw;
         }
     }
+}
+
+// One precision of a batch with per-request precision: the uniform kernel on the requests of precision P.  How many
+// they are only the GPU knows; the shape is chosen for `expected` of them and the grid for all of the batch.
+template <int P>
+hipError_t launch_class(const DequantParams &pr, const GemmArgs &a, int expected, hipStream_t stream)
+{
+    int nt, rw;
+    cheapest_shape(P, a.m, expected, 4, nt, rw);
+    if (g_forced_nt >= 4) {
+        nt = g_forced_nt;
+        rw = g_forced_rw;
+    }
+    switch (nt * 10 + rw) {
+    case 44: return launch_one<P, 4, 4, 4, false, true>(pr, a, stream);
+    case 42: return launch_one<P, 4, 4, 2, false, true>(pr, a, stream);
+    case 41: return launch_one<P, 4, 4, 1, false, true>(pr, a, stream);
+    case 84: return launch_one<P, 8, 2, 4, false, true>(pr, a, stream);
+    case 82: return launch_one<P, 8, 2, 2, false, true>(pr, a, stream);
+    case 164: return launch_one<P, 16, 1, 4, false, true>(pr, a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// zeros for the requests whose precision has no scale set (bit q of `unserved`): one workgroup per request
+__global__ __launch_bounds__(256) void zero_unserved_kernel(const int32_t *p_req, int p_max, uint32_t unserved, _Float16 *y, uint32_t m)
+{
+    const int pv = p_req[blockIdx.x];
+    const int pc = pv < 1 ? 1 : (pv > p_max ? p_max : pv);
+    if (!((unserved >> pc) & 1u)) return;
+    for (uint32_t r = threadIdx.x; r < m; r += 256) y[(size_t)blockIdx.x * m + r] = (_Float16)0.f;
+}
+
+template <int P, bool PW>
+hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
+{
+    int nt, rw;
+    cheapest_shape(P, a.m, a.batch, 1, nt, rw);
     if (g_forced_nt > 0) {
         nt = g_forced_nt;
         rw = g_forced_rw;
@@ -1224,6 +1302,36 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
             return rw16 == 8 ? launch_planewise_mixed<1, 8, 1>(pr, a, stream)
                  : rw16 == 4 ? launch_planewise_mixed<1, 4, 4>(pr, a, stream)
                  : rw16 == 2 ? launch_planewise_mixed<1, 4, 2>(pr, a, stream) : launch_planewise_mixed<1, 4, 1>(pr, a, stream);
+        }
+        if (a.batch > kClassFrom && (g_forced_nt == 0 || g_forced_nt >= 4)) {
+            // Beyond 64 requests: one launch of the uniform kernel per precision, each on the requests of that
+            // precision wherever they sit in the batch (BYCLASS).  A weight is then rebuilt once per precision
+            // and up to 256 requests, at the cost of that precision alone, instead of once per 64 requests at
+            // the cost of all precisions present.
+            int nsets = 0;
+            uint32_t unserved = 0;
+            for (int q = 1; q <= a.p_max; ++q) {
+                if (a.scales[q]) ++nsets;
+                else unserved |= 1u << q;
+            }
+            if (unserved) {
+                hipLaunchKernelGGL(zero_unserved_kernel, dim3((unsigned)a.batch), dim3(256), 0, stream, a.p_req, a.p_max, unserved, a.y, pr.m);
+                hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return e;
+            }
+            // an even split plus a quarter: a precision that draws a few requests more than its share should not
+            // need a second, nearly empty tile
+            const int expected = nsets ? (a.batch * 5 + 4 * nsets - 1) / (4 * nsets) : a.batch;
+            for (int q = 1; q <= a.p_max; ++q) {
+                if (!a.scales[q]) continue;
+                pr.scales = pr.scale_sets[q];
+                pr.has_offsets = pr.offset_sets[q] != nullptr;
+                pr.offsets = pr.has_offsets ? pr.offset_sets[q] : pr.scales;
+                hipError_t e = q == 1 ? launch_class<1>(pr, a, expected, stream) : q == 2 ? launch_class<2>(pr, a, expected, stream)
+                             : q == 3 ? launch_class<3>(pr, a, expected, stream) : launch_class<4>(pr, a, expected, stream);
+                if (e != hipSuccess) return e;
+            }
+            return hipSuccess;
         }
         // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured with three
         // precisions present: 1.8, 1.43 and 0.94 microseconds per workgroup and group of columns; two of the

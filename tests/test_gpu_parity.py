@@ -258,6 +258,46 @@ def test_dequant_mfma_mixed_clamps_and_missing_sets(gpu, kernel):
     assert torch.all(y_some[is3] == 0) and torch.equal(y_some[~is3], y_ok[~is3])
 
 
+@pytest.mark.parametrize("shape", ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4", None])
+def test_per_request_precision_one_launch_per_precision(gpu, shape, forced_shape):
+    """Beyond 64 requests `dequant_mfma` serves a batch with per-request precision by one launch of the uniform
+    kernel per precision, each workgroup picking the requests of that precision out of the batch by rank:
+    every workgroup shape of that path, ragged last tiles, precisions in runs and interleaved, a precision
+    nobody has, everybody at one precision, more than 1024 requests (the ranking goes in blocks of 1024),
+    clamped precisions, a precision without a scale set (zeros), offsets for some precisions only."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    if shape:
+        forced_shape(shape)
+    m, n = 150, 1536
+    dl = gpu.DeviceLayer(syn.make_layer(m, n, seed=(158, 0), signed=True))
+    for batch in (65, 130, 300, 1100):
+        x = syn.make_x(batch, n, seed=(158, batch))
+        drawn = syn.make_p_req(batch, 1, 4, seed=(158, batch))
+        cases = [drawn, np.sort(drawn), np.full(batch, 2, dtype=np.int32), np.where(np.arange(batch) % 3 == 0, 4, 3).astype(np.int32)]
+        for p_req in cases[:4 if batch <= 300 else 1]:
+            used, _ = gpu.check_mixed(dl, p_req.astype(np.int32), x, "dequant_mfma")
+            assert used == "dequant_mfma"
+    zs = {p: syn.make_offsets(p, m, n, seed=(158, p)) for p in (1, 3)}
+    x = syn.make_x(200, n, seed=(158, 200))
+    gpu.check_mixed(dl, syn.make_p_req(200, 1, 4, seed=(158, 201)), x, "dequant_mfma", offsets_by_p=zs)
+    wild = np.array([0, -3, 9, 2, 3] * 40, dtype=np.int32)                # clamped to 1, 1, 4, 2, 3
+    clamped = np.clip(wild, 1, 4).astype(np.int32)
+    bcq.select_kernel("dequant_mfma")
+    try:
+        y_wild = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(wild), gpu.to_dev(x))
+        y_ok = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(clamped), gpu.to_dev(x))
+        some = {p: s for p, s in dl.scales.items() if p != 3}              # no scale set for precision 3
+        y_some = bcq.bcq_gemm_mixed(dl.planes, some, gpu.to_dev(clamped), gpu.to_dev(x), y=torch.full_like(y_ok, 7.0))
+        torch.cuda.synchronize()
+    finally:
+        bcq.select_kernel("auto")
+    assert torch.equal(y_wild, y_ok)
+    is3 = torch.from_numpy(clamped == 3).to(y_ok.device)
+    assert torch.all(y_some[is3] == 0) and torch.equal(y_some[~is3], y_ok[~is3])
+
+
 def test_forced_variant_that_cannot_run_is_an_error(gpu):
     import paper_2510_10467_amd as bcq
     layer = syn.make_layer(16, 640, seed=(160, 0))            # n is shorter than one K slice

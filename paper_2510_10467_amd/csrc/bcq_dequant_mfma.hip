@@ -5,8 +5,8 @@
 //   planewise_mixed_kernel   per-request precision in tiles of 16 requests: one pass over the planes, each request's
 //                            own scales applied to the group sums
 //   dequant_mixed_kernel     per-request precision at 64 requests per workgroup: W_q rebuilt once per precision present
-//   dequant_mfma_kernel with BYCLASS = true: per-request precision beyond 64 requests, one launch per precision, each
-//                            on the requests of that precision picked out of the batch by rank
+//   dequant_byclass_kernel   per-request precision beyond 64 requests: the uniform kernel's body per precision, each
+//                            workgroup on the requests of its precision, picked out of the batch by rank
 //
 // Large-batch kernel: dequantise W_p = sum_i alpha_i B_i tile by tile (Fig. 1(b): p-bit inference
 // reconstructs the weights from the first p planes and the scale set of precision p) and feed the
@@ -113,13 +113,12 @@ struct Ahead {
 // one more pass with an all-ones operand.
 // (The small-tile shapes leave LDS for several workgroups per CU: at least four waves per SIMD keeps the compiler
 // from spending the few registers that would forbid it.)
-// BYCLASS (per-request precision at large batch): the launch serves the requests whose precision is P, and the
-//   workgroup's 16 NT requests are those of rank b0 .. b0 + 16 NT - 1 among them, in the order of the batch; every
-//   wave ranks the batch itself (ballots over p_req, no memory beyond the inputs), the first one leaves the request
-//   numbers in LDS.  A workgroup whose ranks nobody holds returns at once: the grid is laid out for the case that
-//   every request has precision P.
+// BYCLASS (per-request precision at large batch): the workgroup serves requests whose precision is P, namely those
+//   of rank b0 .. b0 + 16 NT - 1 among them, in the order of the batch; every wave ranks the batch itself (ballots
+//   over p_req, no memory beyond the inputs), the first one leaves the request numbers in LDS.  A workgroup whose
+//   ranks nobody holds returns at once: the grid is laid out for the case that every request has precision P.
 template <int P, int NT, int TEAMS, int RW, bool PW = false, bool BYCLASS = false>
-__global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(NT <= 2 ? 4 : 1))) void dequant_mfma_kernel(DequantParams a)
+__device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const int column)
 {
     constexpr int kTeamThreads = 64 * RW;
     constexpr int XU = 4 * NT / RW;           // 16-byte units of an activation tile per thread of a team
@@ -137,7 +136,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
     const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
-    const int b0 = blockIdx.y * (16 * NT);    // first request of the workgroup (BYCLASS: first rank)
+    const int b0 = column * (16 * NT);        // first request of the workgroup (BYCLASS: first rank)
 
     int nreq = a.batch - b0;                  // requests from b0 on (may be more than the workgroup's 16 NT)
     const uint32_t *req_of = reinterpret_cast<const uint32_t *>(lds + lds_bytes(NT, TEAMS));
@@ -492,6 +491,40 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
                 const int r = 16 * u + 4 * kq + i;
                 if (r < nreq) a.y[(size_t)(BYCLASS ? req_of[r] : (uint32_t)(b0 + r)) * a.m + row] = (_Float16)acc[u][i];
             }
+    }
+}
+
+template <int P, int NT, int TEAMS, int RW, bool PW = false>
+__global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(NT <= 2 ? 4 : 1))) void dequant_mfma_kernel(DequantParams a)
+{
+    dequant_mfma_body<P, NT, TEAMS, RW, PW, false>(a, (int)blockIdx.y);
+}
+
+// Per-request precision beyond 64 requests: blockIdx.y + 1 is the precision a workgroup serves, with the scale and
+// offset set of that precision and the body specialised for it; one launch covers every precision, so that the
+// workgroups of all of them share the chip (on short matrices those of one precision would leave most of it idle).
+// blockIdx.z is the tile of 16 NT ranks: workgroups are dispatched in the order of their ids, so the first tiles
+// of every precision, which hold the work, go first, and the tiles nobody's rank reaches (each costs its
+// workgroup the ranking, and a CU holds one such workgroup at a time) trail behind instead of queueing in front
+// of the next precision's work.
+template <int Q, int NT, int TEAMS, int RW>
+__device__ __forceinline__ void serve_precision(DequantParams a)
+{
+    if (!a.scale_sets[Q]) return;               // (requests of such a precision get their zeros from zero_unserved_kernel)
+    a.scales = a.scale_sets[Q];
+    a.has_offsets = a.offset_sets[Q] != nullptr;
+    a.offsets = a.has_offsets ? a.offset_sets[Q] : a.scales;
+    dequant_mfma_body<Q, NT, TEAMS, RW, false, true>(a, (int)blockIdx.z);
+}
+
+template <int NT, int TEAMS, int RW>
+__global__ __launch_bounds__(64 * RW * TEAMS) void dequant_byclass_kernel(DequantParams a)
+{
+    switch (blockIdx.y) {
+    case 0: serve_precision<1, NT, TEAMS, RW>(a); break;
+    case 1: serve_precision<2, NT, TEAMS, RW>(a); break;
+    case 2: serve_precision<3, NT, TEAMS, RW>(a); break;
+    default: serve_precision<4, NT, TEAMS, RW>(a); break;
     }
 }
 
@@ -1101,18 +1134,31 @@ hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t 
     return hipGetLastError();
 }
 
-template <int P, int NT, int TEAMS, int RW, bool PW, bool BYCLASS = false>
+template <int P, int NT, int TEAMS, int RW, bool PW>
 hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
     static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
-    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW, BYCLASS>;
-    constexpr int kLds = lds_bytes(NT, TEAMS) + (BYCLASS ? 16 * NT * 4 : 0);       // (BYCLASS: the request numbers behind the tiles)
-    if (kLds > 64 * 1024) {
+    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW>;
+    if (lds_bytes(NT, TEAMS) > 64 * 1024) {
         // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           lds_bytes(NT, TEAMS));
         if (e != hipSuccess) return e;
     }
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, TEAMS), stream, pr);
+    return hipGetLastError();
+}
+
+template <int NT, int TEAMS, int RW>
+hipError_t launch_byclass(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
+{
+    static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
+    auto kernel = dequant_byclass_kernel<NT, TEAMS, RW>;
+    constexpr int kLds = lds_bytes(NT, TEAMS) + 16 * NT * 4;        // the workgroup's request numbers behind the tiles
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)a.p_max, (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
     hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), kLds, stream, pr);
     return hipGetLastError();
 }
@@ -1140,15 +1186,16 @@ constexpr WgShape kShapes[] = {{1, 4, 0.51f, 0.32f, 0.78f, 0.39f}, {1, 2, 0.36f,
                                {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
                                {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
 
-// the cheapest shape for `batch` requests at precision p, among the shapes of at least min_nt tiles
-void cheapest_shape(int p, int64_t m, int batch, int min_nt, int &nt, int &rw)
+// the cheapest shape for `batch` requests at precision p, among the shapes of at least min_nt tiles; `times`: that
+// many such problems in one launch
+void cheapest_shape(int p, int64_t m, int batch, int min_nt, int &nt, int &rw, int times = 1)
 {
     nt = rw = 4;
     float best = 0.f;
     for (const WgShape &c : kShapes) {
         if (c.nt < min_nt || (c.nt <= 2 && batch > 16 * c.nt)) continue;
         const int blocks = c.rw == 8 ? 1 : c.rw;        // (code 8: one row block, eight teams)
-        const float wgs = (float)((m + 16 * blocks - 1) / (16 * blocks)) * (float)((batch + 16 * c.nt - 1) / (16 * c.nt));
+        const float wgs = (float)((m + 16 * blocks - 1) / (16 * blocks)) * (float)((batch + 16 * c.nt - 1) / (16 * c.nt)) * (float)times;
         const float one = p >= 3 ? c.us_p4 : c.us_p2, many = p >= 3 ? c.many_p4 : c.many_p2;
         float cost = one;
         if (many > 0.f) cost = wgs / 256.f * many > one ? wgs / 256.f * many : one;
@@ -1161,24 +1208,24 @@ void cheapest_shape(int p, int64_t m, int batch, int min_nt, int &nt, int &rw)
     }
 }
 
-// One precision of a batch with per-request precision: the uniform kernel on the requests of precision P.  How many
-// they are only the GPU knows; the shape is chosen for `expected` of them and the grid for all of the batch.
-template <int P>
-hipError_t launch_class(const DequantParams &pr, const GemmArgs &a, int expected, hipStream_t stream)
+// A batch with per-request precision beyond 64 requests: the uniform kernel's body on the requests of each
+// precision.  How many a precision has only the GPU knows; the shape is chosen for `expected` of them at the
+// deepest precision and the grid for all of the batch at every precision.
+hipError_t launch_classes(const DequantParams &pr, const GemmArgs &a, int expected, int nsets, int p_deepest, hipStream_t stream)
 {
     int nt, rw;
-    cheapest_shape(P, a.m, expected, 4, nt, rw);
+    cheapest_shape(p_deepest, a.m, expected, 4, nt, rw, nsets);
     if (g_forced_nt >= 4) {
         nt = g_forced_nt;
         rw = g_forced_rw;
     }
     switch (nt * 10 + rw) {
-    case 44: return launch_one<P, 4, 4, 4, false, true>(pr, a, stream);
-    case 42: return launch_one<P, 4, 4, 2, false, true>(pr, a, stream);
-    case 41: return launch_one<P, 4, 4, 1, false, true>(pr, a, stream);
-    case 84: return launch_one<P, 8, 2, 4, false, true>(pr, a, stream);
-    case 82: return launch_one<P, 8, 2, 2, false, true>(pr, a, stream);
-    case 164: return launch_one<P, 16, 1, 4, false, true>(pr, a, stream);
+    case 44: return launch_byclass<4, 4, 4>(pr, a, stream);
+    case 42: return launch_byclass<4, 4, 2>(pr, a, stream);
+    case 41: return launch_byclass<4, 4, 1>(pr, a, stream);
+    case 84: return launch_byclass<8, 2, 4>(pr, a, stream);
+    case 82: return launch_byclass<8, 2, 2>(pr, a, stream);
+    case 164: return launch_byclass<16, 1, 4>(pr, a, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -1304,10 +1351,10 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
                  : rw16 == 2 ? launch_planewise_mixed<1, 4, 2>(pr, a, stream) : launch_planewise_mixed<1, 4, 1>(pr, a, stream);
         }
         if (a.batch > kClassFrom && (g_forced_nt == 0 || g_forced_nt >= 4)) {
-            // Beyond 64 requests: one launch of the uniform kernel per precision, each on the requests of that
-            // precision wherever they sit in the batch (BYCLASS).  A weight is then rebuilt once per precision
-            // and up to 256 requests, at the cost of that precision alone, instead of once per 64 requests at
-            // the cost of all precisions present.
+            // Beyond 64 requests: the uniform kernel's body per precision, each on the requests of that precision
+            // wherever they sit in the batch (dequant_byclass_kernel).  A weight is then rebuilt once per
+            // precision and up to 256 requests, at the cost of that precision alone, instead of once per 64
+            // requests at the cost of all precisions present.
             int nsets = 0;
             uint32_t unserved = 0;
             for (int q = 1; q <= a.p_max; ++q) {
@@ -1319,19 +1366,15 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
                 hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return e;
             }
-            // an even split plus a quarter: a precision that draws a few requests more than its share should not
-            // need a second, nearly empty tile
-            const int expected = nsets ? (a.batch * 5 + 4 * nsets - 1) / (4 * nsets) : a.batch;
-            for (int q = 1; q <= a.p_max; ++q) {
-                if (!a.scales[q]) continue;
-                pr.scales = pr.scale_sets[q];
-                pr.has_offsets = pr.offset_sets[q] != nullptr;
-                pr.offsets = pr.has_offsets ? pr.offset_sets[q] : pr.scales;
-                hipError_t e = q == 1 ? launch_class<1>(pr, a, expected, stream) : q == 2 ? launch_class<2>(pr, a, expected, stream)
-                             : q == 3 ? launch_class<3>(pr, a, expected, stream) : launch_class<4>(pr, a, expected, stream);
-                if (e != hipSuccess) return e;
-            }
-            return hipSuccess;
+            // an even split plus 1.3 standard deviations of a uniform draw: a precision that gets a few requests more
+            // than its share should not need a second, nearly empty tile (which costs as much as a full one)
+            const float share = nsets ? (float)a.batch / (float)nsets : (float)a.batch;
+            const int expected = (int)__builtin_ceilf(share + 1.3f * __builtin_sqrtf(share * (float)(nsets > 1 ? nsets - 1 : 0) / (float)(nsets ? nsets : 1)));
+            if (nsets == 0) return hipSuccess;
+            int deepest = 1;
+            for (int q = 1; q <= a.p_max; ++q)
+                if (a.scales[q]) deepest = q;
+            return launch_classes(pr, a, expected, nsets, deepest, stream);
         }
         // 64, 32 or 16 rows per workgroup by the same two-factor cost as the uniform kernel (measured with three
         // precisions present: 1.8, 1.43 and 0.94 microseconds per workgroup and group of columns; two of the

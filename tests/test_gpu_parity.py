@@ -338,6 +338,10 @@ def test_auto_dispatch_by_batch(gpu):
     p_many = syn.make_p_req(130, 1, 4, seed=(171, 7))
     used, _ = gpu.check_mixed(big, p_many, syn.make_x(130, 1024, seed=(171, 7)), "auto")
     assert used == "dequant_mfma"
+    used, _ = gpu.check_mixed(big, p_many[:97], syn.make_x(97, 1024, seed=(171, 9)), "auto")   # beyond 96: one pass per precision
+    assert used == "dequant_mfma"
+    used, _ = gpu.check_mixed(big, p_many[:96], syn.make_x(96, 1024, seed=(171, 10)), "auto")
+    assert used == "plane_f16"
     used, _ = gpu.check_mixed(big, p_req[:16], syn.make_x(16, 1024, seed=(171, 5)), "auto")
     assert used == "plane_f16"
     used, _ = gpu.check_mixed(big, p_req[:8], syn.make_x(8, 1024, seed=(171, 8)), "auto")

@@ -94,6 +94,7 @@ struct DequantParams {
     const unsigned char *offset_sets[kMaxP + 1];
     const int32_t *p_req;
     int p_max;
+    uint32_t class_order;                   // dequant_byclass_kernel: byte y = the precision served by the workgroups with blockIdx.y = y
 };
 
 // What a thread fetches one group ahead into registers: the plane words of its row (its share of the next
@@ -102,6 +103,36 @@ template <int P, int XU>
 struct Ahead {
     uint32_t w[P];
 };
+
+// The requests of precision q (after clamping to [1, p_max]) in the order of the batch: those of rank b0 .. b0 + TB - 1
+// get their numbers written to req_of[0 .. TB - 1] by the workgroup's first wave; returns how many of these ranks
+// exist (0 or less: none), the same number in every wave, each of which runs the whole ranking itself.  Sixteen
+// independent loads at a time (1024 requests), so that a batch costs one memory latency, not one per 64 requests.
+template <int TB>
+__device__ __forceinline__ int rank_requests(const DequantParams &a, const int q, const int b0, uint32_t *req_of)
+{
+    const int lane = threadIdx.x & 63;
+    int seen = 0;                               // requests of precision q so far
+    for (int blk = 0; blk < a.batch && seen < b0 + TB; blk += 1024) {
+        int pv[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int b = blk + 64 * j + lane;
+            pv[j] = b < a.batch ? a.p_req[b] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int b = blk + 64 * j + lane;
+            const int pc = pv[j] < 1 ? 1 : (pv[j] > a.p_max ? a.p_max : pv[j]);
+            const bool is = b < a.batch && pc == q;
+            const unsigned long long mask = __ballot(is);
+            const int rank = seen + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (is && rank >= b0 && rank < b0 + TB && threadIdx.x < 64) req_of[rank - b0] = (uint32_t)b;
+            seen += __popcll(mask);
+        }
+    }
+    return seen - b0 > TB ? TB : seen - b0;
+}
 
 // NT: 16-request tiles per workgroup (1, 2, 4, 8 or 16); TEAMS: teams of waves (K split inside the workgroup); RW: waves per
 // team = 16-row blocks per workgroup.
@@ -141,31 +172,8 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     int nreq = a.batch - b0;                  // requests from b0 on (may be more than the workgroup's 16 NT)
     const uint32_t *req_of = reinterpret_cast<const uint32_t *>(lds + lds_bytes(NT, TEAMS));
     if constexpr (BYCLASS) {
-        // Sixteen independent loads at a time (1024 requests), so that a batch costs one memory latency, not one
-        // per 64 requests.  `seen` = requests of precision P so far: the same number in every wave.
-        int seen = 0;
-        for (int blk = 0; blk < a.batch && seen < b0 + 16 * NT; blk += 1024) {
-            int pv[16];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int b = blk + 64 * j + lane;
-                pv[j] = b < a.batch ? a.p_req[b] : 0;
-            }
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int b = blk + 64 * j + lane;
-                const int pc = pv[j] < 1 ? 1 : (pv[j] > a.p_max ? a.p_max : pv[j]);
-                const bool is = b < a.batch && pc == P;
-                const unsigned long long mask = __ballot(is);
-                const int rank = seen + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                if (is && rank >= b0 && rank < b0 + 16 * NT && threadIdx.x < 64)
-                    reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, TEAMS))[rank - b0] = (uint32_t)b;
-                seen += __popcll(mask);
-            }
-        }
-        nreq = seen - b0;
+        nreq = rank_requests<16 * NT>(a, P, b0, reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, TEAMS)));
         if (nreq <= 0) return;                // (every wave of the workgroup: none has reached a barrier yet)
-        if (nreq > 16 * NT) nreq = 16 * NT;
         __syncthreads();
     }
 
@@ -500,8 +508,9 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     dequant_mfma_body<P, NT, TEAMS, RW, PW, false>(a, (int)blockIdx.y);
 }
 
-// Per-request precision beyond 64 requests: blockIdx.y + 1 is the precision a workgroup serves, with the scale and
-// offset set of that precision and the body specialised for it; one launch covers every precision, so that the
+// Per-request precision beyond 64 requests: byte blockIdx.y of class_order is the precision a workgroup serves, with
+// the scale and offset set of that precision and the body specialised for it (the deepest precision first, those
+// without a scale set, whose requests only get zeros, last); one launch covers every precision, so that the
 // workgroups of all of them share the chip (on short matrices those of one precision would leave most of it idle).
 // blockIdx.z is the tile of 16 NT ranks: workgroups are dispatched in the order of their ids, so the first tiles
 // of every precision, which hold the work, go first, and the tiles nobody's rank reaches (each costs its
@@ -510,7 +519,20 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 template <int Q, int NT, int TEAMS, int RW>
 __device__ __forceinline__ void serve_precision(DequantParams a)
 {
-    if (!a.scale_sets[Q]) return;               // (requests of such a precision get their zeros from zero_unserved_kernel)
+    if (!a.scale_sets[Q]) {
+        // no scale set for this precision: its requests get zeros (the workgroup's rows of its tile of ranks)
+        extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+        uint32_t *req_of = reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, TEAMS));
+        const int nreq = rank_requests<16 * NT>(a, Q, (int)blockIdx.z * (16 * NT), req_of);
+        if (nreq <= 0) return;
+        __syncthreads();
+        const uint32_t row0 = blockIdx.x * (16 * RW);
+        for (int i = threadIdx.x; i < nreq * 16 * RW; i += 64 * RW * TEAMS) {
+            const uint32_t row = row0 + (uint32_t)(i % (16 * RW));
+            if (row < a.m) a.y[(size_t)req_of[i / (16 * RW)] * a.m + row] = (_Float16)0.f;
+        }
+        return;
+    }
     a.scales = a.scale_sets[Q];
     a.has_offsets = a.offset_sets[Q] != nullptr;
     a.offsets = a.has_offsets ? a.offset_sets[Q] : a.scales;
@@ -520,10 +542,10 @@ __device__ __forceinline__ void serve_precision(DequantParams a)
 template <int NT, int TEAMS, int RW>
 __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_byclass_kernel(DequantParams a)
 {
-    switch (blockIdx.y) {
-    case 0: serve_precision<1, NT, TEAMS, RW>(a); break;
-    case 1: serve_precision<2, NT, TEAMS, RW>(a); break;
-    case 2: serve_precision<3, NT, TEAMS, RW>(a); break;
+    switch ((a.class_order >> (8 * blockIdx.y)) & 0xffu) {
+    case 1: serve_precision<1, NT, TEAMS, RW>(a); break;
+    case 2: serve_precision<2, NT, TEAMS, RW>(a); break;
+    case 3: serve_precision<3, NT, TEAMS, RW>(a); break;
     default: serve_precision<4, NT, TEAMS, RW>(a); break;
     }
 }
@@ -1230,15 +1252,6 @@ hipError_t launch_classes(const DequantParams &pr, const GemmArgs &a, int expect
     }
 }
 
-// zeros for the requests whose precision has no scale set (bit q of `unserved`): one workgroup per request
-__global__ __launch_bounds__(256) void zero_unserved_kernel(const int32_t *p_req, int p_max, uint32_t unserved, _Float16 *y, uint32_t m)
-{
-    const int pv = p_req[blockIdx.x];
-    const int pc = pv < 1 ? 1 : (pv > p_max ? p_max : pv);
-    if (!((unserved >> pc) & 1u)) return;
-    for (uint32_t r = threadIdx.x; r < m; r += 256) y[(size_t)blockIdx.x * m + r] = (_Float16)0.f;
-}
-
 template <int P, bool PW>
 hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
@@ -1355,22 +1368,19 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
             // wherever they sit in the batch (dequant_byclass_kernel).  A weight is then rebuilt once per
             // precision and up to 256 requests, at the cost of that precision alone, instead of once per 64
             // requests at the cost of all precisions present.
-            int nsets = 0;
-            uint32_t unserved = 0;
-            for (int q = 1; q <= a.p_max; ++q) {
-                if (a.scales[q]) ++nsets;
-                else unserved |= 1u << q;
-            }
-            if (unserved) {
-                hipLaunchKernelGGL(zero_unserved_kernel, dim3((unsigned)a.batch), dim3(256), 0, stream, a.p_req, a.p_max, unserved, a.y, pr.m);
-                hipError_t e = hipGetLastError();
-                if (e != hipSuccess) return e;
-            }
+            int nsets = 0, y = 0;
+            pr.class_order = 0;
+            for (int q = a.p_max; q >= 1; --q)
+                if (a.scales[q]) {
+                    ++nsets;
+                    pr.class_order |= (uint32_t)q << (8 * y++);
+                }
+            for (int q = a.p_max; q >= 1; --q)
+                if (!a.scales[q]) pr.class_order |= (uint32_t)q << (8 * y++);
             // an even split plus 1.3 standard deviations of a uniform draw: a precision that gets a few requests more
             // than its share should not need a second, nearly empty tile (which costs as much as a full one)
             const float share = nsets ? (float)a.batch / (float)nsets : (float)a.batch;
             const int expected = (int)__builtin_ceilf(share + 1.3f * __builtin_sqrtf(share * (float)(nsets > 1 ? nsets - 1 : 0) / (float)(nsets ? nsets : 1)));
-            if (nsets == 0) return hipSuccess;
             int deepest = 1;
             for (int q = 1; q <= a.p_max; ++q)
                 if (a.scales[q]) deepest = q;

@@ -515,3 +515,57 @@ def test_large_batch_kernels_on_one_to_three_groups(gpu, kernel, n):
         gpu.check_gemv(dl, 3, x, kernel, offsets=z)
         used, _ = gpu.check_mixed(dl, syn.make_p_req(batch, 1, 4, seed=(157, batch)), x, kernel)
         assert used == kernel
+
+
+def test_seeded_random_cases_against_the_oracle(gpu):
+    """Eighty seeded random cases of bcq_gemm_mixed and bcq_gemv: shapes (ragged rows, one to 32 groups of columns,
+    groups of 64 / 128 / 256), batches on both sides of every dispatch threshold, precisions drawn, sorted, all
+    equal or outside [1, p_max], offsets for some precisions, automatic dispatch or a forced large-batch shape."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    rng = np.random.default_rng([syn.BASE_SEED, 910])
+    shapes = ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4", None, None, None]
+    done = 0
+    while done < 80:
+        m = int(rng.choice([16, 37, 100, 150, 260, 700, 1100, 4100, 8200]))
+        n = int(rng.choice([1024, 1536, 2048, 2304, 4096]))
+        group = int(rng.choice([128, 128, 128, 256, 64])) if n % 256 == 0 else 128
+        batch = int(rng.choice([1, 3, 8, 9, 16, 17, 33, 48, 49, 64, 65, 80, 97, 128, 129, 200, 257, 400, 1030]))
+        if n % group or m * batch > 300000:
+            continue
+        layer = syn.make_layer(m, n, group=group, seed=(911, done), signed=bool(rng.integers(2)))
+        dl = gpu.DeviceLayer(layer)
+        x = syn.make_x(batch, n, seed=(912, done))
+        kind = int(rng.integers(4))
+        if kind == 0:
+            p_req = syn.make_p_req(batch, 1, 4, seed=(913, done))
+        elif kind == 1:
+            p_req = np.sort(syn.make_p_req(batch, 2, 4, seed=(913, done)))
+        elif kind == 2:
+            p_req = np.full(batch, int(rng.integers(1, 5)), dtype=np.int32)
+        else:
+            p_req = rng.choice([1, 4, 4, 4, 7, -2], size=batch).astype(np.int32)
+        zs = None
+        if rng.integers(3) == 0 and group != 64:
+            zs = {p: syn.make_offsets(p, m, n, group, seed=(914, done, p)) for p in (1, 2, 3, 4) if rng.integers(2)}
+        kernel = str(rng.choice(["auto", "auto", "dequant_mfma"]))
+        shape = shapes[int(rng.integers(len(shapes)))]
+        what = f"case {done}: m={m} n={n} group={group} batch={batch} kind={kind} offsets={sorted(zs) if zs else None} kernel={kernel} shape={shape}"
+        if shape and kernel != "auto":
+            bcq.select_dequant_shape(*[int(v) for v in shape.split(",")])
+        try:
+            bcq.select_kernel(kernel)
+            try:
+                y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req.astype(np.int32)), gpu.to_dev(x), group=group,
+                                       offsets_by_p={q: gpu.to_dev(z) for q, z in zs.items()} if zs else None)
+                torch.cuda.synchronize()
+            finally:
+                bcq.select_kernel("auto")
+            y_ref, a_ref = gpu.oracle.gemm_mixed(layer.planes, layer.scales, np.clip(p_req, 1, 4).astype(np.int32), x, group, offsets_by_p=zs)
+            gpu.assert_within_tolerance(y, y_ref, a_ref, what)
+            p = int(rng.integers(1, 5))
+            gpu.check_gemv(dl, p, x, "auto", group, offsets=zs[p] if zs and p in zs else None)
+        finally:
+            bcq.select_dequant_shape(0, 0)
+        done += 1

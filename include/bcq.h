@@ -86,9 +86,12 @@ int bcq_select_kernel(int variant);
  * rows per workgroup, one of (1,4) (1,2) (1,1) (2,4) (2,2) (4,4), or (0,4) (0,2)
  * (0,1) for a single tile of 16 requests and (32,4) (32,2) (32,1) for one of 32,
  * (0,8) and (32,8) for those tiles with one row block whose columns are split
- * over eight teams of waves instead of four;
+ * over eight teams of waves instead of four, (4,8) and (2,8) for 256 and 128 requests
+ * with eight row blocks, (4,40) for 256 requests and four row blocks served by two teams
+ * of waves that share the activation tiles;
  * per-request precision uses the row blocks and whether the tile has 32
- * requests only.  (0, 0) restores the automatic choice.
+ * requests only, beyond 64 requests the whole shape if it has 64 requests or
+ * more.  (0, 0) restores the automatic choice.
  * Returns BCQ_OK, or BCQ_ERR_VARIANT for any other pair.  Host call, not
  * thread-safe against concurrent launches.
  */

@@ -148,11 +148,20 @@ __device__ __forceinline__ int rank_requests(const DequantParams &a, const int q
 //   of rank b0 .. b0 + 16 NT - 1 among them, in the order of the batch; every wave ranks the batch itself (ballots
 //   over p_req, no memory beyond the inputs), the first one leaves the request numbers in LDS.  A workgroup whose
 //   ranks nobody holds returns at once: the grid is laid out for the case that every request has precision P.
-template <int P, int NT, int TEAMS, int RW, bool PW = false, bool BYCLASS = false>
+// SHARE: the teams do not take alternate groups with tiles of their own but share one pair of tiles and split the
+//   four matrix sub-steps of every group between them (team k takes sub-steps k 4/TEAMS ...): the 128- and
+//   256-request tiles then fit the LDS once instead of TEAMS times, so that a CU holds eight waves on a 256-request
+//   tile (two per SIMD, one computing while the other waits for its operands) instead of four.
+template <int P, int NT, int TEAMS, int RW, bool PW = false, bool BYCLASS = false, bool SHARE = false>
 __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const int column)
 {
     constexpr int kTeamThreads = 64 * RW;
-    constexpr int XU = 4 * NT / RW;           // 16-byte units of an activation tile per thread of a team
+    static_assert(!(SHARE && PW), "the plane-wise variant has no shared-tile form");
+    constexpr int GSTEP = SHARE ? 1 : TEAMS;  // distance between a team's groups
+    constexpr int TN = SHARE ? 4 / TEAMS : 4; // matrix sub-steps of a group that a team computes
+    constexpr int SW = SHARE ? RW * TEAMS : RW;       // waves that stage a tile together
+    constexpr int LT = SHARE ? 1 : TEAMS;     // pairs of tiles in LDS
+    constexpr int XU = 4 * NT / SW;           // 16-byte units of an activation tile per thread of those waves
     constexpr int UT = NT < 4 ? NT : 4;       // request tiles whose operands are held at a time
     static_assert(XU >= 1 && NT % UT == 0, "tile does not split over the team");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -162,7 +171,10 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     // base addresses in scalar registers
     const int tid = threadIdx.x % kTeamThreads, team = __builtin_amdgcn_readfirstlane(threadIdx.x / kTeamThreads);
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    unsigned char *xt0 = lds + kLutBytes + team * 2 * x_tile_bytes(NT);     // the team's two activation tiles, used alternately
+    unsigned char *xt0 = lds + kLutBytes + (SHARE ? 0 : team) * 2 * x_tile_bytes(NT);     // the team's two activation tiles, used alternately
+    const int g_first = SHARE ? 0 : team;     // the team's first group
+    const int sw = SHARE ? team * RW + wave : wave;   // this wave among those that stage a tile
+    const int t0 = SHARE ? team * TN : 0;     // the team's first matrix sub-step
     constexpr int kTile = x_tile_bytes(NT);
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
@@ -170,9 +182,9 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     const int b0 = column * (16 * NT);        // first request of the workgroup (BYCLASS: first rank)
 
     int nreq = a.batch - b0;                  // requests from b0 on (may be more than the workgroup's 16 NT)
-    const uint32_t *req_of = reinterpret_cast<const uint32_t *>(lds + lds_bytes(NT, TEAMS));
+    const uint32_t *req_of = reinterpret_cast<const uint32_t *>(lds + lds_bytes(NT, LT));
     if constexpr (BYCLASS) {
-        nreq = rank_requests<16 * NT>(a, P, b0, reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, TEAMS)));
+        nreq = rank_requests<16 * NT>(a, P, b0, reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, LT)));
         if (nreq <= 0) return;                // (every wave of the workgroup: none has reached a barrier yet)
         __syncthreads();
     }
@@ -206,7 +218,7 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     const uint32_t half_shift = a.gshift < 0 && kq >= 2 ? 16u : 0u;      // groups of 64: columns 64..127 of a step use the upper scale
     uint32_t sc[P], zc = 0;                   // this lane's share of the scales in flight / in use (binary16 bits)
     auto fetch_scales = [&](int block) {      // for the team's steps 4 block .. 4 block + 3
-        const int gj = min(team + TEAMS * (4 * block + (lane & 3)), a.ngroups - 1);
+        const int gj = min(g_first + GSTEP * (4 * block + (lane & 3)), a.ngroups - 1);
         uint32_t off = s_row + scale_col(gj);
         asm volatile("" : "+v"(off));
         if (a.gshift < 0) {
@@ -227,7 +239,7 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     uint32_t xs_src[XU];
 #pragma unroll
     for (int k = 0; k < XU; ++k) {
-        const int req = 4 * (k * RW + wave) + (lane >> 4);
+        const int req = 4 * (k * SW + sw) + (lane >> 4);
         const int part = (lane & 15) ^ (req & 15);
         const uint32_t source = BYCLASS ? req_of[min(req, nreq - 1)] : (uint32_t)min(b0 + req, a.batch - 1);
         xs_src[k] = source * a.x_stride + part * 16;
@@ -236,7 +248,7 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     const unsigned char *xa_lane = xt0 + n16 * kXRowBytes;
     uint32_t xa_off[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) xa_off[t] = (uint32_t)(((4 * kq + t) ^ n16) * 16);
+    for (int t = 0; t < 4; ++t) xa_off[t] = (uint32_t)(((4 * kq + ((t0 + t) & 3)) ^ n16) * 16);      // (entry t: the team's sub-step t0 + t)
 
     // Plane words are loaded as ordinary (cached) loads: a wave takes 16 bytes of each row per step and the
     // rest of the 128-byte line serves the other teams and the next step; marked non-temporal the line was
@@ -253,7 +265,7 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     auto stage_x_unit = [&](int g, int buf, int k) {
         const unsigned char *x_base = a.x + (uint32_t)g * 256;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_base + xs_src[k]),
-                                         (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * RW + wave) * 1024), 16, 0, 0);
+                                         (__attribute__((address_space(3))) void *)(xt0 + buf * kTile + (k * SW + sw) * 1024), 16, 0, 0);
     };
     auto stage_x = [&](int g, int buf) {
 #pragma unroll
@@ -298,14 +310,14 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
             alpha[i] = (float)__builtin_bit_cast(_Float16, (unsigned short)ab);
         }
         // the scales of the next four steps, once the last of these four has handed its own over
-        if ((mine & 3) == 3 && g + TEAMS < a.ngroups) fetch_scales((mine >> 2) + 1);
+        if ((mine & 3) == 3 && g + GSTEP < a.ngroups) fetch_scales((mine >> 2) + 1);
         // The loads for the team's next group are spread over the four matrix steps below: issued all at once
         // right after the barrier, by every wave of the workgroup, they queue up in the memory pipe while
         // no wave has arithmetic to do.  With three or four planes the plane words go two planes per
         // matrix step, otherwise all of them here.
         constexpr bool kSpreadPlanes = P >= 3;
-        const bool more = g + TEAMS < a.ngroups;
-        if (more && !kSpreadPlanes) fetch_w(nxt, g + TEAMS);
+        const bool more = g + GSTEP < a.ngroups;
+        if (more && !kSpreadPlanes) fetch_w(nxt, g + GSTEP);
         const unsigned char *xa_cur = xa_lane + buf * kTile;
         // table offsets of all low and all high nibbles of a plane word at once: byte t of `lo8` (`hi8`) is
         // eight times the low (high) nibble of byte t
@@ -314,6 +326,10 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
         for (int i = 0; i < P; ++i) {
             lo8[i] = (w[i] << 3) & 0x78787878u;
             hi8[i] = (w[i] >> 1) & 0x78787878u;
+            if constexpr (SHARE) {              // byte t below: the team's sub-step t0 + t
+                lo8[i] >>= 8 * t0;
+                hi8[i] >>= 8 * t0;
+            }
             // kept as they are: a look-up is then one add that picks byte t (the compiler would otherwise shift
             // and mask the plane word again for every nibble)
             asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
@@ -343,11 +359,11 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
                         if (kSpreadPlanes) {
 #pragma unroll
                             for (int i = 0; i < P; ++i)
-                                if (i / 2 == slot) fetch_plane(nxt, g + TEAMS, i);
+                                if (i / 2 == slot) fetch_plane(nxt, g + GSTEP, i);
                         }
 #pragma unroll
                         for (int k = 0; k < XU; ++k)
-                            if (k * NSLOT / XU == slot) stage_x_unit(g + TEAMS, buf ^ 1, k);
+                            if (k * NSLOT / XU == slot) stage_x_unit(g + GSTEP, buf ^ 1, k);
                     }
 #pragma unroll
                     for (int c = 0; c < NT / UT; ++c) {
@@ -392,7 +408,7 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
             }
         } else {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < TN; ++t) {
             // every LDS read of this matrix step goes out first: the table entries, then the activation operands
             // of the first four request tiles, which arrive while the weights are being rebuilt
             v4h pl[P], ph[P];
@@ -408,12 +424,12 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
                 if (kSpreadPlanes) {
 #pragma unroll
                     for (int i = 0; i < P; ++i)
-                        if (i / 2 == t) fetch_plane(nxt, g + TEAMS, i);
+                        if ((i / 2 < TN ? i / 2 : TN - 1) == t) fetch_plane(nxt, g + GSTEP, i);
                 }
                 // tile buf ^ 1 was last read before the previous barrier
 #pragma unroll
                 for (int k = 0; k < XU; ++k)
-                    if (k * 4 / XU == t) stage_x_unit(g + TEAMS, buf ^ 1, k);
+                    if (k * TN / XU == t) stage_x_unit(g + GSTEP, buf ^ 1, k);
             }
             __builtin_amdgcn_sched_barrier(0);
             float wf[8];
@@ -452,29 +468,29 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS
         // tile `buf` free, the other tile complete.  A team of ONE wave stages and reads its tiles itself: no barrier,
         // and the waves of the workgroup drift apart, which lets one compute while another waits.
-        if constexpr (RW > 1) __syncthreads();
+        if constexpr (RW > 1 || SHARE) __syncthreads();
     };
 
     Ahead<P, XU> ah0, ah1;
 #pragma unroll
     for (int i = 0; i < P; ++i) sc[i] = 0;
-    if (team < a.ngroups) {
-        stage_x(team, 0);
-        fetch_w(ah0, team);
+    if (g_first < a.ngroups) {
+        stage_x(g_first, 0);
+        fetch_w(ah0, g_first);
         fetch_scales(0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();                            // table and first tiles complete
-    const int npairs = (a.ngroups + 2 * TEAMS - 1) / (2 * TEAMS);
+    const int npairs = (a.ngroups + 2 * GSTEP - 1) / (2 * GSTEP);
     for (int it = 0; it < npairs; ++it) {
-        const int g = 2 * it * TEAMS + team;
+        const int g = 2 * it * GSTEP + g_first;
         step(ah0, ah1, g, 2 * it, 0);
-        step(ah1, ah0, g + TEAMS, 2 * it + 1, 1);
+        step(ah1, ah0, g + GSTEP, 2 * it + 1, 1);
     }
 
     if constexpr (TEAMS > 1) {
         // (teams of one wave run without step barriers: all of them must have left their tiles before these are reused)
-        if constexpr (RW == 1) __syncthreads();
+        if constexpr (RW == 1 && !SHARE) __syncthreads();
         // the other teams hand their accumulators over through the (now free) activation tiles
         v4f *xchg = reinterpret_cast<v4f *>(lds + kLutBytes);
         if (team > 0) {
@@ -502,10 +518,10 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     }
 }
 
-template <int P, int NT, int TEAMS, int RW, bool PW = false>
+template <int P, int NT, int TEAMS, int RW, bool PW = false, bool SHARE = false>
 __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(NT <= 2 ? 4 : 1))) void dequant_mfma_kernel(DequantParams a)
 {
-    dequant_mfma_body<P, NT, TEAMS, RW, PW, false>(a, (int)blockIdx.y);
+    dequant_mfma_body<P, NT, TEAMS, RW, PW, false, SHARE>(a, (int)blockIdx.y);
 }
 
 // Per-request precision beyond 64 requests: byte blockIdx.y of class_order is the precision a workgroup serves, with
@@ -516,13 +532,13 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 // of every precision, which hold the work, go first, and the tiles nobody's rank reaches (each costs its
 // workgroup the ranking, and a CU holds one such workgroup at a time) trail behind instead of queueing in front
 // of the next precision's work.
-template <int Q, int NT, int TEAMS, int RW>
+template <int Q, int NT, int TEAMS, int RW, bool SHARE>
 __device__ __forceinline__ void serve_precision(DequantParams a)
 {
     if (!a.scale_sets[Q]) {
         // no scale set for this precision: its requests get zeros (the workgroup's rows of its tile of ranks)
         extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-        uint32_t *req_of = reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, TEAMS));
+        uint32_t *req_of = reinterpret_cast<uint32_t *>(lds + lds_bytes(NT, SHARE ? 1 : TEAMS));
         const int nreq = rank_requests<16 * NT>(a, Q, (int)blockIdx.z * (16 * NT), req_of);
         if (nreq <= 0) return;
         __syncthreads();
@@ -536,17 +552,17 @@ __device__ __forceinline__ void serve_precision(DequantParams a)
     a.scales = a.scale_sets[Q];
     a.has_offsets = a.offset_sets[Q] != nullptr;
     a.offsets = a.has_offsets ? a.offset_sets[Q] : a.scales;
-    dequant_mfma_body<Q, NT, TEAMS, RW, false, true>(a, (int)blockIdx.z);
+    dequant_mfma_body<Q, NT, TEAMS, RW, false, true, SHARE>(a, (int)blockIdx.z);
 }
 
-template <int NT, int TEAMS, int RW>
+template <int NT, int TEAMS, int RW, bool SHARE = false>
 __global__ __launch_bounds__(64 * RW * TEAMS) void dequant_byclass_kernel(DequantParams a)
 {
     switch ((a.class_order >> (8 * blockIdx.y)) & 0xffu) {
-    case 1: serve_precision<1, NT, TEAMS, RW>(a); break;
-    case 2: serve_precision<2, NT, TEAMS, RW>(a); break;
-    case 3: serve_precision<3, NT, TEAMS, RW>(a); break;
-    default: serve_precision<4, NT, TEAMS, RW>(a); break;
+    case 1: serve_precision<1, NT, TEAMS, RW, SHARE>(a); break;
+    case 2: serve_precision<2, NT, TEAMS, RW, SHARE>(a); break;
+    case 3: serve_precision<3, NT, TEAMS, RW, SHARE>(a); break;
+    default: serve_precision<4, NT, TEAMS, RW, SHARE>(a); break;
     }
 }
 
@@ -1156,28 +1172,30 @@ hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t 
     return hipGetLastError();
 }
 
-template <int P, int NT, int TEAMS, int RW, bool PW>
+template <int P, int NT, int TEAMS, int RW, bool PW, bool SHARE = false>
 hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
-    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW>;
-    if (lds_bytes(NT, TEAMS) > 64 * 1024) {
+    constexpr int LT = SHARE ? 1 : TEAMS;     // pairs of tiles in LDS
+    static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= LT * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
+    auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW, SHARE>;
+    if (lds_bytes(NT, LT) > 64 * 1024) {
         // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           lds_bytes(NT, TEAMS));
+                                           lds_bytes(NT, LT));
         if (e != hipSuccess) return e;
     }
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
-    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, TEAMS), stream, pr);
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, LT), stream, pr);
     return hipGetLastError();
 }
 
-template <int NT, int TEAMS, int RW>
+template <int NT, int TEAMS, int RW, bool SHARE = false>
 hipError_t launch_byclass(const DequantParams &pr, const GemmArgs &a, hipStream_t stream)
 {
-    static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
-    auto kernel = dequant_byclass_kernel<NT, TEAMS, RW>;
-    constexpr int kLds = lds_bytes(NT, TEAMS) + 16 * NT * 4;        // the workgroup's request numbers behind the tiles
+    constexpr int LT = SHARE ? 1 : TEAMS;
+    static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= LT * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
+    auto kernel = dequant_byclass_kernel<NT, TEAMS, RW, SHARE>;
+    constexpr int kLds = lds_bytes(NT, LT) + 16 * NT * 4;           // the workgroup's request numbers behind the tiles
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)a.p_max, (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
@@ -1193,10 +1211,12 @@ hipError_t launch_byclass(const DequantParams &pr, const GemmArgs &a, hipStream_
 // busy on short matrices; the 16-request tile saves matrix instructions and operand reads when the batch is
 // that small.  The cheapest product wins; dequant_mfma_force_shape overrides the choice (benchmarks, tests).
 struct WgShape {
-    int nt, rw;
+    int nt, rw;                 // rw: row-block code (1, 2, 4: that many blocks of 16 rows; 8 and 40: see below)
     float us_p4, us_p2;         // a grid far below one workgroup per CU
     float many_p4, many_p2;     // per workgroup and 256 workgroups of the grid when that is more (0: whole rounds of the above)
 };
+// blocks of 16 rows per workgroup for a shape's row-block code
+constexpr int row_blocks_of(int nt, int code) { return code == 40 ? 4 : code == 8 ? (nt <= 2 ? 1 : 8) : code; }
 // The 16- and 32-request shapes need 32 or 64 KiB of LDS and few registers, so several of their workgroups share a
 // CU and a grid beyond 256 workgroups costs less than whole rounds; they are used for a single tile only (two
 // such tiles never beat one 64-request tile).
@@ -1206,7 +1226,14 @@ constexpr WgShape kShapes[] = {{1, 4, 0.51f, 0.32f, 0.78f, 0.39f}, {1, 2, 0.36f,
                                // blocks and long rows (4096x14336 at 16 requests: 30 -> 20 us)
                                {1, 8, 0.25f, 0.22f, 0.172f, 0.115f}, {2, 8, 0.30f, 0.29f, 0.30f, 0.28f},
                                {4, 4, 0.82f, 0.54f, 0.f, 0.f},     {4, 2, 0.52f, 0.36f, 0.f, 0.f},      {4, 1, 0.45f, 0.37f, 0.f, 0.f},
-                               {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f}};
+                               {8, 4, 1.10f, 0.80f, 0.f, 0.f},     {8, 2, 0.85f, 0.70f, 0.f, 0.f},      {16, 4, 2.10f, 1.75f, 0.f, 0.f},
+                               // 256 requests with EIGHT waves on the tile instead of four (two per SIMD: one computes while the
+                               // other waits for its operands).  Code 40: 64 rows, two teams that share the tiles and split the
+                               // matrix sub-steps of every group (14336x4096 at 256 requests: 68 -> 57 us); code 8: 128 rows, one
+                               // wave per 16 rows, for matrices that still fill the chip then (28672x8192: 254 -> 191 us).
+                               {16, 40, 1.78f, 1.49f, 0.f, 0.f},   {16, 8, 2.95f, 2.42f, 0.f, 0.f},
+                               // (128 requests and 128 rows the same way: 28672x8192 at 128 requests 139 -> 129 us)
+                               {8, 8, 2.01f, 1.48f, 0.f, 0.f}};
 
 // the cheapest shape for `batch` requests at precision p, among the shapes of at least min_nt tiles; `times`: that
 // many such problems in one launch
@@ -1216,7 +1243,7 @@ void cheapest_shape(int p, int64_t m, int batch, int min_nt, int &nt, int &rw, i
     float best = 0.f;
     for (const WgShape &c : kShapes) {
         if (c.nt < min_nt || (c.nt <= 2 && batch > 16 * c.nt)) continue;
-        const int blocks = c.rw == 8 ? 1 : c.rw;        // (code 8: one row block, eight teams)
+        const int blocks = row_blocks_of(c.nt, c.rw);
         const float wgs = (float)((m + 16 * blocks - 1) / (16 * blocks)) * (float)((batch + 16 * c.nt - 1) / (16 * c.nt)) * (float)times;
         const float one = p >= 3 ? c.us_p4 : c.us_p2, many = p >= 3 ? c.many_p4 : c.many_p2;
         float cost = one;
@@ -1248,6 +1275,9 @@ hipError_t launch_classes(const DequantParams &pr, const GemmArgs &a, int expect
     case 84: return launch_byclass<8, 2, 4>(pr, a, stream);
     case 82: return launch_byclass<8, 2, 2>(pr, a, stream);
     case 164: return launch_byclass<16, 1, 4>(pr, a, stream);
+    case 168: return launch_byclass<16, 1, 8>(pr, a, stream);
+    case 88: return launch_byclass<8, 1, 8>(pr, a, stream);
+    case 200: return launch_byclass<16, 2, 4, true>(pr, a, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -1276,6 +1306,11 @@ hipError_t launch_p(const DequantParams &pr, const GemmArgs &a, hipStream_t stre
     case 84: return launch_one<P, 8, 2, 4, PW>(pr, a, stream);
     case 82: return launch_one<P, 8, 2, 2, PW>(pr, a, stream);
     case 164: return launch_one<P, 16, 1, 4, PW>(pr, a, stream);
+    case 168: return launch_one<P, 16, 1, 8, PW>(pr, a, stream);
+    case 88: return launch_one<P, 8, 1, 8, PW>(pr, a, stream);
+    case 200:       // (16 tiles, code 40: two teams on shared tiles)
+        if constexpr (!PW) return launch_one<P, 16, 2, 4, false, true>(pr, a, stream);
+        else return launch_one<P, 16, 1, 4, true>(pr, a, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -1292,8 +1327,8 @@ bool dequant_mfma_force_shape(int request_tiles, int row_blocks)
     const int nt = request_tiles == 0 ? 1 : request_tiles == 32 ? 2 : 4 * request_tiles;      // 32: a tile of 32 requests
     const int key = nt * 10 + row_blocks;
     const bool known = key == 14 || key == 12 || key == 11 || key == 24 || key == 22 || key == 21 || key == 44 || key == 42 || key == 41 ||
-                       key == 84 || key == 82 || key == 164 || key == 18 || key == 28;
-    if (!known || request_tiles < 0 || (row_blocks != 1 && row_blocks != 2 && row_blocks != 4 && row_blocks != 8)) return false;
+                       key == 84 || key == 82 || key == 164 || key == 18 || key == 28 || key == 168 || key == 200 || key == 88;
+    if (!known || request_tiles < 0 || (row_blocks != 1 && row_blocks != 2 && row_blocks != 4 && row_blocks != 8 && row_blocks != 40)) return false;
     g_forced_nt = nt;
     g_forced_rw = row_blocks;
     return true;

@@ -134,6 +134,10 @@ def test_argument_validation_without_device(lib):
     assert lib.bcq_select_dequant_shape(32, 2) == 0
     assert lib.bcq_select_dequant_shape(0, 8) == 0
     assert lib.bcq_select_dequant_shape(1, 8) == -6
+    assert lib.bcq_select_dequant_shape(4, 40) == 0
+    assert lib.bcq_select_dequant_shape(4, 8) == 0
+    assert lib.bcq_select_dequant_shape(2, 8) == 0
+    assert lib.bcq_select_dequant_shape(2, 40) == -6
     assert lib.bcq_select_dequant_shape(16, 2) == -6
     assert lib.bcq_select_dequant_shape(0, 3) == -6
     assert lib.bcq_select_dequant_shape(-1, 4) == -6

@@ -120,7 +120,7 @@ def test_dequant_mfma_uniform(gpu, m, n, kernel):
 
 
 @pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])
-@pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "0,8", "32,4", "32,2", "32,1", "32,8", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4"])
+@pytest.mark.parametrize("shape", ["0,4", "0,2", "0,1", "0,8", "32,4", "32,2", "32,1", "32,8", "1,4", "1,2", "1,1", "2,4", "2,2", "4,4", "4,8", "4,40", "2,8"])
 def test_dequant_mfma_every_workgroup_shape(gpu, shape, forced_shape, kernel):
     """The kernel picks its workgroup shape (request tiles, row blocks) from m and the batch; small test
     matrices would only ever see one of them, so each is forced here (ragged rows, ragged request tiles;
@@ -258,7 +258,7 @@ def test_dequant_mfma_mixed_clamps_and_missing_sets(gpu, kernel):
     assert torch.all(y_some[is3] == 0) and torch.equal(y_some[~is3], y_ok[~is3])
 
 
-@pytest.mark.parametrize("shape", ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4", None])
+@pytest.mark.parametrize("shape", ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4", "4,8", "4,40", "2,8", None])
 def test_per_request_precision_one_launch_per_precision(gpu, shape, forced_shape):
     """Beyond 64 requests `dequant_mfma` serves a batch with per-request precision by one launch of the uniform
     kernel per precision, each workgroup picking the requests of that precision out of the batch by rank:
@@ -525,7 +525,7 @@ def test_seeded_random_cases_against_the_oracle(gpu):
 
     import paper_2510_10467_amd as bcq
     rng = np.random.default_rng([syn.BASE_SEED, 910])
-    shapes = ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4", None, None, None]
+    shapes = ["1,4", "1,2", "1,1", "2,4", "2,2", "4,4", "4,8", "4,40", None, None, None, None]
     done = 0
     while done < 80:
         m = int(rng.choice([16, 37, 100, 150, 260, 700, 1100, 4100, 8200]))

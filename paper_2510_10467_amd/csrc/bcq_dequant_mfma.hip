@@ -42,7 +42,9 @@
 // activation tiles and accumulators of its own; the teams meet at every barrier and add their
 // accumulators through LDS at the end.  The activation tiles fill the LDS, so a CU runs one workgroup at a
 // time and a short matrix needs small row blocks (RW < 4) to give every CU one; the host picks the shape
-// from measured per-shape costs (launch_p).
+// from measured per-shape costs (cheapest_shape).  A tile of 256 requests leaves LDS for one pair of tiles:
+// its second wave per SIMD comes either from eight row blocks (RW = 8) or from two teams that SHARE the
+// tiles, work on every group together and split its four matrix sub-steps (SHARE).
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -59,7 +61,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxP = 4;
-constexpr int kClassFrom = 64;              // per-request precision: beyond this many requests one launch per precision
+constexpr int kClassFrom = 64;              // per-request precision: beyond this many requests the uniform kernel's body per precision
 int g_forced_nt = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2;         // LDS row of one request's 128 activations; its sixteen parts sit XOR-permuted

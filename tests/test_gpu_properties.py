@@ -37,7 +37,9 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
     dl = gpu.DeviceLayer(layer)
     rng = np.random.default_rng([syn.BASE_SEED, 200, m])
     rows = np.unique(np.concatenate([[0, 15, 16, m - 17, m - 1], rng.integers(0, m, size=120)]))
-    batches = (1, 3, 16, 80, 256) if name in ("gate_proj", "llama70b_down", "q_proj") else (1, 3, 16, 80)
+    # (256 and 512 requests: the shapes with eight waves on a 256-request tile, 64 rows on gate_proj at 256, 128 rows otherwise)
+    batches = {"gate_proj": (1, 3, 16, 80, 256, 512), "llama70b_down": (1, 3, 16, 80, 256), "q_proj": (1, 3, 16, 80, 256),
+               "llama70b_up": (1, 3, 16, 80, 256)}.get(name, (1, 3, 16, 80))
     for batch in batches:
         x = syn.make_x(batch, n, seed=(200, batch))
         xd = gpu.to_dev(x)
@@ -104,7 +106,7 @@ def test_one_hot_readout_and_symmetries(gpu, oracle):
             bcq.select_kernel("auto")
 
 
-@pytest.mark.parametrize("m,n,batch", [(14336, 4096, 16), (14336, 4096, 96), (4096, 14336, 200)])
+@pytest.mark.parametrize("m,n,batch", [(14336, 4096, 16), (14336, 4096, 96), (4096, 14336, 200), (14336, 4096, 400)])
 def test_full_size_mixed_precision_sampled_rows(gpu, oracle, m, n, batch):
     """Per-request precision at the benchmark's shapes: the paper-sized batch on the plane-wise fp16 kernel,
     serving-sized ones on the dequantising kernel."""
@@ -117,7 +119,7 @@ def test_full_size_mixed_precision_sampled_rows(gpu, oracle, m, n, batch):
     p_req = syn.make_p_req(batch, 2, 4, seed=(231, batch))
     y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req), gpu.to_dev(x))
     torch.cuda.synchronize()
-    assert bcq.last_kernel() == {16: "plane_f16", 96: "dequant_mfma", 200: "dequant_mfma"}[batch]
+    assert bcq.last_kernel() == {16: "plane_f16", 96: "dequant_mfma", 200: "dequant_mfma", 400: "dequant_mfma"}[batch]
     rng = np.random.default_rng([syn.BASE_SEED, 231, m])
     rows = np.unique(np.concatenate([[0, 15, 16, m - 1], rng.integers(0, m, size=60)]))
     sub = {p: np.ascontiguousarray(s[:, rows, :]) for p, s in layer.scales.items()}

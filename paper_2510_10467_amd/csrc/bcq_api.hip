@@ -39,12 +39,12 @@ int choose(const bcq::GemmArgs &a)
         bool tiles16 = f16_ok && a.batch <= 32;                 // one tile of 16 or 32 requests
         // Per-request precision: the plane-wise fp16 variant works in tiles of 16 requests whatever mix of
         // precisions they hold (from 9 requests on); rebuilding the weights
-        // once per precision present takes over from 49 requests (8192 rows and more) or 97 on, and from 28 / 40
-        // requests where the fp16 variant cannot run (beyond 64 requests as one launch of the uniform kernel per
-        // precision, see dequant_mfma_launch).
+        // takes over from 65 requests (8192 rows and more) or 97 on, as one launch of the uniform kernel's body per
+        // precision (see dequant_mfma_launch), and from 28 / 40 requests where the fp16 variant cannot run (up to 64
+        // requests rebuilt once per precision present).
         if (a.uniform_p == 0) {
             from = f16_ok ? 9 : (a.m >= 8192 ? 28 : 40);
-            tiles16 = f16_ok && a.batch <= (a.m >= 8192 ? 48 : 96);
+            tiles16 = f16_ok && a.batch <= (a.m >= 8192 ? 64 : 96);
         }
         bool pays = a.m >= 4096 && a.batch >= from;
         // Shorter matrices give the large-batch kernel few workgroups, but the FP4 kernel's time still grows with

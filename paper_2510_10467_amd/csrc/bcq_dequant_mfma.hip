@@ -56,6 +56,7 @@ namespace {
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -901,14 +902,20 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
     }
     // This lane's own requests: accumulator u, register k holds request 16u + 4kq + k.  The scales of a plane
     // travel as four binary16 values in two registers (sets 1 | 2 and 3 | 4); `pick` is the byte selector that
-    // moves the value of the request's precision into the low half (a precision of 0 selects zero bytes).
-    uint32_t pick[NT][4];
+    // moves the values of TWO requests' precisions into the two halves of a register (a precision of 0 selects
+    // zero bytes), from which the fused multiply-adds take them without a conversion of their own.
+    uint32_t pick[NT][2];
 #pragma unroll
     for (int u = 0; u < NT; ++u)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int pq = __shfl(p_lane, 16 * u + 4 * kq + k);
-            pick[u][k] = pq == 0 ? 0x0C0C0C0Cu : 0x0C0C0000u | (uint32_t)((2 * pq - 1) << 8) | (uint32_t)(2 * pq - 2);
+        for (int k2 = 0; k2 < 2; ++k2) {
+            uint32_t sel = 0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int pq = __shfl(p_lane, 16 * u + 4 * kq + 2 * k2 + h);
+                sel |= (pq == 0 ? 0x0C0Cu : (uint32_t)((2 * pq - 1) << 8) | (uint32_t)(2 * pq - 2)) << (16 * h);
+            }
+            pick[u][k2] = sel;
         }
 
     const unsigned char *const set1 = a.scale_sets[1], *const set2 = a.scale_sets[2], *const set3 = a.scale_sets[3],
@@ -998,8 +1005,8 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
             for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
             // (scales of a precision no request of the tile has were never fetched: they are still zero)
-            auto own_value = [](uint32_t hi, uint32_t lo, uint32_t sel) {
-                return (float)__builtin_bit_cast(_Float16, (unsigned short)__builtin_amdgcn_perm(hi, lo, sel));
+            auto own_values = [](uint32_t hi, uint32_t lo, uint32_t sel) {       // of requests 2 k2 and 2 k2 + 1
+                return __builtin_bit_cast(h2v, __builtin_amdgcn_perm(hi, lo, sel));
             };
             uint32_t w[kMaxP], s_lo[kMaxP], s_hi[kMaxP];
 #pragma unroll
@@ -1029,7 +1036,7 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
                 if (i < PH) asm volatile("" : "+v"(lo8[i]), "+v"(hi8[i]));
             }
             // scale of plane i for the request in (u, k): that of the request's own precision, zero from plane p on
-            auto own_scale = [&](int i, int u, int k) { return own_value(s_hi[i], s_lo[i], pick[u][k]); };
+            auto own_scales = [&](int i, int u, int k2) { return own_values(s_hi[i], s_lo[i], pick[u][k2]); };
             constexpr int NPASS = kMaxP / PP;
 #pragma unroll
             for (int pass = 0; pass < NPASS; ++pass) {
@@ -1068,7 +1075,11 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
                             for (int u = 0; u < NT; ++u)
 #pragma unroll
-                                for (int k = 0; k < 4; ++k) acc[u][k] = fmaf(own_scale(pass * PP + ii, u, k), tmp[ii][u][k], acc[u][k]);
+                                for (int k2 = 0; k2 < 2; ++k2) {
+                                    const h2v al = own_scales(pass * PP + ii, u, k2);
+                                    acc[u][2 * k2] = fmaf((float)al[0], tmp[ii][u][2 * k2], acc[u][2 * k2]);
+                                    acc[u][2 * k2 + 1] = fmaf((float)al[1], tmp[ii][u][2 * k2 + 1], acc[u][2 * k2 + 1]);
+                                }
                         }
                 }
             }
@@ -1087,7 +1098,11 @@ __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
                 for (int u = 0; u < NT; ++u)
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) acc[u][k] = fmaf(own_value(z_hi, z_lo, pick[u][k]), tz[u][k], acc[u][k]);
+                    for (int k2 = 0; k2 < 2; ++k2) {
+                        const h2v zz = own_values(z_hi, z_lo, pick[u][k2]);
+                        acc[u][2 * k2] = fmaf((float)zz[0], tz[u][2 * k2], acc[u][2 * k2]);
+                        acc[u][2 * k2 + 1] = fmaf((float)zz[1], tz[u][2 * k2 + 1], acc[u][2 * k2 + 1]);
+                    }
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): what was staged for the next step has landed in LDS

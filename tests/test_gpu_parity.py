@@ -370,7 +370,9 @@ def test_auto_dispatch_by_batch(gpu):
     assert used == "plane_f16"
     used, _ = gpu.check_mixed(tall, p_req[:30], syn.make_x(30, 1024, seed=(172, 3)), "auto")
     assert used == "plane_f16"
-    used, _ = gpu.check_mixed(tall, p_many[:49], syn.make_x(49, 1024, seed=(172, 7)), "auto")
+    used, _ = gpu.check_mixed(tall, p_many[:64], syn.make_x(64, 1024, seed=(172, 7)), "auto")    # tiles of 32 requests up to 64
+    assert used == "plane_f16"
+    used, _ = gpu.check_mixed(tall, p_many[:65], syn.make_x(65, 1024, seed=(172, 9)), "auto")    # beyond: one pass per precision
     assert used == "dequant_mfma"
     used, _ = gpu.check_mixed(tall, p_req[:8], syn.make_x(8, 1024, seed=(172, 8)), "auto")
     assert used == "plane_mfma"

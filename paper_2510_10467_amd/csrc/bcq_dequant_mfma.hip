@@ -218,7 +218,8 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     auto scale_col = [&](int g) { return (uint32_t)(a.gshift > 0 ? (g >> 1) * 2 : a.gshift < 0 ? g * 4 : g * 2); };
     const int pull = (4 * n16 + kq) * 4;      // byte index of the lane to take from
     const int pull_row = 4 * n16 * 4;         // first of the four lanes that hold the scales of row n16
-    const uint32_t half_shift = a.gshift < 0 && kq >= 2 ? 16u : 0u;      // groups of 64: columns 64..127 of a step use the upper scale
+    // groups of 64: columns 64..127 of a step use the upper scale (the plane-wise variant has no groups of 64: no shift at all)
+    const uint32_t half_shift = !PW && a.gshift < 0 && kq >= 2 ? 16u : 0u;
     uint32_t sc[P], zc = 0;                   // this lane's share of the scales in flight / in use (binary16 bits)
     auto fetch_scales = [&](int block) {      // for the team's steps 4 block .. 4 block + 3
         const int gj = min(g_first + GSTEP * (4 * block + (lane & 3)), a.ngroups - 1);
@@ -302,14 +303,16 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
 #pragma unroll
         for (int k = 0; k < XU; ++k) asm volatile("" : "+v"(xs_src[k]));
         const int pull_scale = pull_row + (mine & 3) * 4;       // the lane that fetched this step's scales of row n16
-        const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)zc) >> half_shift;
+        uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)zc);
+        if constexpr (!PW) zb >>= half_shift;
         const float z = a.has_offsets ? (float)__builtin_bit_cast(_Float16, (unsigned short)zb) : 0.f;
         uint32_t w[P];
         float alpha[P];
 #pragma unroll
         for (int i = 0; i < P; ++i) {
             w[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(pull, (int)cur.w[i]);
-            const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)sc[i]) >> half_shift;
+            uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_scale, (int)sc[i]);
+            if constexpr (!PW) ab >>= half_shift;
             alpha[i] = (float)__builtin_bit_cast(_Float16, (unsigned short)ab);
         }
         // the scales of the next four steps, once the last of these four has handed its own over

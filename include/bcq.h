@@ -173,8 +173,12 @@ int bcq_gemm_mixed_offset(const uint32_t *planes, const bcq_half *const *scales_
  * bcq_gemv_multi -- several weight matrices applied to the SAME activations at
  * the same precision in one call (the q/k/v and the gate/up projections of a
  * decoder layer; section 4.4 measures whole decoding steps made of such layers).
- * Equivalent to `count` calls of bcq_gemv, bit for bit, but small-batch
- * problems run as a single kernel launch.
+ * Equivalent to `count` calls of bcq_gemv, but as a single kernel launch
+ * where one kernel family serves the matrices taken together: bit for bit
+ * the results of separate calls at small batches (up to 8 requests); at
+ * larger batches the workgroup shape, and with it the order of the fp32
+ * sums, is chosen for the sum of the rows, so results agree with separate
+ * calls within the accuracy both are held to, not bit for bit.
  *   count      1 .. BCQ_MAX_MULTI
  *   planes     HOST array of `count` device pointers, matrix k: [>= p][m[k]][n/32]
  *   scales_p   HOST array of `count` device pointers, matrix k: [p][m[k]][n/group]

@@ -253,6 +253,19 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
         g_last = "plane_mfma";
         return bcq::plane_mfma_launch_multi(mats, count, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
     }
+    // larger batches: one launch of the large-batch kernels when the matrices taken together (one matrix of all their
+    // rows) would run there; k and v projections of 1024 rows are too short for those kernels on their own
+    if (count > 1 && bcq::dequant_mfma_supports_multi(mats, count)) {
+        bcq::GemmArgs all = mats[0];
+        all.m = 0;
+        for (int k = 0; k < count; ++k) all.m += mats[k].m;
+        const int c = choose(all);
+        if ((c == BCQ_KERNEL_PLANE_F16 && group >= 128) || c == BCQ_KERNEL_DEQUANT_MFMA) {
+            g_last = c == BCQ_KERNEL_PLANE_F16 ? "plane_f16" : "dequant_mfma";
+            return bcq::dequant_mfma_launch_multi(mats, count, static_cast<hipStream_t>(stream), c == BCQ_KERNEL_PLANE_F16) == hipSuccess
+                       ? BCQ_OK : BCQ_ERR_HIP;
+        }
+    }
     for (int k = 0; k < count; ++k)
         if (int rc = run(mats[k], static_cast<hipStream_t>(stream))) return rc;
     return BCQ_OK;

@@ -98,6 +98,14 @@ struct DequantParams {
     const int32_t *p_req;
     int p_max;
     uint32_t class_order;                   // dequant_byclass_kernel: byte y = the precision served by the workgroups with blockIdx.y = y
+    // several matrices with the same n, precision and activations in one launch (nmat > 1): matrix k owns the workgroup
+    // rows mat_blk0[k] .. mat_blk0[k+1]-1 of the grid; unused entries hold the total
+    int nmat;
+    const unsigned char *mat_planes[BCQ_MAX_MULTI];
+    const unsigned char *mat_scales[BCQ_MAX_MULTI];
+    _Float16 *mat_y[BCQ_MAX_MULTI];
+    uint32_t mat_m[BCQ_MAX_MULTI];
+    uint32_t mat_blk0[BCQ_MAX_MULTI];
 };
 
 // What a thread fetches one group ahead into registers: the plane words of its row (its share of the next
@@ -156,7 +164,7 @@ __device__ __forceinline__ int rank_requests(const DequantParams &a, const int q
 //   256-request tiles then fit the LDS once instead of TEAMS times, so that a CU holds eight waves on a 256-request
 //   tile (two per SIMD, one computing while the other waits for its operands) instead of four.
 template <int P, int NT, int TEAMS, int RW, bool PW = false, bool BYCLASS = false, bool SHARE = false>
-__device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const int column)
+__device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const int column, const uint32_t rowblk)
 {
     constexpr int kTeamThreads = 64 * RW;
     static_assert(!(SHARE && PW), "the plane-wise variant has no shared-tile form");
@@ -181,7 +189,7 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
     constexpr int kTile = x_tile_bytes(NT);
     const int n16 = lane & 15;                // weight row inside the wave's block / request inside a 16-request tile
     const int kq = lane >> 4;                 // K quarter: columns 32kq + 8t .. 32kq + 8t + 7 of the group in step t
-    const uint32_t row0 = blockIdx.x * (16 * RW) + wave * 16;
+    const uint32_t row0 = rowblk * (16 * RW) + wave * 16;
     const int b0 = column * (16 * NT);        // first request of the workgroup (BYCLASS: first rank)
 
     int nreq = a.batch - b0;                  // requests from b0 on (may be more than the workgroup's 16 NT)
@@ -527,7 +535,23 @@ __device__ __forceinline__ void dequant_mfma_body(const DequantParams &a, const 
 template <int P, int NT, int TEAMS, int RW, bool PW = false, bool SHARE = false>
 __global__ __launch_bounds__(64 * RW * TEAMS) __attribute__((amdgpu_waves_per_eu(NT <= 2 ? 4 : 1))) void dequant_mfma_kernel(DequantParams a)
 {
-    dequant_mfma_body<P, NT, TEAMS, RW, PW, false, SHARE>(a, (int)blockIdx.y);
+    if (a.nmat > 1) {
+        // which matrix this row of workgroups belongs to, picked by comparison (no indexing of the arguments)
+        static_assert(BCQ_MAX_MULTI == 4, "the selection below is written for four matrices");
+        uint32_t wg = blockIdx.x;
+        const bool g1 = wg >= a.mat_blk0[1], g2 = wg >= a.mat_blk0[2], g3 = wg >= a.mat_blk0[3];
+        a.planes = g3 ? a.mat_planes[3] : g2 ? a.mat_planes[2] : g1 ? a.mat_planes[1] : a.mat_planes[0];
+        a.scales = g3 ? a.mat_scales[3] : g2 ? a.mat_scales[2] : g1 ? a.mat_scales[1] : a.mat_scales[0];
+        a.offsets = a.scales;
+        a.y = g3 ? a.mat_y[3] : g2 ? a.mat_y[2] : g1 ? a.mat_y[1] : a.mat_y[0];
+        a.m = g3 ? a.mat_m[3] : g2 ? a.mat_m[2] : g1 ? a.mat_m[1] : a.mat_m[0];
+        wg -= g3 ? a.mat_blk0[3] : g2 ? a.mat_blk0[2] : g1 ? a.mat_blk0[1] : 0u;
+        a.plane_stride = a.m * a.row_stride;
+        a.scale_plane_stride = a.m * a.scale_row_stride;
+        dequant_mfma_body<P, NT, TEAMS, RW, PW, false, SHARE>(a, (int)blockIdx.y, wg);
+        return;
+    }
+    dequant_mfma_body<P, NT, TEAMS, RW, PW, false, SHARE>(a, (int)blockIdx.y, blockIdx.x);
 }
 
 // Per-request precision beyond 64 requests: byte blockIdx.y of class_order is the precision a workgroup serves, with
@@ -558,7 +582,7 @@ __device__ __forceinline__ void serve_precision(DequantParams a)
     a.scales = a.scale_sets[Q];
     a.has_offsets = a.offset_sets[Q] != nullptr;
     a.offsets = a.has_offsets ? a.offset_sets[Q] : a.scales;
-    dequant_mfma_body<Q, NT, TEAMS, RW, false, true, SHARE>(a, (int)blockIdx.z);
+    dequant_mfma_body<Q, NT, TEAMS, RW, false, true, SHARE>(a, (int)blockIdx.z, blockIdx.x);
 }
 
 template <int NT, int TEAMS, int RW, bool SHARE = false>
@@ -1205,6 +1229,20 @@ hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t st
         if (e != hipSuccess) return e;
     }
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
+    if (pr.nmat > 1) {
+        // several matrices: every matrix gets whole workgroups (pr.mat_m holds the row counts; the offsets are made here
+        // because they depend on the rows per workgroup)
+        DequantParams pm = pr;
+        uint32_t blk = 0;
+        for (int k = 0; k < BCQ_MAX_MULTI; ++k) {
+            pm.mat_blk0[k] = blk;
+            if (k < pr.nmat) blk += (pr.mat_m[k] + 16 * RW - 1) / (16 * RW);
+        }
+        for (int k = pr.nmat; k < BCQ_MAX_MULTI; ++k) pm.mat_blk0[k] = blk;     // never reached
+        grid.x = blk;
+        hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, LT), stream, pm);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, LT), stream, pr);
     return hipGetLastError();
 }
@@ -1364,7 +1402,31 @@ bool dequant_mfma_supports(const GemmArgs &a)
     return p_ok && group_ok && small_enough && (a.batch + 15) / 16 <= 65535 && (a.m + 15) / 16 < (int64_t(1) << 31);
 }
 
-hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool planewise)
+// Several matrices (same n, precision, batch, activations and group size, no offsets) as one launch: the grid's rows of
+// workgroups are the concatenation of theirs, the shape is chosen for the sum of their rows.
+bool dequant_mfma_supports_multi(const GemmArgs *mats, int count)
+{
+    if (count < 2 || count > BCQ_MAX_MULTI) return false;
+    int64_t rows = 0;
+    for (int k = 0; k < count; ++k) {
+        const GemmArgs &a = mats[k];
+        if (!dequant_mfma_supports(a) || a.uniform_p < 1 || a.offsets[a.uniform_p]) return false;
+        if (a.n != mats[0].n || a.uniform_p != mats[0].uniform_p || a.batch != mats[0].batch || a.x != mats[0].x || a.group != mats[0].group)
+            return false;
+        rows += a.m;
+    }
+    return (rows + 15) / 16 + count < (int64_t(1) << 31);
+}
+
+hipError_t dequant_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t stream, bool planewise)
+{
+    GemmArgs all = mats[0];
+    all.m = 0;
+    for (int k = 0; k < count; ++k) all.m += mats[k].m;
+    return dequant_mfma_launch(all, stream, planewise, mats, count);
+}
+
+hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool planewise, const GemmArgs *mats, int count)
 {
     DequantParams pr{};
     pr.planes = reinterpret_cast<const unsigned char *>(a.planes);
@@ -1458,6 +1520,16 @@ hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool plane
         }
         if (g_forced_nt > 0) rw = g_forced_rw;
         return rw == 4 ? launch_mixed<2, 4>(pr, a, stream) : rw == 2 ? launch_mixed<2, 2>(pr, a, stream) : launch_mixed<4, 1>(pr, a, stream);
+    }
+    if (mats && count > 1) {
+        // (a: the matrices taken together, for the choice of the shape; each keeps its own rows, planes, scales and results)
+        pr.nmat = count;
+        for (int k = 0; k < count; ++k) {
+            pr.mat_planes[k] = reinterpret_cast<const unsigned char *>(mats[k].planes);
+            pr.mat_scales[k] = reinterpret_cast<const unsigned char *>(mats[k].scales[a.uniform_p]);
+            pr.mat_y[k] = mats[k].y;
+            pr.mat_m[k] = (uint32_t)mats[k].m;
+        }
     }
     pr.scales = reinterpret_cast<const unsigned char *>(a.scales[a.uniform_p]);
     pr.has_offsets = a.offsets[a.uniform_p] != nullptr;

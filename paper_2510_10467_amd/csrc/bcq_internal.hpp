@@ -52,7 +52,10 @@ bool dequant_mfma_supports(const GemmArgs &a);
 // benchmarks and tests: force the workgroup shape (request tiles of 64, or 0 for one tile of 16; blocks of 16 rows); (0, 0) = automatic
 bool dequant_mfma_force_shape(int request_tiles, int row_blocks);
 // planewise: the variant that multiplies the +-1 planes themselves and scales the group sums (groups of 128 or 256)
-hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool planewise = false);
+hipError_t dequant_mfma_launch(const GemmArgs &a, hipStream_t stream, bool planewise = false, const GemmArgs *mats = nullptr, int count = 0);
+// several matrices (same n, precision, batch, activations, group size; no offsets) in one launch of the large-batch kernels
+bool dequant_mfma_supports_multi(const GemmArgs *mats, int count);
+hipError_t dequant_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t stream, bool planewise);
 
 // Offline quantiser (Algorithm 1): group must be 32, 64, 128 or 256; 1 <= p_low <= p_high <= 4.
 bool quantize_supports(int64_t m, int64_t n, int group);

@@ -464,6 +464,45 @@ def test_gemv_multi_equals_separate_calls(gpu, oracle, ms, n):
                 assert torch.equal(y, bcq.bcq_gemv(d.planes, d.scales[p], p, x)), "multi differs from the separate call"
 
 
+@pytest.mark.parametrize("kernel", ["auto", "dequant_mfma", "plane_f16"])
+def test_gemv_multi_on_the_large_batch_kernels(gpu, oracle, kernel, forced_shape):
+    """Beyond the first kernel's batches the matrices of a multi call run as ONE launch of the large-batch kernels
+    (the rows of workgroups of all matrices side by side, the shape chosen for the sum of their rows): ragged
+    row counts, two to four matrices, matrices too short for those kernels on their own, every family forced
+    and the automatic choice, a forced workgroup shape of every kind."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    n = 1536
+    for ms, shape in (((4096, 1024, 1000), None), ((150, 70), "1,4"), ((150, 70, 33, 260), "0,1"), ((100, 300), "4,40"), ((4100, 90), "32,8")):
+        if shape and kernel == "auto":
+            continue
+        if shape and kernel == "plane_f16" and not shape.startswith(("0,", "32,")):
+            continue
+        if shape and kernel == "dequant_mfma" and shape.startswith(("0,", "32,")):
+            continue
+        layers = [syn.make_layer(m, n, seed=(192, k, m), signed=True) for k, m in enumerate(ms)]
+        dls = [gpu.DeviceLayer(layer) for layer in layers]
+        if shape:
+            forced_shape(shape)
+        for batch in ((20, 70) if kernel != "plane_f16" else (12, 30)):
+            xh = syn.make_x(batch, n, seed=(192, batch))
+            x = gpu.to_dev(xh)
+            for p in (2, 4):
+                bcq.select_kernel(kernel)
+                try:
+                    ys = bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[p] for d in dls], p, x)
+                    torch.cuda.synchronize()
+                    used = bcq.last_kernel()
+                finally:
+                    bcq.select_kernel("auto")
+                assert used == (kernel if kernel != "auto" else ("plane_f16" if batch <= 32 else "dequant_mfma")), used
+                for d, y in zip(dls, ys):
+                    y_ref, a_ref = oracle.gemv(d.layer.planes, d.layer.scales[p], xh)
+                    gpu.assert_within_tolerance(y, y_ref, a_ref, f"bcq_gemv_multi[{kernel}] ms={ms} shape={shape} p={p} batch={batch}")
+        bcq.select_dequant_shape(0, 0)
+
+
 def test_gemv_multi_falls_back_to_separate_launches(gpu, oracle):
     import torch
 

@@ -164,16 +164,16 @@ def run_suite(args, torch, bcq, syn, dev):
         for (_, m, n) in syn.PHI4_14B_SHAPES:
             bench_shape(m, n, (1,), PRECISIONS)
     elif args.suite == "fused":
-        # The linear layers of one Llama-3-8B decoder layer, batch 1: seven bcq_gemv calls against four
+        # The linear layers of one Llama-3-8B decoder layer, batches 1, 16 and 64: seven bcq_gemv calls against four
         # calls in which q/k/v and gate/up (same activations) go through bcq_gemv_multi as one launch each.
         shapes = {"q": (4096, 4096), "k": (1024, 4096), "v": (1024, 4096), "o": (4096, 4096),
                   "gate": (14336, 4096), "up": (14336, 4096), "down": (4096, 14336)}
         copies = 8                                                   # 8 x 218 MB of planes: cold for the last-level cache
         sets = [{name: device_layer(m, n) for name, (m, n) in shapes.items()} for _ in range(copies)]
-        x4k = torch.randn((1, 4096), device=dev, generator=gen).half()
-        x14k = torch.randn((1, 14336), device=dev, generator=gen).half()
-        ys = {name: torch.empty((1, m), dtype=torch.float16, device=dev) for name, (m, n) in shapes.items()}
-        for p in PRECISIONS:
+        for batch, p in [(b, q) for b in (1, 16, 64) for q in PRECISIONS]:
+            x4k = torch.randn((batch, 4096), device=dev, generator=gen).half()
+            x14k = torch.randn((batch, 14336), device=dev, generator=gen).half()
+            ys = {name: torch.empty((batch, m), dtype=torch.float16, device=dev) for name, (m, n) in shapes.items()}
             def separate():
                 for c in range(copies):
                     L = sets[c]
@@ -190,10 +190,10 @@ def run_suite(args, torch, bcq, syn, dev):
                     bcq.bcq_gemv_multi([L[k][0] for k in ("gate", "up")], [L[k][1][p] for k in ("gate", "up")], p, x4k,
                                        [ys[k] for k in ("gate", "up")])
                     bcq.bcq_gemv(L["down"][0], L["down"][1][p], p, x14k, ys["down"])
-            by = sum(syn.algorithmic_bytes(m, n, p, 1) for (m, n) in shapes.values())
+            by = sum(syn.algorithmic_bytes(m, n, p, batch) for (m, n) in shapes.values())
             us_sep = timed_graph(separate) * 1e3 / copies
             us_fus = timed_graph(fused) * 1e3 / copies
-            rows.append({"workload": "linear layers of one Llama-3-8B decoder layer, batch 1", "p": p,
+            rows.append({"workload": f"linear layers of one Llama-3-8B decoder layer, batch {batch}", "p": p, "batch": batch,
                          "seven_calls_us": round(us_sep, 2), "four_calls_us": round(us_fus, 2),
                          "seven_calls_GBps": round(by / us_sep / 1e3, 1), "four_calls_GBps": round(by / us_fus / 1e3, 1),
                          "pct_of_hbm_peak_four_calls": round(100 * by / us_fus / 1e3 / HBM_PEAK_GBS, 2)})

@@ -11,8 +11,11 @@
 //     operand register, three of them after a shift.  Which bit lands in which
 //     K slot is a fixed permutation, mirrored on the activation side.
 //   * activation operand (MFMA "A", 16 rows): binary16 activations are split
-//     EXACTLY into four E5M2 terms (E5M2 is the top byte of binary16, so
-//     x = t0 + t1 + t2 + t3 with t_k = top byte of the running remainder).  Row
+//     EXACTLY, over the whole binary16 range, into four E5M2 terms (E5M2 is the
+//     top byte of binary16: t_k = top byte of the running remainder, which is
+//     scaled up by 4, 8, 8 between the terms so that the low bits of small
+//     values stay above the 2^-16 spacing of E5M2 subnormals;
+//     x = t0 + t1/4 + t2/32 + t3/256).  Row
 //     4*b + k of the operand holds term k of request b, so one instruction
 //     serves up to four requests.  The split is done once per workgroup and
 //     parked in LDS in operand-register order.  Operand rows of absent requests
@@ -110,6 +113,14 @@ __device__ __forceinline__ v8i expand_plane_word(uint32_t w, uint32_t sign, uint
     r[2] = (int)(((w << 2) & sign) | one);
     r[3] = (int)(((w << 3) & sign) | one);
     return r;
+}
+
+// The four E5M2 terms of an activation carry the scales 1, 4, 32 and 256 (see the conversion in `sweep`);
+// their sums over a group, rows 4b .. 4b + 3 of the result, recombine to the group sum of request b.
+// Every product is a power-of-two scaling, so the only roundings are those of the fp32 additions.
+__device__ __forceinline__ float term_sum(v4f d)
+{
+    return fmaf(fmaf(d[3], 0.125f, d[2]), 0.03125f, fmaf(d[1], 0.25f, d[0]));
 }
 
 // Sum of a value over the 8 lanes l & ~7 .. l | 7 (result in all of them).
@@ -292,14 +303,18 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 h2 r23 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 6], dwd[k0 + 4], sel));
                 const int inv = 3 - low, w = inv >> 1, z = inv & 1;
                 uint32_t *d32 = reinterpret_cast<uint32_t *>(img_unit + w * (L::kRows * 16) + 8 * z + b * 64);
-                // exact split into four E5M2 terms: top bytes of the running binary16 remainders
+                // exact split into four E5M2 terms: term j is the top byte of the running binary16 remainder, and
+                // the remainder is scaled by 4, 8 and 8 on the way (never past the value it came from, so nothing
+                // overflows): the terms carry the scales 1, 4, 32 and 256, which term_sum() undoes.  Without the
+                // scaling the terms, whose spacing ends at 2^-16, would lose the low bits of small activations.
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
                     const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
                     if (j < 3) {
-                        r01 = r01 - __builtin_bit_cast(h2, t01);
-                        r23 = r23 - __builtin_bit_cast(h2, t23);
+                        const _Float16 c = j == 0 ? (_Float16)4.0f : (_Float16)8.0f;
+                        r01 = (r01 - __builtin_bit_cast(h2, t01)) * h2{c, c};
+                        r23 = (r23 - __builtin_bit_cast(h2, t23)) * h2{c, c};
                     }
                     d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);              // bytes: i = 0, 1, 2, 3
                 }
@@ -386,8 +401,8 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                         const uint32_t sw = gl < 4 ? ld.sc[i - 1][gl & 3] : ld.sc2[i - 1][gl & 3];
                         const float a_lo = (float)__builtin_bit_cast(_Float16, (unsigned short)(sw & 0xffffu));
                         const float a_hi = (float)__builtin_bit_cast(_Float16, (unsigned short)(sw >> 16));
-                        acc = fmaf(-a_lo, (d_lo[0] + d_lo[1]) + (d_lo[2] + d_lo[3]), acc);
-                        acc = fmaf(-a_hi, (d_hi[0] + d_hi[1]) + (d_hi[2] + d_hi[3]), acc);
+                        acc = fmaf(-a_lo, term_sum(d_lo), acc);
+                        acc = fmaf(-a_hi, term_sum(d_hi), acc);
                     }
                     d_lo = n_lo;
                     d_hi = n_hi;
@@ -405,7 +420,7 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                 for (int i = 0; i < PH; ++i) {
                     const uint32_t sw = ld.sc[i][gl >> 1];
                     const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
-                    const float sum = (d[i][0] + d[i][1]) + (d[i][2] + d[i][3]);
+                    const float sum = term_sum(d[i]);
                     // the FP4 sign bit is set for weight bit 1 (= +1), so the instruction returns -(B_i x)
                     acc = fmaf(-alpha, sum, acc);
                 }

@@ -58,47 +58,8 @@ typedef enum {
     BCQ_ERR_VARIANT = -6     /* a forced kernel variant cannot run this problem */
 } bcq_status;
 
-/* Kernel variants for bcq_select_kernel (benchmarks and tests only). */
-typedef enum {
-    BCQ_KERNEL_AUTO = 0,       /* pick by shape and batch */
-    BCQ_KERNEL_SIGN_SELECT = 1,/* generic per-bit add/subtract kernel, any legal shape */
-    BCQ_KERNEL_PLANE_MFMA = 2, /* bit-planes fed to the FP4 matrix pipe, small batches */
-    BCQ_KERNEL_DEQUANT_MFMA = 3,/* dequantise to fp16 tiles in LDS + fp16 MFMA, large batches */
-    BCQ_KERNEL_PLANE_F16 = 4   /* +-1 planes as fp16 MFMA operands, group sums scaled in fp32 by each request's own scales; groups >= 128 */
-} bcq_kernel;
-
 /* Static, NUL-terminated description of a status code.  Host call. */
 const char *bcq_strerror(int status);
-
-/*
- * Force one kernel variant for later bcq_gemv / bcq_gemm_mixed calls of this
- * process (BCQ_KERNEL_AUTO restores the default choice).  A forced variant
- * that cannot handle a problem makes the call return BCQ_ERR_VARIANT.
- * Returns BCQ_OK, or BCQ_ERR_VARIANT for an unknown id.  Host call, not
- * thread-safe against concurrent launches.
- */
-int bcq_select_kernel(int variant);
-
-/*
- * Force the workgroup shape of the large-batch kernel for later calls of this
- * process (benchmarks and tests only; the library otherwise picks it from m and
- * the batch): `request_tiles` tiles of 64 requests and `row_blocks` blocks of 16
- * rows per workgroup, one of (1,4) (1,2) (1,1) (2,4) (2,2) (4,4), or (0,4) (0,2)
- * (0,1) for a single tile of 16 requests and (32,4) (32,2) (32,1) for one of 32,
- * (0,8) and (32,8) for those tiles with one row block whose columns are split
- * over eight teams of waves instead of four, (4,8) and (2,8) for 256 and 128 requests
- * with eight row blocks, (4,40) for 256 requests and four row blocks served by two teams
- * of waves that share the activation tiles;
- * per-request precision uses the row blocks and whether the tile has 32
- * requests only, beyond 64 requests the whole shape if it has 64 requests or
- * more.  (0, 0) restores the automatic choice.
- * Returns BCQ_OK, or BCQ_ERR_VARIANT for any other pair.  Host call, not
- * thread-safe against concurrent launches.
- */
-int bcq_select_dequant_shape(int request_tiles, int row_blocks);
-
-/* Name of the variant the most recent successful launch used ("" before any). */
-const char *bcq_last_kernel(void);
 
 /*
  * bcq_pack -- bit-plane storage (section 3.3): turn +-1 codes into planes.

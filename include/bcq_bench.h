@@ -18,6 +18,46 @@ extern "C" {
 #endif
 
 /*
+ * Test and benchmark knobs.  They live here and not in bcq.h because no product call needs them; their state is
+ * PER HOST THREAD (thread-local): a thread that forces a variant or a shape changes its own later calls only, and
+ * bcq_last_kernel reports the calling thread's own most recent launch.
+ */
+
+/* Kernel variants for bcq_select_kernel. */
+typedef enum {
+    BCQ_KERNEL_AUTO = 0,        /* pick by shape and batch */
+    BCQ_KERNEL_SIGN_SELECT = 1, /* generic per-bit add/subtract kernel, any legal shape */
+    BCQ_KERNEL_PLANE_MFMA = 2,  /* bit-planes fed to the FP4 matrix pipe, small batches */
+    BCQ_KERNEL_DEQUANT_MFMA = 3,/* dequantise to fp16 tiles in LDS + fp16 MFMA, large batches */
+    BCQ_KERNEL_PLANE_F16 = 4    /* +-1 planes as fp16 MFMA operands, group sums scaled in fp32 by each request's own scales; groups >= 128 */
+} bcq_kernel;
+
+/*
+ * Force one kernel variant for the calling thread's later product calls (BCQ_KERNEL_AUTO restores the default
+ * choice).  A forced variant that cannot handle a problem makes the call return BCQ_ERR_VARIANT (-6).
+ * Returns 0, or -6 for an unknown id.
+ */
+int bcq_select_kernel(int variant);
+
+/* The variant the calling thread has forced (BCQ_KERNEL_AUTO if none). */
+int bcq_selected_kernel(void);
+
+/*
+ * Force the workgroup shape of the large-batch kernel for the calling thread's later calls (the library otherwise
+ * picks it from m and the batch): `request_tiles` tiles of 64 requests and `row_blocks` blocks of 16 rows per
+ * workgroup, one of (1,4) (1,2) (1,1) (2,4) (2,2) (4,4), or (0,4) (0,2) (0,1) for a single tile of 16 requests and
+ * (32,4) (32,2) (32,1) for one of 32, (0,8) and (32,8) for those tiles with one row block whose columns are split
+ * over eight teams of waves instead of four, (4,8) and (2,8) for 256 and 128 requests with eight row blocks, (4,40)
+ * for 256 requests and four row blocks served by two teams of waves that share the activation tiles; per-request
+ * precision uses the row blocks and whether the tile has 32 requests only, beyond 64 requests the whole shape if it
+ * has 64 requests or more.  (0, 0) restores the automatic choice.  Returns 0, or -6 for any other pair.
+ */
+int bcq_select_dequant_shape(int request_tiles, int row_blocks);
+
+/* Name of the variant the calling thread's most recent successful launch used ("" before any). */
+const char *bcq_last_kernel(void);
+
+/*
  * Streaming read of `bytes` bytes (a multiple of 16, 16-byte aligned) with 128-bit
  * non-temporal loads and no stores to speak of: `sink` (64 words) is written only
  * if a workgroup's XOR of everything it read equals one particular constant.

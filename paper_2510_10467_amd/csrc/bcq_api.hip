@@ -2,13 +2,20 @@
 // lives in the kernel files; this file never touches tensor data.
 #include <hip/hip_runtime.h>
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "bcq.h"
+#include "bcq_bench.h"
 #include "bcq_internal.hpp"
 
 namespace {
 
-int g_forced = BCQ_KERNEL_AUTO;
-const char *g_last = "";
+// test and benchmark knobs (bcq_bench.h): per host thread, so that one thread's forced variant never changes
+// another thread's dispatch
+thread_local int g_forced = BCQ_KERNEL_AUTO;
+thread_local const char *g_last = "";
 
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -19,6 +26,15 @@ int check_shape(int64_t m, int64_t n, int batch, int group)
     // index arithmetic inside the kernels is 64-bit, but word counts per row are kept in int
     if (n > (int64_t(1) << 30) || m > (int64_t(1) << 40)) return BCQ_ERR_BAD_SHAPE;
     return BCQ_OK;
+}
+
+// pack / unpack run one thread per plane word in workgroups of 256: the word count must fit one grid dimension
+bool pack_grid_fits(int n_planes, int64_t m, int64_t n)
+{
+    if (m > (int64_t(1) << 40) || n > (int64_t(1) << 30)) return false;
+    const int64_t words_per_plane_row = n / 32;
+    if (m > ((int64_t(1) << 39) - 1) / (words_per_plane_row * n_planes)) return false;      // 2^31 blocks x 256 words
+    return true;
 }
 
 // The kernel family a problem runs on: the forced one, or the default choice.
@@ -101,6 +117,25 @@ int run(const bcq::GemmArgs &a, hipStream_t stream)
 
 }  // namespace
 
+namespace bcq {
+
+hipError_t allow_dynamic_lds(const void *kernel, int bytes)
+{
+    if (bytes <= 64 * 1024) return hipSuccess;
+    static std::mutex lock;
+    static std::map<std::pair<int, const void *>, int> granted;      // (device, kernel) -> bytes already allowed
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    std::lock_guard<std::mutex> guard(lock);
+    int &have = granted[{dev, kernel}];
+    if (bytes <= have) return hipSuccess;
+    if (hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) return e;
+    have = bytes;
+    return hipSuccess;
+}
+
+}  // namespace bcq
+
 extern "C" {
 
 const char *bcq_strerror(int status)
@@ -124,6 +159,8 @@ int bcq_select_kernel(int variant)
     return BCQ_OK;
 }
 
+int bcq_selected_kernel(void) { return g_forced; }
+
 const char *bcq_last_kernel(void) { return g_last; }
 
 int bcq_select_dequant_shape(int request_tiles, int row_blocks)
@@ -135,7 +172,7 @@ int bcq_pack(const int8_t *codes, uint32_t *planes, int n_planes, int64_t m, int
 {
     if (!codes || !planes) return BCQ_ERR_NULL;
     if (n_planes < 1 || n_planes > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
-    if (m < 1 || n < 32 || (n % 32) != 0) return BCQ_ERR_BAD_SHAPE;
+    if (m < 1 || n < 32 || (n % 32) != 0 || !pack_grid_fits(n_planes, m, n)) return BCQ_ERR_BAD_SHAPE;
     if (!aligned(codes, 16) || !aligned(planes, 4)) return BCQ_ERR_ALIGN;
     return bcq::pack_launch(codes, planes, n_planes, m, n, static_cast<hipStream_t>(stream)) == hipSuccess
                ? BCQ_OK : BCQ_ERR_HIP;
@@ -145,7 +182,7 @@ int bcq_unpack(const uint32_t *planes, int8_t *codes, int n_planes, int64_t m, i
 {
     if (!codes || !planes) return BCQ_ERR_NULL;
     if (n_planes < 1 || n_planes > BCQ_MAX_PLANES) return BCQ_ERR_BAD_P;
-    if (m < 1 || n < 32 || (n % 32) != 0) return BCQ_ERR_BAD_SHAPE;
+    if (m < 1 || n < 32 || (n % 32) != 0 || !pack_grid_fits(n_planes, m, n)) return BCQ_ERR_BAD_SHAPE;
     if (!aligned(codes, 16) || !aligned(planes, 4)) return BCQ_ERR_ALIGN;
     return bcq::unpack_launch(planes, codes, n_planes, m, n, static_cast<hipStream_t>(stream)) == hipSuccess
                ? BCQ_OK : BCQ_ERR_HIP;

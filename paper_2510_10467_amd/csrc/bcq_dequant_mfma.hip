@@ -63,7 +63,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxP = 4;
 constexpr int kClassFrom = 64;              // per-request precision: beyond this many requests the uniform kernel's body per precision
-int g_forced_nt = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
+thread_local int g_forced_nt = 0, g_forced_rw = 0;       // workgroup shape forced by dequant_mfma_force_shape (0: automatic)
 constexpr int kLutBytes = 256;              // 16 entries x 8 bytes, rounded up to keep what follows aligned
 constexpr int kXRowBytes = 128 * 2;         // LDS row of one request's 128 activations; its sixteen parts sit XOR-permuted
 
@@ -1193,11 +1193,7 @@ hipError_t launch_planewise_mixed(const DequantParams &pr, const GemmArgs &a, hi
 {
     static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= TEAMS * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
     auto kernel = planewise_mixed_kernel<NT, TEAMS, RW>;
-    if (lds_bytes(NT, TEAMS) > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           lds_bytes(NT, TEAMS));
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds_bytes(NT, TEAMS))) return e;
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
     hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(NT, TEAMS), stream, pr);
     return hipGetLastError();
@@ -1208,9 +1204,7 @@ hipError_t launch_mixed(const DequantParams &pr, const GemmArgs &a, hipStream_t 
 {
     static_assert((TEAMS - 1) * RW * kMaxP * 4 * 64 * 16 <= TEAMS * 2 * x_tile_bytes(4), "accumulator exchange must fit in the tiles");
     auto kernel = dequant_mixed_kernel<TEAMS, RW>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       lds_bytes(4, TEAMS));
-    if (e != hipSuccess) return e;
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds_bytes(4, TEAMS))) return e;
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 63) / 64));
     hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), lds_bytes(4, TEAMS), stream, pr);
     return hipGetLastError();
@@ -1222,12 +1216,7 @@ hipError_t launch_one(const DequantParams &pr, const GemmArgs &a, hipStream_t st
     constexpr int LT = SHARE ? 1 : TEAMS;     // pairs of tiles in LDS
     static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= LT * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
     auto kernel = dequant_mfma_kernel<P, NT, TEAMS, RW, PW, SHARE>;
-    if (lds_bytes(NT, LT) > 64 * 1024) {
-        // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           lds_bytes(NT, LT));
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds_bytes(NT, LT))) return e;
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
     if (pr.nmat > 1) {
         // several matrices: every matrix gets whole workgroups (pr.mat_m holds the row counts; the offsets are made here
@@ -1254,8 +1243,7 @@ hipError_t launch_byclass(const DequantParams &pr, const GemmArgs &a, hipStream_
     static_assert((TEAMS - 1) * RW * NT * 64 * 16 <= LT * 2 * x_tile_bytes(NT), "accumulator exchange must fit in the tiles");
     auto kernel = dequant_byclass_kernel<NT, TEAMS, RW, SHARE>;
     constexpr int kLds = lds_bytes(NT, LT) + 16 * NT * 4;           // the workgroup's request numbers behind the tiles
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    if (e != hipSuccess) return e;
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), kLds)) return e;
     dim3 grid((unsigned)((a.m + 16 * RW - 1) / (16 * RW)), (unsigned)a.p_max, (unsigned)((a.batch + 16 * NT - 1) / (16 * NT)));
     hipLaunchKernelGGL(kernel, grid, dim3(64 * RW * TEAMS), kLds, stream, pr);
     return hipGetLastError();

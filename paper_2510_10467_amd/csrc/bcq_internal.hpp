@@ -36,6 +36,10 @@ __device__ __forceinline__ int request_precision(const GemmArgs &a, int b)
     return a.scales[p] ? p : 0;
 }
 
+// More than 64 KiB of dynamic LDS needs a per-function attribute.  It sticks to the function, so it is set once per
+// kernel instance and device (and again only if a later launch asks for more); defined in bcq_api.hip.
+hipError_t allow_dynamic_lds(const void *kernel, int bytes);
+
 // Kernel families.  *_supports tells whether the family can run the problem;
 // *_launch enqueues it on `stream` and returns the HIP launch status.
 bool sign_select_supports(const GemmArgs &a);

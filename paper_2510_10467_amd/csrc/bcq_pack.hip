@@ -62,6 +62,7 @@ hipError_t pack_launch(const int8_t *codes, uint32_t *planes, int n_planes, int6
 {
     int64_t total = (int64_t)n_planes * m * (n / 32);
     int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidValue;        // beyond one grid dimension
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, codes, planes, total);
     return hipGetLastError();
 }
@@ -70,6 +71,7 @@ hipError_t unpack_launch(const uint32_t *planes, int8_t *codes, int n_planes, in
 {
     int64_t total = (int64_t)n_planes * m * (n / 32);
     int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidValue;        // beyond one grid dimension
     hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, planes, codes, total);
     return hipGetLastError();
 }

@@ -608,12 +608,7 @@ Plan make_plan(const GemmArgs &a, bool share_row_blocks = true)
 template <typename K>
 hipError_t launch_one(K kernel, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
 {
-    if (pl.lds_bytes > 64 * 1024) {
-        // opt in to more than 64 KiB of dynamic LDS (a per-function attribute, cheap to repeat)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)pl.lds_bytes)) return e;
     hipLaunchKernelGGL(kernel, grid, block, pl.lds_bytes, stream, pr);
     return hipGetLastError();
 }

@@ -155,3 +155,43 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros((1, 128), dtype=torch.float16)
     with pytest.raises(TypeError):
         bcq.bcq_gemv(planes, scales, 2, x)
+
+
+def test_test_knobs_are_per_thread(lib):
+    """One thread forcing a kernel variant or a workgroup shape leaves the other threads' dispatch alone."""
+    import threading
+    lib.bcq_selected_kernel.restype = ctypes.c_int
+    assert lib.bcq_select_kernel(0) == 0
+    seen = {}
+    forced = threading.Event()
+    checked = threading.Event()
+
+    def forcing():
+        assert lib.bcq_select_kernel(2) == 0
+        seen["forcing"] = lib.bcq_selected_kernel()
+        forced.set()
+        checked.wait(10)
+        seen["forcing_after"] = lib.bcq_selected_kernel()
+
+    def watching():
+        forced.wait(10)
+        seen["watching"] = lib.bcq_selected_kernel()
+        seen["watching_last"] = lib.bcq_last_kernel()
+        checked.set()
+
+    threads = [threading.Thread(target=forcing), threading.Thread(target=watching)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(20)
+    assert seen["forcing"] == 2 and seen["forcing_after"] == 2
+    assert seen["watching"] == 0, "a variant forced by one thread changed another thread's choice"
+    assert lib.bcq_selected_kernel() == 0
+
+
+def test_pack_rejects_what_one_grid_cannot_hold(lib):
+    """More plane words than 2^31 - 1 workgroups of 256 threads cover: an error before any launch."""
+    C, P = 0x1000, 0x2000
+    assert lib.bcq_pack(C, P, 4, ctypes.c_int64(1 << 33), ctypes.c_int64(4096), None) == -3
+    assert lib.bcq_unpack(P, C, 8, ctypes.c_int64(1 << 36), ctypes.c_int64(32), None) == -3
+    assert lib.bcq_pack(C, P, 1, ctypes.c_int64(1 << 41), ctypes.c_int64(32), None) == -3

@@ -298,6 +298,42 @@ def test_per_request_precision_one_launch_per_precision(gpu, shape, forced_shape
     assert torch.all(y_some[is3] == 0) and torch.equal(y_some[~is3], y_ok[~is3])
 
 
+def test_forced_variant_and_last_kernel_are_per_thread(gpu):
+    """One thread forces the generic kernel; another, launching at the same time, keeps the default choice, and each
+    reads its own last kernel."""
+    import threading
+
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    layer = syn.make_layer(64, 2048, seed=(185, 0))
+    dl = gpu.DeviceLayer(layer)
+    x = gpu.to_dev(syn.make_x(1, 2048, seed=(185, 1)))
+    seen, forced, done = {}, threading.Event(), threading.Event()
+
+    def forcing():
+        bcq.select_kernel("sign_select")
+        forced.set()
+        bcq.bcq_gemv(dl.planes, dl.scales[2], 2, x)
+        done.wait(30)
+        seen["forcing"] = bcq.last_kernel()
+        bcq.select_kernel("auto")
+
+    def default():
+        forced.wait(30)
+        bcq.bcq_gemv(dl.planes, dl.scales[2], 2, x)
+        seen["default"] = bcq.last_kernel()
+        done.set()
+
+    threads = [threading.Thread(target=forcing), threading.Thread(target=default)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(60)
+    torch.cuda.synchronize()
+    assert seen == {"forcing": "sign_select", "default": "plane_mfma"}
+
+
 def test_forced_variant_that_cannot_run_is_an_error(gpu):
     import paper_2510_10467_amd as bcq
     layer = syn.make_layer(16, 640, seed=(160, 0))            # n is shorter than one K slice
@@ -455,8 +491,9 @@ def test_gemv_multi_equals_separate_calls(gpu, oracle, ms, n):
         xh = syn.make_x(batch, n, seed=(190, batch))
         x = gpu.to_dev(xh)
         for p in (1, 2, 3, 4):
-            ys = bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[p] for d in dls], p, x)
-            torch.cuda.synchronize()
+            outs = [gpu.Guarded((batch, m)) for m in ms]
+            bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[p] for d in dls], p, x, ys=[o.t for o in outs])
+            ys = [o.check(f"bcq_gemv_multi ms={ms} n={n} p={p} batch={batch}, output {k}") for k, o in enumerate(outs)]
             assert bcq.last_kernel() == "plane_mfma"
             for d, y in zip(dls, ys):
                 y_ref, a_ref = oracle.gemv(d.layer.planes, d.layer.scales[p], xh)

@@ -28,7 +28,8 @@ def sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y_gpu, what):
 
 
 @pytest.mark.parametrize("name,m,n", [("gate_proj", 14336, 4096), ("down_proj", 4096, 14336), ("q_proj", 4096, 4096),
-                                       ("k_proj", 1024, 4096), ("llama70b_up", 28672, 8192), ("llama70b_down", 8192, 28672)])
+                                       ("k_proj", 1024, 4096), ("llama70b_up", 28672, 8192), ("llama70b_down", 8192, 28672),
+                                       ("phi4_attn", 5120, 5120), ("phi4_up", 17920, 5120), ("phi4_down", 5120, 17920)])
 def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
     import torch
 
@@ -44,8 +45,9 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
         x = syn.make_x(batch, n, seed=(200, batch))
         xd = gpu.to_dev(x)
         for p in (2, 3, 4):
-            y = bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd)
-            torch.cuda.synchronize()
+            out = gpu.Guarded((batch, m))
+            bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd, y=out.t)
+            y = out.check(f"{name} p={p} batch={batch} ({bcq.last_kernel()})")
             sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"{name} p={p} batch={batch} ({bcq.last_kernel()})")
 
 

@@ -13,15 +13,28 @@ import torch
 import oracle
 import paper_2510_10467_amd as bcq
 import synthetic_inputs as syn
-from tests.gpu_util import to_dev
+from tests.gpu_util import Guarded, to_dev
 
 pytestmark = pytest.mark.gpu
 
 
 def run_gpu(w, p_low, p_high, cycles, group=128, with_offset=False):
-    planes, scales, offsets = bcq.bcq_quantize(to_dev(w), p_low, p_high, cycles, group=group, with_offset=with_offset)
+    # every output sits between 4 KiB bands of sentinel values: a store past either end fails the test
+    m, n = w.shape
+    g_planes = Guarded((p_high, m, n // 32), torch.int32)
+    g_scales = {p: Guarded((p, m, n // group)) for p in range(p_low, p_high + 1)}
+    g_offsets = {p: Guarded((m, n // group)) for p in range(p_low, p_high + 1)} if with_offset else None
+    planes, scales, offsets = bcq.bcq_quantize(to_dev(w), p_low, p_high, cycles, group=group, with_offset=with_offset,
+                                               planes=g_planes.t, scales_by_p={p: g.t for p, g in g_scales.items()},
+                                               offsets_by_p=None if g_offsets is None else {p: g.t for p, g in g_offsets.items()})
     torch.cuda.synchronize()
     assert bcq.last_kernel() == "quantize"
+    what = f"bcq_quantize m={m} n={n} p={p_low}..{p_high} g={group}"
+    g_planes.check(what + " planes")
+    for p, g in g_scales.items():
+        g.check(what + f" scale set {p}")
+    for p, g in (g_offsets or {}).items():
+        g.check(what + f" offset set {p}")
     planes = planes.cpu().numpy().view(np.uint32)
     scales = {p: s.cpu().numpy() for p, s in scales.items()}
     offsets = None if offsets is None else {p: z.cpu().numpy() for p, z in offsets.items()}

@@ -166,7 +166,9 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
  * With `offsets_by_p` the asymmetric scheme of section 4.1 is fitted: the
  * offset is one more least-squares unknown (all-ones basis vector).
  * Definitions that decide codes: sign(0) = +1; the residual that re-signs the
- * new plane excludes that plane (section 2.2's residual after p-1 planes);
+ * new plane excludes that plane (section 2.2's residual after p-1 planes; the
+ * listing's own form, which takes the new plane's term out as well, is
+ * available through bcq_quantize_form);
  * nearest-level ties go to the first level when enumerated with plane 0 as the
  * most significant bit of the index; a plane that is linearly dependent on the
  * planes before it gets scale 0.  Arithmetic is IEEE double (sums of binary16
@@ -186,6 +188,27 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
  */
 int bcq_quantize(const bcq_half *w, int p_low, int p_high, int cycles, uint32_t *planes, bcq_half *const *scales_by_p,
                  bcq_half *const *offsets_by_p, int64_t m, int64_t n, int group, void *stream);
+
+/*
+ * bcq_quantize_form -- bcq_quantize with the residual of the expansion cycles
+ * chosen by the caller.  Algorithm 1 (section 3.2) prints the cycle as
+ * "R <- W - Dequant({alpha_i^p, B_i} for i = 1..p); B_p <- sign(R); LS": read
+ * literally, the new plane's own term alpha_p B_p is subtracted too from the
+ * second cycle on (in the first both are zero).  Section 2.2 defines the
+ * residual that a new plane takes the sign of as the one after the planes
+ * before it, and the literal form does not settle (a code whose residual is
+ * smaller than the new scale flips every cycle; on Gaussian weights its 3-bit
+ * error is about 2.5 times that of the other form), so bcq_quantize uses
+ *   BCQ_RESIDUAL_FROZEN_PLANES  R = W - sum_{i<p} alpha_i B_i  (planes 1..p-1)
+ * and this call also offers
+ *   BCQ_RESIDUAL_LISTING        R = W - sum_{i<=p} alpha_i B_i (all p planes).
+ * Both agree after one cycle.  Any other value: BCQ_ERR_VARIANT.  All other
+ * arguments, results and errors as for bcq_quantize.
+ */
+enum { BCQ_RESIDUAL_FROZEN_PLANES = 0, BCQ_RESIDUAL_LISTING = 1 };
+int bcq_quantize_form(const bcq_half *w, int p_low, int p_high, int cycles, int residual_form, uint32_t *planes,
+                      bcq_half *const *scales_by_p, bcq_half *const *offsets_by_p, int64_t m, int64_t n, int group,
+                      void *stream);
 
 #ifdef __cplusplus
 }

@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.bcq_gemm_mixed_offset.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i64, i32, i32, vp]
         L.bcq_quantize.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, i64, i32, vp]
         L.bcq_quantize.restype = i32
+        L.bcq_quantize_form.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i64, i64, i32, vp]
+        L.bcq_quantize_form.restype = i32
         L.bcq_bench_stream_read.argtypes = [vp, i64, vp, vp]
         L.bcq_bench_stream_read.restype = i32
         L.bcq_bench_fp16_gemv.argtypes = [vp, vp, vp, i64, i64, vp]
@@ -208,9 +210,11 @@ def bcq_gemm_mixed(planes: torch.Tensor, scales_by_p: dict, p_req: torch.Tensor,
 
 
 def bcq_quantize(w: torch.Tensor, p_low: int, p_high: int, cycles: int, group: int = 128, with_offset: bool = False,
-                 planes: torch.Tensor | None = None, scales_by_p: dict | None = None, offsets_by_p: dict | None = None):
+                 planes: torch.Tensor | None = None, scales_by_p: dict | None = None, offsets_by_p: dict | None = None,
+                 listing_residual: bool = False):
     """Algorithm 1 on float16 weights [m][n]: returns ``(planes int32 [p_high][m][n/32], {p: scales float16
-    [p][m][n/group]}, {p: offsets float16 [m][n/group]} or None)`` for p = p_low..p_high."""
+    [p][m][n/group]}, {p: offsets float16 [m][n/group]} or None)`` for p = p_low..p_high.  ``listing_residual``
+    selects the expansion residual as the algorithm's listing prints it (``bcq_quantize_form``)."""
     m, n = w.shape
     if n % 32 or n % group:
         raise ValueError("bcq_quantize: n must be a multiple of 32 and of group")
@@ -235,10 +239,10 @@ def bcq_quantize(w: torch.Tensor, p_low: int, p_high: int, cycles: int, group: i
             if offsets_by_p[p].shape != (m, n // group):
                 raise ValueError(f"bcq_quantize: bad offset set for precision {p}")
             op[p] = _dev(offsets_by_p[p], torch.float16, f"offsets_by_p[{p}]")
-    _check(lib().bcq_quantize(_dev(w, torch.float16, "w"), p_low, p_high, cycles, _dev(planes, torch.int32, "planes"),
-                              ctypes.cast(sp, ctypes.c_void_p),
-                              ctypes.cast(op, ctypes.c_void_p) if offsets_by_p is not None else None,
-                              m, n, group, _stream()), "bcq_quantize")
+    _check(lib().bcq_quantize_form(_dev(w, torch.float16, "w"), p_low, p_high, cycles, 1 if listing_residual else 0,
+                                   _dev(planes, torch.int32, "planes"), ctypes.cast(sp, ctypes.c_void_p),
+                                   ctypes.cast(op, ctypes.c_void_p) if offsets_by_p is not None else None,
+                                   m, n, group, _stream()), "bcq_quantize")
     return planes, scales_by_p, offsets_by_p
 
 

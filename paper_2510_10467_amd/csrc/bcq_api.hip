@@ -311,6 +311,13 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
 int bcq_quantize(const bcq_half *w, int p_low, int p_high, int cycles, uint32_t *planes, bcq_half *const *scales_by_p,
                  bcq_half *const *offsets_by_p, int64_t m, int64_t n, int group, void *stream)
 {
+    return bcq_quantize_form(w, p_low, p_high, cycles, BCQ_RESIDUAL_FROZEN_PLANES, planes, scales_by_p, offsets_by_p, m, n, group, stream);
+}
+
+int bcq_quantize_form(const bcq_half *w, int p_low, int p_high, int cycles, int residual_form, uint32_t *planes,
+                      bcq_half *const *scales_by_p, bcq_half *const *offsets_by_p, int64_t m, int64_t n, int group, void *stream)
+{
+    if (residual_form != BCQ_RESIDUAL_FROZEN_PLANES && residual_form != BCQ_RESIDUAL_LISTING) return BCQ_ERR_VARIANT;
     if (!w || !planes || !scales_by_p) return BCQ_ERR_NULL;
     if (p_low < 1 || p_high < p_low || p_high > 4 || cycles < 0 || (cycles < 1 && p_high > p_low)) return BCQ_ERR_BAD_P;
     if (int rc = check_shape(m, n, 0, group)) return rc;
@@ -323,7 +330,7 @@ int bcq_quantize(const bcq_half *w, int p_low, int p_high, int cycles, uint32_t 
     hipError_t err = bcq::quantize_launch(reinterpret_cast<const _Float16 *>(w), p_low, p_high, cycles, planes,
                                           reinterpret_cast<_Float16 *const *>(scales_by_p),
                                           reinterpret_cast<_Float16 *const *>(offsets_by_p), m, n, group,
-                                          static_cast<hipStream_t>(stream));
+                                          residual_form == BCQ_RESIDUAL_LISTING, static_cast<hipStream_t>(stream));
     g_last = "quantize";
     return err == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
 }

@@ -64,7 +64,7 @@ hipError_t dequant_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_
 // Offline quantiser (Algorithm 1): group must be 32, 64, 128 or 256; 1 <= p_low <= p_high <= 4.
 bool quantize_supports(int64_t m, int64_t n, int group);
 hipError_t quantize_launch(const _Float16 *w, int p_low, int p_high, int cycles, uint32_t *planes, _Float16 *const *scales_by_p,
-                           _Float16 *const *offsets_by_p, int64_t m, int64_t n, int group, hipStream_t stream);
+                           _Float16 *const *offsets_by_p, int64_t m, int64_t n, int group, bool listing_residual, hipStream_t stream);
 
 hipError_t pack_launch(const int8_t *codes, uint32_t *planes, int n_planes, int64_t m, int64_t n, hipStream_t stream);
 hipError_t unpack_launch(const uint32_t *planes, int8_t *codes, int n_planes, int64_t m, int64_t n, hipStream_t stream);

@@ -272,7 +272,10 @@ __device__ __forceinline__ void base_stage_two(Lane &s, int cycles, double sum_w
 // The frozen codes of a column select one of 2^(P-1) levels; each cycle the lanes of a group write those
 // levels into the group's LDS table (`table`, 8 doubles) and every column reads its own back.  The table
 // is private to lanes of one wave, whose LDS accesses complete in program order.
-template <int P, int LANES, bool OFFSET>
+// LISTING: the residual as Algorithm 1 prints it, R = W - Dequant over all P planes: the new plane's own term
+// alpha_P b_P (zero in the first cycle, where both start as zero) is taken out too, in the order
+// ((a_1 b_1 + ... + a_{P-1} b_{P-1}) + a_P b_P) + z.
+template <int P, int LANES, bool OFFSET, bool LISTING>
 __device__ __forceinline__ void expand_stage(Lane &s, int cycles, double sum_w, double *table, int lane_in_group)
 {
     constexpr int NL = 1 << (P - 1);
@@ -299,15 +302,22 @@ __device__ __forceinline__ void expand_stage(Lane &s, int cycles, double sum_w, 
             double v = ((c >> (P - 2)) & 1) ? s.alpha[0] : -s.alpha[0];
 #pragma unroll
             for (int i = 1; i < P - 1; ++i) v = v + (((c >> (P - 2 - i)) & 1) ? s.alpha[i] : -s.alpha[i]);
-            table[c] = OFFSET ? v + s.z : v;
+            table[c] = (OFFSET && !LISTING) ? v + s.z : v;
         }
+        const uint32_t own = s.word[P - 1];              // the new plane's codes of the previous cycle
+        const double own_scale = s.alpha[P - 1];
         __builtin_amdgcn_wave_barrier();
         double acc[2] = {0.0, 0.0};
         uint32_t minus = 0;                              // sign bits of the residuals, column 31 first
 #pragma unroll
         for (int j = 31; j >= 0; --j) {
             const uint32_t off = (pick[j >> 2] >> (8 * (j & 3))) & 0xffu;
-            const double lev = *reinterpret_cast<const double *>(reinterpret_cast<const char *>(table) + off);
+            double lev = *reinterpret_cast<const double *>(reinterpret_cast<const char *>(table) + off);
+            if constexpr (LISTING) {
+                const double own_term = t == 0 ? 0.0 : flip(own_scale, ((own >> j) & 1u) ? 0u : 0x80000000u);
+                lev = lev + own_term;
+                if constexpr (OFFSET) lev = lev + s.z;
+            }
             const double r = s.w[j] - lev;               // never -0: the weights hold no -0
             const uint32_t rhi = (uint32_t)(__builtin_bit_cast(uint64_t, r) >> 32);
             minus = __builtin_amdgcn_alignbit(minus, rhi, 31);
@@ -331,7 +341,7 @@ __device__ __forceinline__ void store_set(const QuantParams &a, const Lane &s, i
     if constexpr (OFFSET) a.offsets[p][gid] = to_half(s.z);
 }
 
-template <int LANES, bool OFFSET>
+template <int LANES, bool OFFSET, bool LISTING>
 __global__ __launch_bounds__(256) void quantize_kernel(QuantParams a)
 {
     __shared__ double tables[(256 / LANES) * 8];
@@ -378,9 +388,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams a)
     store_set<LANES, OFFSET>(a, s, p_low, gid, writer);
     for (int p = p_low + 1; p <= a.p_high; ++p) {
         switch (p) {
-        case 2: expand_stage<2, LANES, OFFSET>(s, a.cycles, sum_w, table, lane_in_group); break;
-        case 3: expand_stage<3, LANES, OFFSET>(s, a.cycles, sum_w, table, lane_in_group); break;
-        default: expand_stage<4, LANES, OFFSET>(s, a.cycles, sum_w, table, lane_in_group); break;
+        case 2: expand_stage<2, LANES, OFFSET, LISTING>(s, a.cycles, sum_w, table, lane_in_group); break;
+        case 3: expand_stage<3, LANES, OFFSET, LISTING>(s, a.cycles, sum_w, table, lane_in_group); break;
+        default: expand_stage<4, LANES, OFFSET, LISTING>(s, a.cycles, sum_w, table, lane_in_group); break;
         }
         store_set<LANES, OFFSET>(a, s, p, gid, writer);
     }
@@ -392,11 +402,16 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams a)
 }
 
 template <int LANES>
-hipError_t launch_lanes(const QuantParams &pr, bool offset, hipStream_t stream)
+hipError_t launch_lanes(const QuantParams &pr, bool offset, bool listing, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((pr.total_words + 255) / 256);
-    if (offset) hipLaunchKernelGGL((quantize_kernel<LANES, true>), dim3(blocks), dim3(256), 0, stream, pr);
-    else hipLaunchKernelGGL((quantize_kernel<LANES, false>), dim3(blocks), dim3(256), 0, stream, pr);
+    if (listing) {
+        if (offset) hipLaunchKernelGGL((quantize_kernel<LANES, true, true>), dim3(blocks), dim3(256), 0, stream, pr);
+        else hipLaunchKernelGGL((quantize_kernel<LANES, false, true>), dim3(blocks), dim3(256), 0, stream, pr);
+    } else {
+        if (offset) hipLaunchKernelGGL((quantize_kernel<LANES, true, false>), dim3(blocks), dim3(256), 0, stream, pr);
+        else hipLaunchKernelGGL((quantize_kernel<LANES, false, false>), dim3(blocks), dim3(256), 0, stream, pr);
+    }
     return hipGetLastError();
 }
 
@@ -410,7 +425,7 @@ bool quantize_supports(int64_t m, int64_t n, int group)
 }
 
 hipError_t quantize_launch(const _Float16 *w, int p_low, int p_high, int cycles, uint32_t *planes, _Float16 *const *scales_by_p,
-                           _Float16 *const *offsets_by_p, int64_t m, int64_t n, int group, hipStream_t stream)
+                           _Float16 *const *offsets_by_p, int64_t m, int64_t n, int group, bool listing_residual, hipStream_t stream)
 {
     QuantParams pr{};
     pr.w = w;
@@ -426,10 +441,10 @@ hipError_t quantize_launch(const _Float16 *w, int p_low, int p_high, int cycles,
     pr.cycles = cycles;
     const bool offset = offsets_by_p != nullptr;
     switch (group) {
-    case 32: return launch_lanes<1>(pr, offset, stream);
-    case 64: return launch_lanes<2>(pr, offset, stream);
-    case 128: return launch_lanes<4>(pr, offset, stream);
-    default: return launch_lanes<8>(pr, offset, stream);
+    case 32: return launch_lanes<1>(pr, offset, listing_residual, stream);
+    case 64: return launch_lanes<2>(pr, offset, listing_residual, stream);
+    case 128: return launch_lanes<4>(pr, offset, listing_residual, stream);
+    default: return launch_lanes<8>(pr, offset, listing_residual, stream);
     }
 }
 

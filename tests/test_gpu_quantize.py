@@ -18,7 +18,7 @@ from tests.gpu_util import Guarded, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def run_gpu(w, p_low, p_high, cycles, group=128, with_offset=False):
+def run_gpu(w, p_low, p_high, cycles, group=128, with_offset=False, listing=False):
     # every output sits between 4 KiB bands of sentinel values: a store past either end fails the test
     m, n = w.shape
     g_planes = Guarded((p_high, m, n // 32), torch.int32)
@@ -26,7 +26,8 @@ def run_gpu(w, p_low, p_high, cycles, group=128, with_offset=False):
     g_offsets = {p: Guarded((m, n // group)) for p in range(p_low, p_high + 1)} if with_offset else None
     planes, scales, offsets = bcq.bcq_quantize(to_dev(w), p_low, p_high, cycles, group=group, with_offset=with_offset,
                                                planes=g_planes.t, scales_by_p={p: g.t for p, g in g_scales.items()},
-                                               offsets_by_p=None if g_offsets is None else {p: g.t for p, g in g_offsets.items()})
+                                               offsets_by_p=None if g_offsets is None else {p: g.t for p, g in g_offsets.items()},
+                                               listing_residual=listing)
     torch.cuda.synchronize()
     assert bcq.last_kernel() == "quantize"
     what = f"bcq_quantize m={m} n={n} p={p_low}..{p_high} g={group}"
@@ -41,10 +42,10 @@ def run_gpu(w, p_low, p_high, cycles, group=128, with_offset=False):
     return planes, scales, offsets
 
 
-def compare(w, p_low, p_high, cycles, group=128, with_offset=False):
-    print(f"quantize m={w.shape[0]} n={w.shape[1]} p={p_low}..{p_high} T={cycles} g={group} offset={with_offset}", flush=True)
-    planes, scales, offsets = run_gpu(w, p_low, p_high, cycles, group, with_offset)
-    q = oracle.quantize(w, p_low, p_high, cycles, group=group, with_offset=with_offset)
+def compare(w, p_low, p_high, cycles, group=128, with_offset=False, listing=False):
+    print(f"quantize m={w.shape[0]} n={w.shape[1]} p={p_low}..{p_high} T={cycles} g={group} offset={with_offset} listing={listing}", flush=True)
+    planes, scales, offsets = run_gpu(w, p_low, p_high, cycles, group, with_offset, listing)
+    q = oracle.quantize(w, p_low, p_high, cycles, group=group, with_offset=with_offset, literal_residual=listing)
     ref_planes = oracle.pack(q["codes"])
     diff = np.count_nonzero(planes != ref_planes)
     assert diff == 0, f"{diff} of {planes.size} plane words differ"
@@ -115,16 +116,32 @@ def test_quantised_layer_runs_through_the_product():
     assert rel[0] < 0.45 and rel[2] < 0.16
 
 
-@pytest.mark.parametrize("m,n,with_offset", [(14336, 4096, False), (4096, 14336, True)])
-def test_full_size_layers_sampled_rows(m, n, with_offset):
+@pytest.mark.parametrize("m,n", [(64, 1024), (37, 1280)])
+@pytest.mark.parametrize("with_offset", [False, True])
+def test_listing_residual_form(m, n, with_offset):
+    """The expansion residual as Algorithm 1 prints it (all p planes subtracted): bit-exact against the oracle's
+    literal form at the paper's setting and at few cycles, other group sizes, and different from the default form."""
+    w = syn.make_weights(m, n, seed=(98, m))
+    if with_offset:
+        w = (w.astype(np.float32) + 0.03).astype(np.float16)
+    planes_l, scales_l, _ = compare(w, 2, 4, 20, with_offset=with_offset, listing=True)
+    compare(w, 2, 4, 2, with_offset=with_offset, listing=True)
+    compare(w, 1, 3, 3, group=64, with_offset=with_offset, listing=True)
+    compare(w, 3, 4, 4, group=256 if n % 256 == 0 else 32, with_offset=with_offset, listing=True)
+    planes_d, _, _ = run_gpu(w, 2, 4, 20, 128, with_offset)
+    assert np.array_equal(planes_l[:2], planes_d[:2]) and not np.array_equal(planes_l[2:], planes_d[2:])
+
+
+@pytest.mark.parametrize("m,n,with_offset,listing", [(14336, 4096, False, False), (4096, 14336, True, False), (14336, 4096, False, True)])
+def test_full_size_layers_sampled_rows(m, n, with_offset, listing):
     """The benchmark's shapes and settings (p 2..4, T = 20); groups are independent, so the oracle runs on a
     sample of rows and every plane word, scale and offset of those rows must match bit for bit."""
     w = syn.make_weights(m, n, seed=(97, m))
     print(f"quantize full size m={m} n={n} offset={with_offset}", flush=True)
-    planes, scales, offsets = run_gpu(w, 2, 4, 20, 128, with_offset)
+    planes, scales, offsets = run_gpu(w, 2, 4, 20, 128, with_offset, listing)
     rng = np.random.default_rng([syn.BASE_SEED, 97, m])
     rows = np.unique(np.concatenate([[0, 1, m - 1], rng.integers(0, m, size=45)]))
-    q = oracle.quantize(np.ascontiguousarray(w[rows]), 2, 4, 20, with_offset=with_offset)
+    q = oracle.quantize(np.ascontiguousarray(w[rows]), 2, 4, 20, with_offset=with_offset, literal_residual=listing)
     assert np.array_equal(planes[:, rows, :], oracle.pack(q["codes"]))
     for p in (2, 3, 4):
         assert np.array_equal(scales[p][:, rows, :].view(np.uint16), q["scales"][p].astype(np.float16).view(np.uint16))

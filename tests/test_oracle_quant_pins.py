@@ -211,6 +211,39 @@ def test_expansion_cycles_replayed_with_numpy():
     np.testing.assert_allclose(q["scales"][3], alpha, rtol=1e-8, atol=1e-14)
 
 
+@pytest.mark.parametrize("p_high,cycles", [(3, 3), (4, 2), (4, 5)])
+def test_listing_residual_cycles_replayed_with_numpy(p_high, cycles):
+    """The expansion loop exactly as Algorithm 1 prints it (literal_residual=True), replayed with numpy: every cycle
+    takes R = W - Dequant over ALL p planes with the current scales -- the new plane included, zero with a zero
+    scale in the first cycle -- re-signs the new plane with sign(R) and refits all p scales by least squares."""
+    w = gauss(3, 256, 19)
+    wd = w.astype(np.float64)
+    q = oracle.quantize(w, 2, p_high, cycles, literal_residual=True)
+    B = q["codes"].astype(np.float64).copy()
+    alpha = q["scales"][2]
+    for p in range(3, p_high + 1):
+        alpha = np.concatenate([alpha, np.zeros((1, 3, 2))])           # alpha^p starts as [alpha^(p-1), 0]
+        Bp = B[:p].copy()
+        Bp[p - 1] = 0.0                                                # B_p starts as 0
+        for _ in range(cycles):
+            R = wd - sum(np.repeat(alpha[i], 128, axis=1) * Bp[i] for i in range(p))
+            Bp[p - 1] = sign1(R)
+            alpha = lstsq_groups(Bp, wd, 128)
+        assert np.array_equal(q["codes"][p - 1], Bp[p - 1].astype(np.int8)), f"plane {p} differs from the replay"
+        np.testing.assert_allclose(q["scales"][p], alpha, rtol=1e-8, atol=1e-14)
+        assert np.array_equal(q["codes"][:p - 1], B[:p - 1].astype(np.int8))      # frozen planes untouched
+
+
+def test_listing_residual_differs_from_the_default_from_the_second_cycle_on():
+    """Both forms agree after one cycle and part ways from the second (the new plane enters its own residual)."""
+    w = gauss(4, 256, 20)
+    a1, b1 = oracle.quantize(w, 2, 3, 1), oracle.quantize(w, 2, 3, 1, literal_residual=True)
+    assert np.array_equal(a1["codes"], b1["codes"])
+    a2, b2 = oracle.quantize(w, 2, 3, 2), oracle.quantize(w, 2, 3, 2, literal_residual=True)
+    assert np.array_equal(a2["codes"][:2], b2["codes"][:2])
+    assert not np.array_equal(a2["codes"][2], b2["codes"][2])
+
+
 @pytest.mark.parametrize("cycles", [2, 20])
 def test_expansion_ends_with_least_squares(cycles):
     """Each expansion stage ends with LS: its scale set is numpy's least-squares solution for its planes."""

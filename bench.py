@@ -55,21 +55,36 @@ def parse_args():
     return ap.parse_args()
 
 
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2510_10467_amd", "csrc", "bcq_plane_mfma.hip")
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "plane_mfma_llama3_8b_batch1.txt")
+
+
+def kernel_source_sha256():
+    import hashlib
+    with open(KERNEL_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
 def profiled_traffic_bytes(p, m, n):
-    """HBM bytes per launch of the dominant kernel from the committed counter summary (FETCH_SIZE +
-    WRITE_SIZE, scaled by a plain copy), or None when the summary does not cover this kernel."""
-    path = os.path.join(ROOT, "profiles", "plane_mfma_llama3_8b_batch1.txt")
+    """HBM bytes per launch of the dominant kernel from the committed counter summary (FETCH_SIZE + WRITE_SIZE,
+    scaled by a plain copy).  The summary names the sha256 of the kernel source it was taken with; if the source has
+    changed since, or the summary does not cover this kernel, the figure is None (never a stale number).
+    Returns (bytes or None, note)."""
     want = (f"plane_mfma_kernel<{p},1,false>", f"{m}x{n}")
     try:
-        seen_counters = False
-        for line in open(path):
-            seen_counters = seen_counters or line.startswith("HBM traffic counters")
-            parts = line.split()
-            if seen_counters and len(parts) >= 8 and parts[0] == want[0] and parts[1] == want[1]:
-                return int(float(parts[-3]) * 1e6)          # column "scaled MB"
+        text = open(TRAFFIC_PROFILE).read()
     except OSError:
-        pass
-    return None
+        return None, "no counter summary under profiles/"
+    stamp = [line.split()[-1] for line in text.splitlines() if line.startswith("kernel source sha256:")]
+    if not stamp or stamp[0] != kernel_source_sha256():
+        return None, "the kernel source has changed since the counter summary was taken"
+    seen_counters = False
+    for line in text.splitlines():
+        seen_counters = seen_counters or line.startswith("HBM traffic counters")
+        parts = line.split()
+        if seen_counters and len(parts) >= 8 and parts[0] == want[0] and parts[1] == want[1]:
+            return int(float(parts[-3]) * 1e6), "profiles/plane_mfma_llama3_8b_batch1.txt, same kernel source"
+    return None, "the counter summary does not cover this kernel"
 
 
 def run_suite(args, torch, bcq, syn, dev):
@@ -361,7 +376,7 @@ def main():
             fns = [lambda c=c, p=p: run_step(c, (p,)) for c in range(copies)]
         else:
             fns = [capture(lambda c=c, p=p: run_step(c, (p,))).replay for c in range(copies)]
-        ms = timed(fns, max(args.steps // 2, 8), max(args.warmup // 2, 4))
+        ms = timed(fns, max(args.steps, 40), max(args.warmup // 2, 8))
         per_p[str(p)] = {"us_per_layer_set": round(ms * 1e3, 3), "us_per_gemv_mean": round(ms * 1e3 / len(layers), 3),
                          "effective_GBps": round(bytes_per_p[p] / (ms * 1e-3) / 1e9, 1),
                          "pct_of_hbm_peak": round(100 * bytes_per_p[p] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
@@ -413,9 +428,10 @@ def main():
     dom_us = kernel_time_us(dom_li, dom_p)
     dom_bytes = syn.algorithmic_bytes(dm, dn, dom_p, 1)
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    traffic, traffic_note = profiled_traffic_bytes(dom_p, dm, dn)
     roofline = {"bound": "hbm", "kernel": f"plane_mfma_kernel<{dom_p}> m={dm} n={dn} batch=1",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": profiled_traffic_bytes(dom_p, dm, dn),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_note,
                 "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3)}
 
     # What a pure streaming read reaches on this GPU: as many bytes as the dominant kernel moves (cold, rotating
@@ -439,6 +455,102 @@ def main():
                                           "kernel_vs_stream_read": round(us_read / dom_us, 4)}
     roofline["stream_read_1GiB"] = {"us": round(us_big, 1), "GBps": round((1 << 30) / us_big / 1e3, 1)}
 
+    # ---- the same GPU on the half-precision product of the dominant shape (the paper's Table 2 sets its kernel
+    # against one): the library's GEMV and a plain one-wavefront-per-row kernel, rotating over distinct matrices
+    ws = [torch.randn((dm, dn), dtype=torch.float16, device=dev) for _ in range(12)]
+    xv = xs[dn][0]
+    yv = torch.empty((dm,), dtype=torch.float16, device=dev)
+
+    def fp16_burst():
+        for i in range(48):
+            torch.mv(ws[i % len(ws)], xv)
+
+    def fp16_own_burst():
+        for i in range(48):
+            bcq.bench_fp16_gemv(ws[i % len(ws)], xv, yv)
+    fp16_burst()
+    fp16_own_burst()
+    torch.cuda.synchronize()
+    us16 = timed([fp16_burst], 10, 3) * 1e3 / 48
+    us16o = timed([fp16_own_burst if args.no_graph else capture(fp16_own_burst).replay], 10, 3) * 1e3 / 48
+    del ws
+    fp16_gemv = {"m": dm, "n": dn, "bytes": 2 * dm * dn,
+                 "library_torch_mv": {"us": round(us16, 3), "GBps": round(2 * dm * dn / (us16 * 1e-6) / 1e9, 1)},
+                 "plain_hip_kernel": {"us": round(us16o, 3), "GBps": round(2 * dm * dn / (us16o * 1e-6) / 1e9, 1)},
+                 "bcq_p4_speedup_vs_plain_kernel": round(us16o / dom_us, 2)}
+
+    # ---- other configurations, generated on the GPU with the same distributions (cold: >= 1 GiB of copies each)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(syn.BASE_SEED + 1)
+
+    def device_layer(m, n, precisions):
+        planes = torch.randint(-2 ** 31, 2 ** 31 - 1, (syn.P_MAX, m, n // 32), dtype=torch.int32, device=dev, generator=gen)
+        scales = {}
+        for p in precisions:
+            rows = [(torch.randn((m, n // syn.GROUP), device=dev, generator=gen) * 0.02).abs()]
+            for _ in range(1, p):
+                rows.append(rows[-1] * (0.4 + 0.2 * torch.rand((m, n // syn.GROUP), device=dev, generator=gen)))
+            scales[p] = torch.stack(rows).half().contiguous()
+        return planes, scales
+
+    def shape_times(m, n, precisions, launches=32):
+        """us per bcq_gemv call at batch 1 for every p, back-to-back launches over cold copies."""
+        ncopies = min(128, max(2, -(-MIN_ROTATION_BYTES // (m * n // 2))))
+        sets = [device_layer(m, n, precisions) for _ in range(ncopies)]
+        x = torch.randn((1, n), device=dev, generator=gen).half()
+        y = torch.empty((1, m), dtype=torch.float16, device=dev)
+        out = {}
+        for p in precisions:
+            def burst():
+                for i in range(launches):
+                    pl, sc = sets[(i * 7) % ncopies]
+                    bcq.bcq_gemv(pl, sc[p], p, x, y)
+            burst()
+            torch.cuda.synchronize()
+            us = timed([burst if args.no_graph else capture(burst).replay], 10, 3) * 1e3 / launches
+            by = syn.algorithmic_bytes(m, n, p, 1)
+            out[str(p)] = {"us": round(us, 3), "GBps": round(by / us / 1e3, 1), "pct_of_hbm_peak": round(100 * by / us / 1e3 / HBM_PEAK_GBS, 2)}
+        del sets
+        return out
+
+    single_gemv_4096 = {"workload": "single BCQ GEMV m=4096 n=4096 batch 1, p in {1,2,3,4}, group 128", "per_p": shape_times(4096, 4096, (1, 2, 3, 4))}
+    llama70b = {"workload": "Llama-3-70B-shaped layer m=28672 n=8192 batch 1, group 128", "per_p": shape_times(28672, 8192, (2, 4), launches=16)}
+
+    # ---- per-request precision against the uniform kernel: batch 16 on the gate/up shape, each request's precision
+    # drawn uniformly from {2,3,4} (seeded), against uniform batches of 16 at the deepest precision; 40 repeats each,
+    # alternating, the ratio taken over the medians
+    same_shape = [k for k, (_, mm, nn) in enumerate(layers) if (mm, nn) == (dm, dn)]
+    mix_sets = [dev_sets[c][k] for c in range(copies) for k in same_shape]
+    x16 = torch.randn((16, dn), device=dev, generator=gen).half()
+    y16 = torch.empty((16, dm), dtype=torch.float16, device=dev)
+    p_req_h = syn.make_p_req(16, 2, 4, seed=(4, 16))
+    p_req = torch.from_numpy(p_req_h).to(dev)
+
+    def mixed_burst():
+        for i in range(len(mix_sets)):
+            pl, sc = mix_sets[i]
+            bcq.bcq_gemm_mixed(pl, sc, p_req, x16, y16)
+
+    def uniform_burst():
+        for i in range(len(mix_sets)):
+            pl, sc = mix_sets[i]
+            bcq.bcq_gemv(pl, sc[int(p_req_h.max())], int(p_req_h.max()), x16, y16)
+    mixed_burst()
+    mixed_kernel = bcq.last_kernel()
+    uniform_burst()
+    uniform_kernel = bcq.last_kernel()
+    torch.cuda.synchronize()
+    fm = mixed_burst if args.no_graph else capture(mixed_burst).replay
+    fu = uniform_burst if args.no_graph else capture(uniform_burst).replay
+    tm, tu = [], []
+    for _ in range(40):
+        tm.append(timed([fm], 1, 1) * 1e3 / len(mix_sets))
+        tu.append(timed([fu], 1, 1) * 1e3 / len(mix_sets))
+    med = lambda v: sorted(v)[len(v) // 2]
+    mixed_vs_uniform = {"workload": f"batch 16 on {dm}x{dn}, p per request drawn from {{2,3,4}}: " + ",".join(str(v) for v in p_req_h.tolist()),
+                        "mixed_us": round(med(tm), 2), "uniform_p_max_us": round(med(tu), 2), "ratio": round(med(tm) / med(tu), 3),
+                        "repeats": 40, "kernels": {"mixed": mixed_kernel, "uniform": uniform_kernel}, "target_ratio": 1.10}
+
     details = None
     if args.details:
         details = {"kernels": []}
@@ -453,30 +565,6 @@ def main():
                 details["kernels"].append({"m": m, "n": n, "p": p, "us": round(us, 3),
                                            "GBps": round(by / (us * 1e-6) / 1e9, 1),
                                            "pct_of_hbm_peak": round(100 * by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 2)})
-        # fp16 GEMV of the same shape on the same GPU (library GEMV), rotating over distinct matrices
-        ws = [torch.randn((dm, dn), dtype=torch.float16, device=dev) for _ in range(12)]
-        xv = xs[dn][0]
-
-        def fp16_burst():
-            for i in range(48):
-                torch.mv(ws[i % len(ws)], xv)
-        fp16_burst()
-        torch.cuda.synchronize()
-        us16 = timed([fp16_burst], 10, 3) * 1e3 / 48
-        details["fp16_gemv"] = {"m": dm, "n": dn, "us": round(us16, 3), "GBps": round(2 * dm * dn / (us16 * 1e-6) / 1e9, 1)}
-        # the same product with a plain hand-written kernel (one wavefront per row), so that the comparison
-        # does not hinge on a library's choice of kernel
-        yv = torch.empty((dm,), dtype=torch.float16, device=dev)
-
-        def fp16_own_burst():
-            for i in range(48):
-                bcq.bench_fp16_gemv(ws[i % len(ws)], xv, yv)
-        fp16_own_burst()
-        torch.cuda.synchronize()
-        us16o = timed([capture(fp16_own_burst).replay], 10, 3) * 1e3 / 48
-        details["fp16_gemv_plain_kernel"] = {"m": dm, "n": dn, "us": round(us16o, 3),
-                                             "GBps": round(2 * dm * dn / (us16o * 1e-6) / 1e9, 1)}
-        del ws
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -516,6 +604,10 @@ def main():
         "bytes_per_step": bytes_per_step,
         "per_precision": per_p,
         "multi_call": multi_call,
+        "fp16_gemv": fp16_gemv,
+        "single_gemv_4096": single_gemv_4096,
+        "llama70b_batch1": llama70b,
+        "mixed_vs_uniform": mixed_vs_uniform,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }

@@ -593,14 +593,20 @@ Plan make_plan(const GemmArgs &a, bool share_row_blocks = true)
     if (KS < ks_cap / 2 && nslices > ks_cap) KS = ks_cap;   // awkward factorisation: ragged last chunk instead
     pl.KS = KS;
     pl.nchunk = (nslices + KS - 1) / KS;
-    // A workgroup is one row block: every wave builds its own slice of the operand image and no wave
-    // waits for another before the final combine.  Only when a short matrix meets several batch tiles
-    // do row blocks share a workgroup and its image: that halves or quarters the
-    // conversion work of a tile, at the price of workgroup barriers.
+    // With one request a workgroup is one row block: every wave builds its own slice of the operand image and no
+    // wave waits for another before the final combine.  With more, 2 or 4 row blocks share a workgroup and its
+    // image (each wave converts one request slot): that halves or quarters the conversion work of a tile, at the
+    // price of workgroup barriers.
     pl.RB = 1;
     const int64_t row_blocks = (a.m + 15) / 16;
-    if (share_row_blocks && a.batch > kMaxBatchTile && row_blocks < 512)
-        while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= wave_cap && row_blocks / (pl.RB * 2) >= 128) pl.RB *= 2;
+    // From two requests on the conversion outweighs the barriers wherever the matrix still gives about one workgroup
+    // per compute unit afterwards (14336 x 4096 at p = 2 / 4: 9.9 -> 7.9 / 12.9 -> 12.1 us with four requests); short
+    // matrices with several batch tiles share down to 128 workgroups per tile.
+    const int64_t min_groups = a.batch > kMaxBatchTile && row_blocks < 512 ? 128 : 224;
+    if (share_row_blocks && a.batch >= 2)
+        while (pl.RB * 2 <= pl.NB && pl.RB * 2 * KS <= wave_cap && row_blocks / (pl.RB * 2) >= min_groups &&
+               (size_t)lds_total(pl.NB, KS, pl.RB * 2) <= lds_budget())
+            pl.RB *= 2;
     pl.lds_bytes = (size_t)lds_total(pl.NB, KS, pl.RB);
     return pl;
 }

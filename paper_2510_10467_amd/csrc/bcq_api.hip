@@ -51,7 +51,8 @@ int choose(const bcq::GemmArgs &a)
         // Up to 32 requests (one tile of 16 or 32) multiplying the +-1 planes themselves and scaling the group sums
         // beats rebuilding the weights by up to 15 %; beyond that it is the other way round.
         const bool f16_ok = a.group >= 128;                     // the fp16 plane-wise variant needs one scale per 128-column step
-        int from = a.m >= 8192 && a.uniform_p <= 2 ? 5 : 9;
+        // (8192 columns and more: from 5 requests at any precision, 28672 x 8192 at p = 4 and 8 requests 85 -> 70 us)
+        int from = a.m >= 8192 && (a.uniform_p <= 2 || a.n >= 8192) ? 5 : 9;
         bool tiles16 = f16_ok && a.batch <= 32;                 // one tile of 16 or 32 requests
         // Per-request precision: the plane-wise fp16 variant works in tiles of 16 requests whatever mix of
         // precisions they hold (from 9 requests on); rebuilding the weights
@@ -73,7 +74,10 @@ int choose(const bcq::GemmArgs &a)
             pays = a.batch * a.m >= 70000;
             tiles16 = a.batch <= 256;
         }
-        if (dequant_mfma_supports(a) && pays) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
+        // Tall matrices with up to eight requests: the row-streaming form of the FP4 kernel beats both (14336 x 4096,
+        // eight requests: 13.7 us at p = 4 and 9.0 us at p = 2 against 19.4 and 11.9 us).
+        if (plane_mfma_streams(a)) choice = BCQ_KERNEL_PLANE_MFMA;
+        else if (dequant_mfma_supports(a) && pays) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all
         // of its work per request, so the dequantising one wins from the second request on
@@ -96,7 +100,7 @@ int run(const bcq::GemmArgs &a, hipStream_t stream)
     case BCQ_KERNEL_PLANE_MFMA:
         if (!plane_mfma_supports(a)) return BCQ_ERR_VARIANT;
         err = plane_mfma_launch(a, stream);
-        g_last = "plane_mfma";
+        g_last = plane_mfma_streams(a) ? "plane_mfma_rows" : "plane_mfma";      // (the row-streaming form of the family)
         break;
     case BCQ_KERNEL_DEQUANT_MFMA:
         if (!dequant_mfma_supports(a)) return BCQ_ERR_VARIANT;

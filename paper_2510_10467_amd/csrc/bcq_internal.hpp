@@ -46,6 +46,7 @@ bool sign_select_supports(const GemmArgs &a);
 hipError_t sign_select_launch(const GemmArgs &a, hipStream_t stream);
 
 bool plane_mfma_supports(const GemmArgs &a);
+bool plane_mfma_streams(const GemmArgs &a);     // tall matrix, 2 to 8 requests: the row-streaming form takes it
 hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream);
 
 // `count` matrices that share n, precision, batch and activations as ONE launch

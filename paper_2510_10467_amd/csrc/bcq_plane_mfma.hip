@@ -37,6 +37,8 @@
 // order, so results are deterministic and no global scratch is needed.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "bcq_internal.hpp"
 
 namespace bcq {
@@ -556,6 +558,245 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED, GS)) void plane_mfma_kern
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Row-streaming form for tall matrices and two to eight requests.  A workgroup owns four blocks of 16 rows and
+// builds ONE operand image of the whole activation vectors; after that its waves run free: a wave takes a row block
+// and all of its columns (KH = 1) or half of them (KH = 2, the halves meet in LDS at the end) in chunks of 1024,
+// with the loads of the chunk after next already under way while it works, so that what arrives is consumed while
+// the rest still streams in.  With five to eight requests a plane word is expanded once and feeds two matrix
+// instructions (requests 0-3 and 4-7).  The chunks are unrolled (NS, their number per row, is a template argument):
+// inside a loop the compiler waits for every outstanding load at the top of each iteration, which takes the lead away.
+constexpr int kStreamWaves = 4;
+
+template <int PH>
+struct ChunkLoads {
+    u32x4 sc[PH];                           // the 8 scales of the lane's row, per plane
+    u32x4 wa[PH], wb[PH];                   // plane words: rows 0-7 and rows 8-15 of the block
+};
+
+template <int PH>
+__device__ __forceinline__ void issue_chunk(ChunkLoads<PH> &ld, const PlaneMfmaParams &pr, uint32_t o_wa, uint32_t o_wb, uint32_t o_s,
+                                            const unsigned char *sbase, int slice)
+{
+#pragma unroll
+    for (int i = 0; i < PH; ++i)
+        ld.sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)i * pr.scale_plane_stride + (uint32_t)slice * (kSliceGroups * 2) + o_s);
+#pragma unroll
+    for (int i = 0; i < PH; ++i) {
+        const unsigned char *w_base = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice * (kSliceCols / 8);
+        ld.wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w_base + o_wa));
+        ld.wb[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w_base + o_wb));
+    }
+}
+
+template <int P, int NB, int NS, int KH>
+__global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr)
+{
+    using L = Lds<NB>;
+    constexpr int PH = P;
+    constexpr int W = kStreamWaves;                                  // row blocks per workgroup
+    constexpr int NW = W * KH;                                       // waves per workgroup: KH parts of the K range per row block
+    constexpr int NC = NS / KH;                                      // chunks per wave
+    static_assert(NS % KH == 0, "whole chunks per wave");
+    constexpr int NT = NB > kMaxBatchTile ? 2 : 1;                   // matrix instructions per (group, plane)
+    constexpr int XS = (NS + NW - 1) / NW;                           // slices of the image a wave converts
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nb = min(NB, pr.batch);
+    const int rb = wave & (W - 1), kh = wave >> 2;                   // row block of the workgroup, part of the K range
+    static_assert(W == 4, "wave -> (row block, K part)");
+    const int c0 = kh * NC;                                          // first chunk of this wave
+    const uint32_t block_row0 = (blockIdx.x * (uint32_t)W + rb) * 16;
+    const uint32_t last_row = pr.m - 1;
+
+    // plane loads: lane (l >> 3, l & 7) takes group l & 7 (16 bytes) of block rows l >> 3 and 8 + (l >> 3); rows past
+    // the end repeat the last row.  Output side: lane (q, r16) reports row r16 for request slots q and 4 + q.
+    const uint32_t r8 = lane >> 3;
+    const uint32_t o_wa = __umul24(min(block_row0 + r8, last_row), pr.row_stride) + (lane & 7) * 16;
+    const uint32_t o_wb = __umul24(min(block_row0 + 8 + r8, last_row), pr.row_stride) + (lane & 7) * 16;
+    const int q = lane >> 4, r16 = lane & 15;
+    uint32_t row = block_row0 + r16;
+    const bool row_ok = row <= last_row;
+    row = min(row, last_row);
+    const uint32_t o_s = __umul24(row, pr.scale_row_stride);
+    const unsigned char *sbase = pr.scales[P];
+
+    // ---- loads in the order of use (they return in the order in which they were asked for): the activations of the
+    // slices this wave converts (wave, wave + 4, ...), then the first two chunks of planes and scales
+    u32x4 xv[XS][NB][2];
+#pragma unroll
+    for (int k = 0; k < XS; ++k) {
+        const int slice = min(wave + k * NW, NS - 1);
+        const unsigned char *x_base = pr.x + (uint32_t)slice * (kSliceCols * 2) + lane * 32;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const uint32_t xo = (uint32_t)(b < nb ? b : 0) * pr.x_stride;
+            xv[k][b][0] = *reinterpret_cast<const u32x4 *>(x_base + xo);
+            xv[k][b][1] = *reinterpret_cast<const u32x4 *>(x_base + xo + 16);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    ChunkLoads<PH> la, lb;
+    issue_chunk<PH>(la, pr, o_wa, o_wb, o_s, sbase, c0);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (NC > 1) issue_chunk<PH>(lb, pr, o_wa, o_wb, o_s, sbase, c0 + 1);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- operand image of the whole K range (the layout of Lds<NB>, slice after slice)
+    const int u16 = lane & 7;
+#pragma unroll
+    for (int k = 0; k < XS; ++k) {
+        const int slice = wave + k * NW;
+        if (slice < NS) {
+            unsigned char *img_group = lds + slice * L::kSliceImage + (lane >> 3) * L::kGroupBytes;
+            unsigned char *img_unit = img_group + (u16 >> 2) * L::kHalfBytes + (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const u32x4 c0 = xv[k][b][0], c1 = xv[k][b][1];
+                const uint32_t dwd[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+                for (int low = 0; low < 4; ++low) {
+                    const uint32_t sel = (low & 1) ? 0x07060302u : 0x05040100u;
+                    const int k0 = low >> 1;
+                    h2 r01 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 2], dwd[k0], sel));
+                    h2 r23 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 6], dwd[k0 + 4], sel));
+                    const int inv = 3 - low, w = inv >> 1, z = inv & 1;
+                    uint32_t *d32 = reinterpret_cast<uint32_t *>(img_unit + w * (L::kRows * 16) + 8 * z + b * 64);
+                    // the exact four-term split of `sweep`
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t t01 = __builtin_bit_cast(uint32_t, r01) & 0xFF00FF00u;
+                        const uint32_t t23 = __builtin_bit_cast(uint32_t, r23) & 0xFF00FF00u;
+                        if (j < 3) {
+                            const _Float16 c = j == 0 ? (_Float16)4.0f : (_Float16)8.0f;
+                            r01 = (r01 - __builtin_bit_cast(h2, t01)) * h2{c, c};
+                            r23 = (r23 - __builtin_bit_cast(h2, t23)) * h2{c, c};
+                        }
+                        d32[4 * j] = __builtin_amdgcn_perm(t23, t01, 0x07050301u);
+                    }
+                }
+            }
+        }
+    }
+    // the image is complete once every wave's LDS writes are done and the workgroup has met; the global loads under
+    // way stay out of it (the barrier of __syncthreads would wait for them)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    asm volatile("" : "+v"(lane));
+
+    uint32_t sign = 0x88888888u, one = 0x22222222u;
+    asm volatile("" : "+v"(one));
+    asm volatile("" : "+s"(sign));
+    constexpr int kTileRows = NT > 1 ? 16 : L::kRows;               // operand rows of one matrix instruction
+    const int arow = r16 < kTileRows ? r16 : kTileRows - 1;
+    const unsigned char *img_lane0 = lds + (q * L::kRows + arow) * 16;
+    unsigned char *tile = lds + NS * L::kSliceImage + wave * L::kWaveTile;   // NW tiles, then the partial sums
+    unsigned char *tile_wr = tile + (lane >> 3) * L::kTileRow + (lane & 7) * 16;
+    const unsigned char *tile_rd = tile + r16 * L::kTileRow + q * 4;
+
+    float acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = 0.f;
+    auto process = [&](ChunkLoads<PH> &ld, auto c_tag) {
+        constexpr int c = decltype(c_tag)::value;
+        u32x4 sc[PH];
+#pragma unroll
+        for (int i = 0; i < PH; ++i) sc[i] = ld.sc[i];
+        // plane words into operand order through the wave's tile (see `sweep`)
+        uint32_t wt[PH][kSliceGroups];
+#pragma unroll
+        for (int i = 0; i < PH; ++i) {
+            *reinterpret_cast<u32x4 *>(tile_wr) = ld.wa[i];
+            *reinterpret_cast<u32x4 *>(tile_wr + 8 * L::kTileRow) = ld.wb[i];
+#pragma unroll
+            for (int g = 0; g < kSliceGroups; ++g)
+                wt[i][g] = *reinterpret_cast<const uint32_t *>(tile_rd + g * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < PH; ++i)
+#pragma unroll
+            for (int g = 0; g < kSliceGroups; ++g) asm volatile("" : "+v"(wt[i][g]));
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (c + 2 < NC) {
+            // the buffer is free: the chunk after next.  Its addresses depend on a value that exists only from here
+            // on, so the loads cannot be moved up.
+            uint32_t l_wa = o_wa, l_wb = o_wb, l_s = o_s;
+            asm volatile("" : "+v"(l_wa), "+v"(l_wb), "+v"(l_s));
+            issue_chunk<PH>(ld, pr, l_wa, l_wb, l_s, sbase, c0 + c + 2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        const unsigned char *img_lane = img_lane0 + (c0 + c) * L::kSliceImage;
+        u32x4 lo[NT], hi[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            lo[t] = *reinterpret_cast<const u32x4 *>(img_lane + t * 256);
+            hi[t] = *reinterpret_cast<const u32x4 *>(img_lane + t * 256 + L::kHalfBytes);
+        }
+#pragma unroll
+        for (int gl = 0; gl < kSliceGroups; ++gl) {
+            v8i xa[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                xa[t] = v8i{(int)lo[t].x, (int)lo[t].y, (int)lo[t].z, (int)lo[t].w, (int)hi[t].x, (int)hi[t].y, (int)hi[t].z, (int)hi[t].w};
+            if (gl + 1 < kSliceGroups) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    lo[t] = *reinterpret_cast<const u32x4 *>(img_lane + (gl + 1) * L::kGroupBytes + t * 256);
+                    hi[t] = *reinterpret_cast<const u32x4 *>(img_lane + (gl + 1) * L::kGroupBytes + t * 256 + L::kHalfBytes);
+                }
+            }
+            v4f d[PH][NT];
+#pragma unroll
+            for (int i = 0; i < PH; ++i) {
+                const v8i wb = expand_plane_word(wt[i][gl], sign, one);
+                const v4f zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    d[i][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa[t], wb, zero, 1, 4, 0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < PH; ++i) {
+                const uint32_t sw = sc[i][gl >> 1];
+                const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] = fmaf(-alpha, term_sum(d[i][t]), acc[t]);
+            }
+            // the sums are due here: nothing keeps matrix results for later
+#pragma unroll
+            for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[t]));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto run = [&](auto self, auto c_tag) {
+        constexpr int c = decltype(c_tag)::value;
+        if constexpr (c < NC) {
+            process((c & 1) ? lb : la, c_tag);
+            self(self, std::integral_constant<int, c + 1>{});
+        }
+    };
+    run(run, std::integral_constant<int, 0>{});
+    if constexpr (KH > 1) {
+        // the parts of a row block meet in LDS, added in a fixed order
+        float *red = reinterpret_cast<float *>(lds + NS * L::kSliceImage + NW * L::kWaveTile);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) red[(wave * NT + t) * 64 + lane] = acc[t];
+        __syncthreads();
+        if (kh != 0) return;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            float v = 0.f;
+#pragma unroll
+            for (int k = 0; k < KH; ++k) v += red[((k * W + rb) * NT + t) * 64 + lane];
+            acc[t] = v;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+        if (row_ok && 4 * t + q < nb) pr.y[(size_t)(4 * t + q) * pr.m + row] = (_Float16)acc[t];
+}
+
 // LDS a workgroup may ask for (160 KiB on gfx950), asked of the runtime once
 size_t lds_budget()
 {
@@ -652,7 +893,83 @@ hipError_t launch_multi_nb(int p, const PlaneMfmaParams &pr, const Plan &pl, dim
     }
 }
 
+// Row streaming: which problems take it, and its launch.  Measured against the kernel above on 14336 x 4096,
+// 17920 x 5120 and 28672 x 8192 at p = 1 .. 4: 3 to 45 % faster from two requests on (28672 x 8192, four requests,
+// p = 2: 33 -> 22 us; 14336 x 4096, eight requests, p = 4: 19.4 -> 13.7 us), except for the two cases left out below
+// (3 % slower); with one request it is slower (one wave per SIMD then does all of a row block's arithmetic in turn).
+struct StreamPlan {
+    bool ok;
+    int NB, NS, KH;
+    size_t lds_bytes;
+};
+
+StreamPlan make_stream_plan(const GemmArgs &a)
+{
+    StreamPlan sp{};
+    bool any_offsets = false;
+    for (int q = 1; q <= kMaxP; ++q) any_offsets = any_offsets || a.offsets[q] != nullptr;
+    const int64_t row_blocks = (a.m + 15) / 16;
+    // tall enough for about one workgroup of four row blocks per compute unit; whole chunks; 4 to 8 of them
+    if (a.uniform_p < 1 || a.uniform_p > kMaxP || any_offsets || a.group != 128 || a.batch < 2 || a.batch > 2 * kMaxBatchTile ||
+        row_blocks < 768 || a.n % kSliceCols != 0)
+        return sp;
+    sp.NS = (int)(a.n / kSliceCols);
+    if (sp.NS < 4 || sp.NS > 8) return sp;
+    sp.NB = a.batch <= 2 ? 2 : a.batch <= 4 ? 4 : 8;
+    sp.KH = sp.NB == 8 ? 2 : 1;                // eight requests: two waves per SIMD hide each other's matrix instructions
+    if (sp.KH == 2 && sp.NS % 2 != 0) return sp;
+    if ((sp.NB == 2 && a.uniform_p == 4 && sp.NS == 4) || (sp.NB == 4 && a.uniform_p == 4 && sp.NS == 5)) return sp;
+    const size_t image = (size_t)sp.NS * (sp.NB == 2 ? Lds<2>::kSliceImage : sp.NB == 4 ? Lds<4>::kSliceImage : Lds<8>::kSliceImage);
+    const int waves = kStreamWaves * sp.KH;
+    sp.lds_bytes = image + (size_t)waves * Lds<1>::kWaveTile + (sp.KH > 1 ? (size_t)waves * 2 * 64 * sizeof(float) : 0);
+    sp.ok = sp.lds_bytes <= lds_budget() && (sp.NB < 8 || sp.NS == 4);      // (eight requests: instantiated for four chunks)
+    return sp;
+}
+
+template <int P, int NB, int NS, int KH>
+hipError_t launch_stream_one(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
+{
+    auto kernel = plane_rowstream_kernel<P, NB, NS, KH>;
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)sp.lds_bytes)) return e;
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * kStreamWaves * KH), sp.lds_bytes, stream, pr);
+    return hipGetLastError();
+}
+
+template <int P, int NB>
+hipError_t launch_stream_ns(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
+{
+    switch (sp.NS) {
+    case 4: return launch_stream_one<P, NB, 4, 1>(pr, sp, grid, stream);
+    case 5: return launch_stream_one<P, NB, 5, 1>(pr, sp, grid, stream);
+    case 6: return launch_stream_one<P, NB, 6, 1>(pr, sp, grid, stream);
+    case 7: return launch_stream_one<P, NB, 7, 1>(pr, sp, grid, stream);
+    default: return launch_stream_one<P, NB, 8, 1>(pr, sp, grid, stream);
+    }
+}
+
+template <int P>
+hipError_t launch_stream_p(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
+{
+    if (sp.NB == 2) return launch_stream_ns<P, 2>(pr, sp, grid, stream);
+    if (sp.NB == 4) return launch_stream_ns<P, 4>(pr, sp, grid, stream);
+    return launch_stream_one<P, 8, 4, 2>(pr, sp, grid, stream);
+}
+
+hipError_t launch_stream(const GemmArgs &a, const PlaneMfmaParams &pr, const StreamPlan &sp, hipStream_t stream)
+{
+    const int64_t row_blocks = (a.m + 15) / 16;
+    dim3 grid((unsigned)((row_blocks + kStreamWaves - 1) / kStreamWaves));
+    switch (a.uniform_p) {
+    case 1: return launch_stream_p<1>(pr, sp, grid, stream);
+    case 2: return launch_stream_p<2>(pr, sp, grid, stream);
+    case 3: return launch_stream_p<3>(pr, sp, grid, stream);
+    default: return launch_stream_p<4>(pr, sp, grid, stream);
+    }
+}
+
 }  // namespace
+
+bool plane_mfma_streams(const GemmArgs &a) { return plane_mfma_supports(a) && make_stream_plan(a).ok; }
 
 bool plane_mfma_supports(const GemmArgs &a)
 {
@@ -708,6 +1025,7 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.inv_span = 1.0f / (float)(8 * pr.ntiles);
     pr.inv_ks = 1.0f / (float)pl.KS;
     dim3 block(64 * pl.KS * pl.RB);
+    if (const StreamPlan sp = make_stream_plan(a); sp.ok) return launch_stream(a, pr, sp, stream);
     if (with_offsets) {
         switch (pl.NB) {
         case 1: return launch_nb<1, true>(a, pr, pl, grid, block, stream);

@@ -51,6 +51,72 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
             sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"{name} p={p} batch={batch} ({bcq.last_kernel()})")
 
 
+@pytest.mark.parametrize("m,n", [(12300, 4096), (12290, 5120), (12400, 6144), (12500, 7168), (12304, 8192)])
+def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):
+    """Tall matrices with two to eight requests run the FP4 family in its row-streaming form (one operand image per
+    four row blocks, chunks of 1024 columns prefetched two ahead): 4 to 8 chunks per row, one and two request tiles,
+    a last workgroup with absent row blocks and a ragged last block; the shapes and batches it leaves to the other
+    kernels are checked in the same loop."""
+    import paper_2510_10467_amd as bcq
+    layer = syn.make_layer(m, n, seed=(270, m, n), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    rng = np.random.default_rng([syn.BASE_SEED, 270, m])
+    rows = np.unique(np.concatenate([[0, 15, 16, 63, 64, m - 65, m - 64, m - 17, m - 16, m - 13, m - 2, m - 1], rng.integers(0, m, size=150)]))
+    streamed = 0
+    for batch in (2, 3, 4, 5, 7, 8):
+        x = syn.make_x(batch, n, seed=(270, batch))
+        xd = gpu.to_dev(x)
+        for p in (1, 2, 3, 4):
+            out = gpu.Guarded((batch, m))
+            bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd, y=out.t)
+            used = bcq.last_kernel()
+            streamed += used == "plane_mfma_rows"
+            y = out.check(f"m={m} n={n} p={p} batch={batch} ({used})")
+            sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"m={m} n={n} p={p} batch={batch} ({used})")
+            if used == "plane_mfma_rows":
+                again = bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd)
+                assert np.array_equal(again.cpu().numpy().view(np.uint16), y.cpu().numpy().view(np.uint16)), "not deterministic"
+    # up to four requests at every width (but two requests at 4096 and three or four at 5120 columns, p = 4), five to
+    # eight at 4096 columns
+    assert streamed == {4096: 23, 5120: 10}.get(n, 12), streamed
+
+
+def test_row_streaming_form_reads_every_binary16_activation_exactly(gpu):
+    """The row-streaming form builds its operand image with code of its own: every finite binary16 value, alone in its
+    scale group, against rows whose only non-zero scale (1.0, one plane) sits on that group, comes back bit for bit
+    (two, four and eight requests: one and two request tiles)."""
+    import paper_2510_10467_amd as bcq
+    m = 12288
+    values = np.arange(65536, dtype=np.uint16).view(np.float16)
+    values = values[np.isfinite(values)]                              # 63488 values
+    seen = set()
+    for n, batch, launches in ((8192, 4, None), (8192, 2, 40), (4096, 8, 40)):
+        groups = n // 128
+        rng = np.random.default_rng([syn.BASE_SEED, 271, n])
+        planes = rng.integers(0, 2 ** 32, size=(1, m, n // 32), dtype=np.uint32)
+        group_of_row = np.arange(m) % groups                          # row r reads group r mod groups
+        scales = np.zeros((1, m, groups), dtype=np.float16)
+        scales[0, np.arange(m), group_of_row] = 1.0
+        cols = np.arange(groups) * 128 + rng.integers(0, 128, size=groups)       # where in its group a value sits
+        col_of_row = cols[group_of_row]
+        bit = (planes[0, np.arange(m), col_of_row // 32] >> (col_of_row % 32).astype(np.uint32)) & 1
+        sign = np.where(bit == 1, 1.0, -1.0)
+        x = np.zeros((len(values) // groups, n), dtype=np.float16)
+        x[:, cols] = values.reshape(-1, groups)
+        planes_d, scales_d = gpu.to_dev(planes), gpu.to_dev(scales)
+        for k, start in enumerate(range(0, x.shape[0], batch)):
+            if launches is not None and k >= launches:
+                break                                                 # two and eight requests only sample
+            xb = x[start:start + batch]
+            y = bcq.bcq_gemv(planes_d, scales_d, 1, gpu.to_dev(xb)).cpu().numpy()
+            seen.add(bcq.last_kernel())
+            want = (xb[:, col_of_row].astype(np.float64) * sign[None, :]).astype(np.float16)
+            same = (y.view(np.uint16) == want.view(np.uint16)) | ((y == 0) & (want == 0))
+            assert np.all(same), (f"n={n} batch {batch}: {np.count_nonzero(~same)} values not reproduced, first "
+                                  f"{want[~same][0]!r} -> {y[~same][0]!r}")
+    assert seen == {"plane_mfma_rows"}, seen
+
+
 def test_prefix_invariance_and_determinism(gpu):
     """Only the first p planes are read (section 3.3): scrambling the others leaves y bit-identical;
     repeated launches give bit-identical results."""

@@ -555,6 +555,29 @@ def main():
                         "mixed_us": round(med(tm), 2), "uniform_p_max_us": round(med(tu), 2), "ratio": round(med(tm) / med(tu), 3),
                         "repeats": 40, "kernels": {"mixed": mixed_kernel, "uniform": uniform_kernel}, "target_ratio": 1.10}
 
+    # ---- decode batches (uniform precision) on the gate/up and the down shape, over the copies already resident:
+    # us per call, the kernel that ran, and the share of the HBM peak the algorithmic bytes come to
+    decode_batches = {"workload": "decode batches 2..32, uniform p in {2,3,4}, group 128; us per call over cold copies", "rows": []}
+    for (m_d, n_d) in ((dm, dn), (dn, dm)):
+        shape_sets = [dev_sets[c][k] for c in range(copies) for k, (_, mm, nn) in enumerate(layers) if (mm, nn) == (m_d, n_d)]
+        if not shape_sets:
+            continue
+        for batch in (2, 4, 8, 16, 32):
+            xb = torch.randn((batch, n_d), device=dev, generator=gen).half()
+            yb = torch.empty((batch, m_d), dtype=torch.float16, device=dev)
+            for p in PRECISIONS:
+                def burst():
+                    for pl, sc in shape_sets:
+                        bcq.bcq_gemv(pl, sc[p], p, xb, yb)
+                burst()
+                used = bcq.last_kernel()
+                torch.cuda.synchronize()
+                fn = burst if args.no_graph else capture(burst).replay
+                us = sorted(timed([fn], 4, 2 if k == 0 else 0) for k in range(3))[1] * 1e3 / len(shape_sets)
+                by = syn.algorithmic_bytes(m_d, n_d, p, batch)
+                decode_batches["rows"].append({"m": m_d, "n": n_d, "batch": batch, "p": p, "kernel": used, "us": round(us, 2),
+                                               "pct_of_hbm_peak": round(100 * by / us / 1e3 / HBM_PEAK_GBS, 1)})
+
     details = None
     if args.details:
         details = {"kernels": []}
@@ -612,6 +635,7 @@ def main():
         "single_gemv_4096": single_gemv_4096,
         "llama70b_batch1": llama70b,
         "mixed_vs_uniform": mixed_vs_uniform,
+        "decode_batches": decode_batches,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }

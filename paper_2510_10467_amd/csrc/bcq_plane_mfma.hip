@@ -599,7 +599,10 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
     constexpr int NC = NS / KH;                                      // chunks per wave
     static_assert(NS % KH == 0, "whole chunks per wave");
     constexpr int NT = NB > kMaxBatchTile ? 2 : 1;                   // matrix instructions per (group, plane)
-    constexpr int XS = (NS + NW - 1) / NW;                           // slices of the image a wave converts
+    // the image is converted in NS * RG jobs (a slice of 1024 columns x NB / RG requests), job j by wave j mod NW
+    constexpr int RG = NB >= KH ? KH : 1;
+    constexpr int NBC = NB / RG;
+    constexpr int XS = (NS * RG + NW - 1) / NW;                      // jobs per wave
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
     int lane = tid & 63;
@@ -623,39 +626,46 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
     const uint32_t o_s = __umul24(row, pr.scale_row_stride);
     const unsigned char *sbase = pr.scales[P];
 
-    // ---- loads in the order of use (they return in the order in which they were asked for): the activations of the
-    // slices this wave converts (wave, wave + 4, ...), then the first two chunks of planes and scales
-    u32x4 xv[XS][NB][2];
+    // ---- loads in the order of use (they return in the order in which they were asked for): the activations of this
+    // wave's conversion jobs, then its first chunk of planes and scales and, with a lead of two chunks, its second
+    u32x4 xv[XS][NBC][2];
 #pragma unroll
     for (int k = 0; k < XS; ++k) {
-        const int slice = min(wave + k * NW, NS - 1);
+        const int j = wave + k * NW;
+        const int slice = min(j / RG, NS - 1), b0 = (j % RG) * NBC;
         const unsigned char *x_base = pr.x + (uint32_t)slice * (kSliceCols * 2) + lane * 32;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const uint32_t xo = (uint32_t)(b < nb ? b : 0) * pr.x_stride;
+        for (int b = 0; b < NBC; ++b) {
+            const uint32_t xo = (uint32_t)(b0 + b < nb ? b0 + b : 0) * pr.x_stride;
             xv[k][b][0] = *reinterpret_cast<const u32x4 *>(x_base + xo);
             xv[k][b][1] = *reinterpret_cast<const u32x4 *>(x_base + xo + 16);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
+    // How far the loads run ahead of the sweep: ONE chunk, asked for when the chunk before it has arrived and left
+    // its registers.  With a lead of two every wave's first two chunks queue up wave after wave, and a compute unit
+    // returns loads in the order asked: the last wave sees its first byte when the others are nearly done (14336 x
+    // 4096, p = 4: four requests 11.7 -> 9.6 us, eight requests 14.5 -> 12.2 us; 28672 x 8192, four requests: 38.8 -> 33.0).
+    constexpr int D = 1;
     ChunkLoads<PH> la, lb;
     issue_chunk<PH>(la, pr, o_wa, o_wb, o_s, sbase, c0);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (NC > 1) issue_chunk<PH>(lb, pr, o_wa, o_wb, o_s, sbase, c0 + 1);
+    if constexpr (NC > 1 && D == 2) issue_chunk<PH>(lb, pr, o_wa, o_wb, o_s, sbase, c0 + 1);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- operand image of the whole K range (the layout of Lds<NB>, slice after slice)
     const int u16 = lane & 7;
 #pragma unroll
     for (int k = 0; k < XS; ++k) {
-        const int slice = wave + k * NW;
-        if (slice < NS) {
+        const int j = wave + k * NW;
+        if (j < NS * RG) {
+            const int slice = j / RG, b0 = (j % RG) * NBC;
             unsigned char *img_group = lds + slice * L::kSliceImage + (lane >> 3) * L::kGroupBytes;
             unsigned char *img_unit = img_group + (u16 >> 2) * L::kHalfBytes + (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const u32x4 c0 = xv[k][b][0], c1 = xv[k][b][1];
-                const uint32_t dwd[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+            for (int b = 0; b < NBC; ++b) {
+                const u32x4 v0 = xv[k][b][0], v1 = xv[k][b][1];
+                const uint32_t dwd[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
                 for (int low = 0; low < 4; ++low) {
                     const uint32_t sel = (low & 1) ? 0x07060302u : 0x05040100u;
@@ -663,7 +673,7 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
                     h2 r01 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 2], dwd[k0], sel));
                     h2 r23 = __builtin_bit_cast(h2, __builtin_amdgcn_perm(dwd[k0 + 6], dwd[k0 + 4], sel));
                     const int inv = 3 - low, w = inv >> 1, z = inv & 1;
-                    uint32_t *d32 = reinterpret_cast<uint32_t *>(img_unit + w * (L::kRows * 16) + 8 * z + b * 64);
+                    uint32_t *d32 = reinterpret_cast<uint32_t *>(img_unit + w * (L::kRows * 16) + 8 * z + (b0 + b) * 64);
                     // the exact four-term split of `sweep`
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
@@ -718,12 +728,12 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
 #pragma unroll
             for (int g = 0; g < kSliceGroups; ++g) asm volatile("" : "+v"(wt[i][g]));
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (c + 2 < NC) {
-            // the buffer is free: the chunk after next.  Its addresses depend on a value that exists only from here
-            // on, so the loads cannot be moved up.
+        if constexpr (c + D < NC) {
+            // a buffer is free (this one for a lead of two chunks, the other one for a lead of one): the next loads.
+            // Their addresses depend on a value that exists only from here on, so the loads cannot be moved up.
             uint32_t l_wa = o_wa, l_wb = o_wb, l_s = o_s;
             asm volatile("" : "+v"(l_wa), "+v"(l_wb), "+v"(l_s));
-            issue_chunk<PH>(ld, pr, l_wa, l_wb, l_s, sbase, c0 + c + 2);
+            issue_chunk<PH>(D == 2 ? ld : ((c & 1) ? la : lb), pr, l_wa, l_wb, l_s, sbase, c0 + c + D);
         }
         __builtin_amdgcn_sched_barrier(0);
 
@@ -894,9 +904,9 @@ hipError_t launch_multi_nb(int p, const PlaneMfmaParams &pr, const Plan &pl, dim
 }
 
 // Row streaming: which problems take it, and its launch.  Measured against the kernel above on 14336 x 4096,
-// 17920 x 5120 and 28672 x 8192 at p = 1 .. 4: 3 to 45 % faster from two requests on (28672 x 8192, four requests,
-// p = 2: 33 -> 22 us; 14336 x 4096, eight requests, p = 4: 19.4 -> 13.7 us), except for the two cases left out below
-// (3 % slower); with one request it is slower (one wave per SIMD then does all of a row block's arithmetic in turn).
+// 17920 x 5120 and 28672 x 8192 at p = 1 .. 4 and two to eight requests: never slower, up to 45 % faster (14336 x 4096,
+// p = 4: two requests 10.9 -> 9.5 us, four 12.1 -> 9.7, eight 19.4 -> 12.2; 28672 x 8192, four requests, p = 2: 33 -> 21).
+// With one request it is no faster (one or two waves per SIMD then do all of a row block's arithmetic in turn).
 struct StreamPlan {
     bool ok;
     int NB, NS, KH;
@@ -918,7 +928,6 @@ StreamPlan make_stream_plan(const GemmArgs &a)
     sp.NB = a.batch <= 2 ? 2 : a.batch <= 4 ? 4 : 8;
     sp.KH = sp.NB == 8 ? 2 : 1;                // eight requests: two waves per SIMD hide each other's matrix instructions
     if (sp.KH == 2 && sp.NS % 2 != 0) return sp;
-    if ((sp.NB == 2 && a.uniform_p == 4 && sp.NS == 4) || (sp.NB == 4 && a.uniform_p == 4 && sp.NS == 5)) return sp;
     const size_t image = (size_t)sp.NS * (sp.NB == 2 ? Lds<2>::kSliceImage : sp.NB == 4 ? Lds<4>::kSliceImage : Lds<8>::kSliceImage);
     const int waves = kStreamWaves * sp.KH;
     sp.lds_bytes = image + (size_t)waves * Lds<1>::kWaveTile + (sp.KH > 1 ? (size_t)waves * 2 * 64 * sizeof(float) : 0);

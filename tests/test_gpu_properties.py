@@ -76,9 +76,8 @@ def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):
             if used == "plane_mfma_rows":
                 again = bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd)
                 assert np.array_equal(again.cpu().numpy().view(np.uint16), y.cpu().numpy().view(np.uint16)), "not deterministic"
-    # up to four requests at every width (but two requests at 4096 and three or four at 5120 columns, p = 4), five to
-    # eight at 4096 columns
-    assert streamed == {4096: 23, 5120: 10}.get(n, 12), streamed
+    # up to four requests at every width, five to eight at 4096 columns
+    assert streamed == (24 if n == 4096 else 12), streamed
 
 
 def test_row_streaming_form_reads_every_binary16_activation_exactly(gpu):

@@ -51,7 +51,7 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
             sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"{name} p={p} batch={batch} ({bcq.last_kernel()})")
 
 
-@pytest.mark.parametrize("m,n", [(12300, 4096), (12290, 5120), (12400, 6144), (12500, 7168), (12304, 8192)])
+@pytest.mark.parametrize("m,n", [(12300, 4096), (12290, 5120), (12400, 6144), (12500, 7168), (12304, 8192), (10236, 4096), (8200, 4096)])
 def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):
     """Tall matrices with two to eight requests run the FP4 family in its row-streaming form (one operand image per
     four row blocks, chunks of 1024 columns prefetched two ahead): 4 to 8 chunks per row, one and two request tiles,
@@ -76,8 +76,8 @@ def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):
             if used == "plane_mfma_rows":
                 again = bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd)
                 assert np.array_equal(again.cpu().numpy().view(np.uint16), y.cpu().numpy().view(np.uint16)), "not deterministic"
-    # up to four requests at every width, five to eight at 4096 columns
-    assert streamed == (24 if n == 4096 else 12), streamed
+    # up to four requests at every width from 640 row blocks on, five to eight at 4096 columns from 512 row blocks on
+    assert streamed == (0 if m < 10225 else 12) + (12 if n == 4096 else 0), streamed
 
 
 def test_row_streaming_form_reads_every_binary16_activation_exactly(gpu):

@@ -568,19 +568,25 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED, GS)) void plane_mfma_kern
 // inside a loop the compiler waits for every outstanding load at the top of each iteration, which takes the lead away.
 constexpr int kStreamWaves = 4;
 
-template <int PH>
+// NS: scale sets a lane needs: one, or with per-request precision one per request tile (a lane reports one request of each)
+template <int PH, int NSC>
 struct ChunkLoads {
-    u32x4 sc[PH];                           // the 8 scales of the lane's row, per plane
+    u32x4 sc[NSC][PH];                      // the 8 scales of the lane's row, per plane
     u32x4 wa[PH], wb[PH];                   // plane words: rows 0-7 and rows 8-15 of the block
 };
 
-template <int PH>
-__device__ __forceinline__ void issue_chunk(ChunkLoads<PH> &ld, const PlaneMfmaParams &pr, uint32_t o_wa, uint32_t o_wb, uint32_t o_s,
-                                            const unsigned char *sbase, int slice)
+template <int PH, int NSC>
+__device__ __forceinline__ void issue_chunk(ChunkLoads<PH, NSC> &ld, const PlaneMfmaParams &pr, uint32_t o_wa, uint32_t o_wb, uint32_t o_s,
+                                            const unsigned char *const *sbase, const int *p_own, int slice)
 {
 #pragma unroll
-    for (int i = 0; i < PH; ++i)
-        ld.sc[i] = *reinterpret_cast<const u32x4 *>(sbase + (size_t)i * pr.scale_plane_stride + (uint32_t)slice * (kSliceGroups * 2) + o_s);
+    for (int t = 0; t < NSC; ++t)
+#pragma unroll
+        for (int i = 0; i < PH; ++i) {
+            // (per-request precision: a lane stays inside its own request's set, which has p_own planes)
+            const int ii = min(i, max(p_own[t], 1) - 1);
+            ld.sc[t][i] = *reinterpret_cast<const u32x4 *>(sbase[t] + (size_t)ii * pr.scale_plane_stride + (uint32_t)slice * (kSliceGroups * 2) + o_s);
+        }
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
         const unsigned char *w_base = pr.planes + (size_t)i * pr.plane_stride + (uint32_t)slice * (kSliceCols / 8);
@@ -589,21 +595,51 @@ __device__ __forceinline__ void issue_chunk(ChunkLoads<PH> &ld, const PlaneMfmaP
     }
 }
 
-template <int P, int NB, int NS, int KH>
-__global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr)
+// The activations a wave converts into the operand image: the image is converted in NS * RG jobs (a slice of 1024
+// columns x NB / RG requests), job j by wave j mod NW.  They are the first loads of a wave and depend on nothing but
+// the shape, so they go out before anything else is known (with per-request precision: before the precisions are).
+template <int NB, int NS, int KH>
+struct StreamActivations {
+    static constexpr int NW = kStreamWaves * KH;
+    static constexpr int RG = NB >= KH ? KH : 1;
+    static constexpr int NBC = NB / RG;
+    static constexpr int XS = (NS * RG + NW - 1) / NW;               // jobs per wave
+    u32x4 v[XS][NBC][2];
+    __device__ __forceinline__ void load(const PlaneMfmaParams &pr)
+    {
+        const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int nb = min(NB, pr.batch);
+#pragma unroll
+        for (int k = 0; k < XS; ++k) {
+            const int j = wave + k * NW;
+            const int slice = min(j / RG, NS - 1), b0 = (j % RG) * NBC;
+            const unsigned char *x_base = pr.x + (uint32_t)slice * (kSliceCols * 2) + lane * 32;
+#pragma unroll
+            for (int b = 0; b < NBC; ++b) {
+                const uint32_t xo = (uint32_t)(b0 + b < nb ? b0 + b : 0) * pr.x_stride;
+                v[k][b][0] = *reinterpret_cast<const u32x4 *>(x_base + xo);
+                v[k][b][1] = *reinterpret_cast<const u32x4 *>(x_base + xo + 16);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+};
+
+// PH: planes fetched (the precision, or with per-request precision the deepest one present); p_own[t]: the precision of
+// the request this lane reports on in tile t (PH when uniform, 0: none), sbase[t] its scale set
+template <int PH, int NB, int NS, int KH, bool MIXED>
+__device__ __forceinline__ void rowstream_body(const PlaneMfmaParams &pr, unsigned char *lds, const StreamActivations<NB, NS, KH> &xs,
+                                               const int *p_own, const unsigned char *const *sbase)
 {
     using L = Lds<NB>;
-    constexpr int PH = P;
     constexpr int W = kStreamWaves;                                  // row blocks per workgroup
     constexpr int NW = W * KH;                                       // waves per workgroup: KH parts of the K range per row block
     constexpr int NC = NS / KH;                                      // chunks per wave
     static_assert(NS % KH == 0, "whole chunks per wave");
     constexpr int NT = NB > kMaxBatchTile ? 2 : 1;                   // matrix instructions per (group, plane)
-    // the image is converted in NS * RG jobs (a slice of 1024 columns x NB / RG requests), job j by wave j mod NW
-    constexpr int RG = NB >= KH ? KH : 1;
-    constexpr int NBC = NB / RG;
-    constexpr int XS = (NS * RG + NW - 1) / NW;                      // jobs per wave
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    using XA = StreamActivations<NB, NS, KH>;
+    constexpr int RG = XA::RG, NBC = XA::NBC, XS = XA::XS;
+    constexpr int NSC = MIXED ? NT : 1;                              // scale sets per lane
     const int tid = threadIdx.x;
     int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -624,33 +660,18 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
     const bool row_ok = row <= last_row;
     row = min(row, last_row);
     const uint32_t o_s = __umul24(row, pr.scale_row_stride);
-    const unsigned char *sbase = pr.scales[P];
 
     // ---- loads in the order of use (they return in the order in which they were asked for): the activations of this
-    // wave's conversion jobs, then its first chunk of planes and scales and, with a lead of two chunks, its second
-    u32x4 xv[XS][NBC][2];
-#pragma unroll
-    for (int k = 0; k < XS; ++k) {
-        const int j = wave + k * NW;
-        const int slice = min(j / RG, NS - 1), b0 = (j % RG) * NBC;
-        const unsigned char *x_base = pr.x + (uint32_t)slice * (kSliceCols * 2) + lane * 32;
-#pragma unroll
-        for (int b = 0; b < NBC; ++b) {
-            const uint32_t xo = (uint32_t)(b0 + b < nb ? b0 + b : 0) * pr.x_stride;
-            xv[k][b][0] = *reinterpret_cast<const u32x4 *>(x_base + xo);
-            xv[k][b][1] = *reinterpret_cast<const u32x4 *>(x_base + xo + 16);
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
+    // wave's conversion jobs are under way (xs), now its first chunk of planes and scales
     // How far the loads run ahead of the sweep: ONE chunk, asked for when the chunk before it has arrived and left
     // its registers.  With a lead of two every wave's first two chunks queue up wave after wave, and a compute unit
     // returns loads in the order asked: the last wave sees its first byte when the others are nearly done (14336 x
     // 4096, p = 4: four requests 11.7 -> 9.6 us, eight requests 14.5 -> 12.2 us; 28672 x 8192, four requests: 38.8 -> 33.0).
     constexpr int D = 1;
-    ChunkLoads<PH> la, lb;
-    issue_chunk<PH>(la, pr, o_wa, o_wb, o_s, sbase, c0);
+    ChunkLoads<PH, NSC> la, lb;
+    issue_chunk<PH, NSC>(la, pr, o_wa, o_wb, o_s, sbase, p_own, c0);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (NC > 1 && D == 2) issue_chunk<PH>(lb, pr, o_wa, o_wb, o_s, sbase, c0 + 1);
+    if constexpr (NC > 1 && D == 2) issue_chunk<PH, NSC>(lb, pr, o_wa, o_wb, o_s, sbase, p_own, c0 + 1);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- operand image of the whole K range (the layout of Lds<NB>, slice after slice)
@@ -664,7 +685,7 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
             unsigned char *img_unit = img_group + (u16 >> 2) * L::kHalfBytes + (2 * ((u16 >> 1) & 1) * L::kRows) * 16 + 4 * (u16 & 1);
 #pragma unroll
             for (int b = 0; b < NBC; ++b) {
-                const u32x4 v0 = xv[k][b][0], v1 = xv[k][b][1];
+                const u32x4 v0 = xs.v[k][b][0], v1 = xs.v[k][b][1];
                 const uint32_t dwd[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
                 for (int low = 0; low < 4; ++low) {
@@ -708,11 +729,17 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
     float acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = 0.f;
-    auto process = [&](ChunkLoads<PH> &ld, auto c_tag) {
+    auto process = [&](ChunkLoads<PH, NSC> &ld, auto c_tag) {
         constexpr int c = decltype(c_tag)::value;
-        u32x4 sc[PH];
+        u32x4 sc[NSC][PH];
 #pragma unroll
-        for (int i = 0; i < PH; ++i) sc[i] = ld.sc[i];
+        for (int t = 0; t < NSC; ++t)
+#pragma unroll
+            for (int i = 0; i < PH; ++i) {
+                sc[t][i] = ld.sc[t][i];
+                // scales of planes the lane's request does not use (beyond its precision; an absent request) become zero
+                if (MIXED && !(i < p_own[t])) sc[t][i] = u32x4{0, 0, 0, 0};
+            }
         // plane words into operand order through the wave's tile (see `sweep`)
         uint32_t wt[PH][kSliceGroups];
 #pragma unroll
@@ -733,7 +760,7 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
             // Their addresses depend on a value that exists only from here on, so the loads cannot be moved up.
             uint32_t l_wa = o_wa, l_wb = o_wb, l_s = o_s;
             asm volatile("" : "+v"(l_wa), "+v"(l_wb), "+v"(l_s));
-            issue_chunk<PH>(D == 2 ? ld : ((c & 1) ? la : lb), pr, l_wa, l_wb, l_s, sbase, c0 + c + D);
+            issue_chunk<PH, NSC>(D == 2 ? ld : ((c & 1) ? la : lb), pr, l_wa, l_wb, l_s, sbase, p_own, c0 + c + D);
         }
         __builtin_amdgcn_sched_barrier(0);
 
@@ -767,12 +794,13 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
                     d[i][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xa[t], wb, zero, 1, 4, 0, 0, 0, 0);
             }
 #pragma unroll
-            for (int i = 0; i < PH; ++i) {
-                const uint32_t sw = sc[i][gl >> 1];
-                const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
+            for (int i = 0; i < PH; ++i)
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] = fmaf(-alpha, term_sum(d[i][t]), acc[t]);
-            }
+                for (int t = 0; t < NT; ++t) {
+                    const uint32_t sw = sc[MIXED ? t : 0][i][gl >> 1];
+                    const float alpha = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (sw >> 16) : (sw & 0xffffu)));
+                    acc[t] = fmaf(-alpha, term_sum(d[i][t]), acc[t]);
+                }
             // the sums are due here: nothing keeps matrix results for later
 #pragma unroll
             for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[t]));
@@ -805,6 +833,59 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
 #pragma unroll
     for (int t = 0; t < NT; ++t)
         if (row_ok && 4 * t + q < nb) pr.y[(size_t)(4 * t + q) * pr.m + row] = (_Float16)acc[t];
+}
+
+// P: the uniform precision, or with per-request precision (MIXED) the number of planes stored
+template <int P, int NB, int NS, int KH, bool MIXED = false>
+__global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    StreamActivations<NB, NS, KH> xs;
+    xs.load(pr);
+    if constexpr (!MIXED) {
+        const int p_own[1] = {P};
+        const unsigned char *const sbase[1] = {pr.scales[P]};
+        rowstream_body<P, NB, NS, KH, false>(pr, lds, xs, p_own, sbase);
+    } else {
+        // Section 3.3: requests at different precisions share the plane sweep.  A lane reports one request per tile of
+        // four, so it simply reads the scale set of that request's precision (zero from plane p_b on); the planes are
+        // fetched to the deepest precision present, which every wave of the launch finds the same.
+        constexpr int NT = NB > kMaxBatchTile ? 2 : 1;
+        const int nb = min(NB, pr.batch);
+        const int q = (threadIdx.x & 63) >> 4;
+        const unsigned char *const set1 = pr.scales[1], *const set2 = pr.scales[2], *const set3 = pr.scales[3], *const set4 = pr.scales[4];
+        auto pick = [&](int k) { return k == 1 ? set1 : k == 2 ? set2 : k == 3 ? set3 : set4; };
+        int p_hi = 0, p_own[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) p_own[t] = 0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int raw = pr.p_req[min(b, nb - 1)];                  // the same address in every lane: a scalar load
+            int pb = raw < 1 ? 1 : (raw > pr.p_max ? pr.p_max : raw);
+            if (!((pr.set_mask >> pb) & 1) || b >= nb) pb = 0;          // no such scale set: zeros; absent slot: nothing
+            p_hi = max(p_hi, pb);
+            if ((b & 3) == q) p_own[b >> 2] = pb;
+        }
+        const unsigned char *sbase[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) sbase[t] = pick(p_own[t] > 0 ? p_own[t] : p_hi);
+        switch (p_hi) {           // the same in every wave of the launch
+        case 1: if constexpr (P >= 1) rowstream_body<1, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
+        case 2: if constexpr (P >= 2) rowstream_body<2, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
+        case 3: if constexpr (P >= 3) rowstream_body<3, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
+        case 4: if constexpr (P >= 4) rowstream_body<4, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
+        default: {                // no request has a scale set: zeros
+            const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+            const uint32_t row = (blockIdx.x * (uint32_t)kStreamWaves + (wave & 3)) * 16 + (lane & 15);
+            if (wave < kStreamWaves && row < pr.m) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    if (4 * t + q < nb) pr.y[(size_t)(4 * t + q) * pr.m + row] = (_Float16)0.f;
+            }
+            break;
+        }
+        }
+    }
 }
 
 // LDS a workgroup may ask for (160 KiB on gfx950), asked of the runtime once
@@ -922,11 +1003,14 @@ StreamPlan make_stream_plan(const GemmArgs &a)
     // tall enough to give most compute units a workgroup of four row blocks (measured: from 10240 rows on with up to
     // four requests, 10240 x 4096 at p = 4 13.1 -> 9.6 us, while 8192 rows lose, 8.0 -> 9.5; from 8192 rows on with
     // five to eight, 8192 x 4096 13.5 -> 11.6 us); whole chunks; 4 to 8 of them
-    if (a.uniform_p < 1 || a.uniform_p > kMaxP || any_offsets || a.group != 128 || a.batch < 2 || a.batch > 2 * kMaxBatchTile ||
+    const bool mixed = a.uniform_p == 0;
+    if ((mixed ? a.p_req == nullptr || a.p_max < 1 || a.p_max > kMaxP : a.uniform_p < 1 || a.uniform_p > kMaxP) || any_offsets ||
+        a.group != 128 || a.batch < 2 || a.batch > 2 * kMaxBatchTile ||
         row_blocks < (a.batch > kMaxBatchTile ? 512 : 640) || a.n % kSliceCols != 0)
         return sp;
     sp.NS = (int)(a.n / kSliceCols);
     if (sp.NS < 4 || sp.NS > 8) return sp;
+    if (mixed && sp.NS != 4) return sp;        // per-request precision (four sweep depths per kernel): instantiated for 4096 columns
     sp.NB = a.batch <= 2 ? 2 : a.batch <= 4 ? 4 : 8;
     sp.KH = sp.NB == 8 ? 2 : 1;                // eight requests: two waves per SIMD hide each other's matrix instructions
     if (sp.KH == 2 && sp.NS % 2 != 0) return sp;
@@ -958,6 +1042,23 @@ hipError_t launch_stream_ns(const PlaneMfmaParams &pr, const StreamPlan &sp, dim
     }
 }
 
+template <int P, int NB, int KH>
+hipError_t launch_stream_mixed_one(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
+{
+    auto kernel = plane_rowstream_kernel<P, NB, 4, KH, true>;
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)sp.lds_bytes)) return e;
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * kStreamWaves * KH), sp.lds_bytes, stream, pr);
+    return hipGetLastError();
+}
+
+template <int P>
+hipError_t launch_stream_mixed(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
+{
+    if (sp.NB == 2) return launch_stream_mixed_one<P, 2, 1>(pr, sp, grid, stream);
+    if (sp.NB == 4) return launch_stream_mixed_one<P, 4, 1>(pr, sp, grid, stream);
+    return launch_stream_mixed_one<P, 8, 2>(pr, sp, grid, stream);
+}
+
 template <int P>
 hipError_t launch_stream_p(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
 {
@@ -970,6 +1071,14 @@ hipError_t launch_stream(const GemmArgs &a, const PlaneMfmaParams &pr, const Str
 {
     const int64_t row_blocks = (a.m + 15) / 16;
     dim3 grid((unsigned)((row_blocks + kStreamWaves - 1) / kStreamWaves));
+    if (a.uniform_p == 0) {
+        switch (a.p_max) {
+        case 1: return launch_stream_mixed<1>(pr, sp, grid, stream);
+        case 2: return launch_stream_mixed<2>(pr, sp, grid, stream);
+        case 3: return launch_stream_mixed<3>(pr, sp, grid, stream);
+        default: return launch_stream_mixed<4>(pr, sp, grid, stream);
+        }
+    }
     switch (a.uniform_p) {
     case 1: return launch_stream_p<1>(pr, sp, grid, stream);
     case 2: return launch_stream_p<2>(pr, sp, grid, stream);

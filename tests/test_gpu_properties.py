@@ -80,6 +80,72 @@ def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):
     assert streamed == (0 if m < 10225 else 12) + (12 if n == 4096 else 0), streamed
 
 
+@pytest.mark.parametrize("m", [12300, 8200])
+def test_row_streaming_form_per_request_precision(gpu, oracle, m):
+    """Per-request precision on the row-streaming form (4096 columns): a lane reports one request per tile of four and
+    reads that request's own scale set.  Sampled rows against the oracle; each request bit for bit what the uniform call
+    at its precision gives; precisions outside 1 .. p_max clamped; a precision without a scale set, or none with one,
+    gives zeros; planes beyond the deepest precision present may hold anything."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    n = 4096
+    layer = syn.make_layer(m, n, seed=(272, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    rng = np.random.default_rng([syn.BASE_SEED, 272, m])
+    rows = np.unique(np.concatenate([[0, 15, 16, 63, 64, m - 17, m - 16, m - 9, m - 1], rng.integers(0, m, size=120)]))
+    sub_planes = np.ascontiguousarray(layer.planes[:, rows, :])
+    sub_scales = {p: np.ascontiguousarray(sc[:, rows, :]) for p, sc in layer.scales.items()}
+    for batch in (2, 3, 4, 5, 8):
+        streams = batch > 4 or m >= 10240
+        x = syn.make_x(batch, n, seed=(272, batch))
+        xd = gpu.to_dev(x)
+        draws = [rng.integers(1, 5, size=batch).astype(np.int32), np.full(batch, 2, dtype=np.int32),
+                 np.array([4, 3, 2, 1, 1, 2, 3, 4][:batch], dtype=np.int32)]
+        for p_req in draws:
+            out = gpu.Guarded((batch, m))
+            bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req), xd, y=out.t)
+            used = bcq.last_kernel()
+            assert used == ("plane_mfma_rows" if streams else "plane_mfma"), (batch, used)
+            y = out.check(f"mixed m={m} batch={batch} p_req={p_req.tolist()}")
+            y_ref, a_ref = oracle.gemm_mixed(sub_planes, sub_scales, p_req, x)
+            err = np.abs(y.cpu().numpy().astype(np.float64)[:, rows] - y_ref)
+            assert np.all(err <= oracle.tolerance(y_ref, a_ref)), f"m={m} batch={batch} p_req={p_req.tolist()}"
+            if streams:
+                for p in sorted(set(p_req.tolist())):
+                    yu = bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd)
+                    assert bcq.last_kernel() == "plane_mfma_rows"
+                    sel = torch.from_numpy(p_req == p).to(y.device)
+                    assert torch.equal(y[sel], yu[sel]), f"request at p={p} differs from the uniform call (batch {batch})"
+        if not streams:
+            continue
+        # clamping, a missing set, no set at all, garbage in the planes nobody uses
+        wild = np.array([0, -3, 9, 2, 3, 77, 1, 4][:batch], dtype=np.int32)
+        clamped = np.clip(wild, 1, 4).astype(np.int32)
+        y_wild = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(wild), xd)
+        y_ok = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(clamped), xd)
+        assert torch.equal(y_wild, y_ok)
+        no3 = {p: sc for p, sc in dl.scales.items() if p != 3}
+        p3 = np.array([3, 2, 3, 4, 1, 3, 2, 3][:batch], dtype=np.int32)
+        y_no3 = bcq.bcq_gemm_mixed(dl.planes, no3, gpu.to_dev(p3), xd)
+        y_all = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p3), xd)
+        is3 = torch.from_numpy(p3 == 3).to(y_all.device)
+        assert torch.all(y_no3[is3] == 0) and torch.equal(y_no3[~is3], y_all[~is3])
+        only3 = {3: dl.scales[3]}
+        p12 = np.array([1, 2, 4, 2, 1, 4, 2, 1][:batch], dtype=np.int32)
+        out = gpu.Guarded((batch, m))
+        bcq.bcq_gemm_mixed(dl.planes, only3, gpu.to_dev(p12), xd, y=out.t)
+        assert bcq.last_kernel() == "plane_mfma_rows"
+        assert torch.all(out.check("no request has a scale set") == 0)
+        scrambled = layer.planes.copy()
+        scrambled[2:] = syn.make_planes(m, n, seed=(272, 99))[2:]
+        p2 = np.array([2, 1, 2, 2, 1, 2, 1, 2][:batch], dtype=np.int32)
+        ya = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p2), xd)
+        yb = bcq.bcq_gemm_mixed(gpu.to_dev(scrambled), dl.scales, gpu.to_dev(p2), xd)
+        assert torch.equal(ya, yb), "planes beyond the deepest precision present influenced the result"
+    torch.cuda.synchronize()
+
+
 def test_row_streaming_form_reads_every_binary16_activation_exactly(gpu):
     """The row-streaming form builds its operand image with code of its own: every finite binary16 value, alone in its
     scale group, against rows whose only non-zero scale (1.0, one plane) sits on that group, comes back bit for bit

@@ -135,11 +135,12 @@ int bcq_gemm_mixed_offset(const uint32_t *planes, const bcq_half *const *scales_
  * the same precision in one call (the q/k/v and the gate/up projections of a
  * decoder layer; section 4.4 measures whole decoding steps made of such layers).
  * Equivalent to `count` calls of bcq_gemv, but as a single kernel launch
- * where one kernel family serves the matrices taken together: bit for bit
- * the results of separate calls at small batches (up to 8 requests); at
- * larger batches the workgroup shape, and with it the order of the fp32
- * sums, is chosen for the sum of the rows, so results agree with separate
- * calls within the accuracy both are held to, not bit for bit.
+ * where one kernel family serves the matrices taken together.  The kernel
+ * form and workgroup shape, and with them the order of the fp32 sums, are
+ * chosen for the sum of the rows: results agree with separate calls within
+ * the accuracy both are held to, and bit for bit wherever the same form
+ * serves both (with one request always; with up to 8 unless the matrices
+ * are tall enough only together for the row-streaming form).
  *   count      1 .. BCQ_MAX_MULTI
  *   planes     HOST array of `count` device pointers, matrix k: [>= p][m[k]][n/32]
  *   scales_p   HOST array of `count` device pointers, matrix k: [p][m[k]][n/group]

@@ -148,7 +148,8 @@ def bcq_gemv(planes: torch.Tensor, scales_p: torch.Tensor, p: int, x: torch.Tens
 
 def bcq_gemv_multi(planes: list, scales_p: list, p: int, x: torch.Tensor, ys: list | None = None, group: int = 128) -> list:
     """Several matrices (same n and precision) applied to the same activations in one call: the q/k/v or
-    gate/up projections of a decoder layer.  Returns the list of outputs, bit for bit those of bcq_gemv."""
+    gate/up projections of a decoder layer.  Returns the list of outputs (those of bcq_gemv within the tolerance both are held
+    to; bit for bit wherever the same kernel form serves both)."""
     count = len(planes)
     batch, n = x.shape
     if len(scales_p) != count or (ys is not None and len(ys) != count):

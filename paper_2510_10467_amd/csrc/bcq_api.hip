@@ -288,10 +288,13 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
     }
     if (batch == 0) return BCQ_OK;
     // one launch when every matrix would run on the plane-wise kernel anyway
+    // (or when the row-streaming form takes all their rows together: two to eight requests, 640 row blocks in all)
+    const bool forced_elsewhere = g_forced != BCQ_KERNEL_AUTO && g_forced != BCQ_KERNEL_PLANE_MFMA;
+    const bool streams = count > 1 && !forced_elsewhere && bcq::plane_mfma_streams_multi(mats, count);
     bool together = count > 1 && bcq::plane_mfma_supports_multi(mats, count);
-    for (int k = 0; together && k < count; ++k) together = choose(mats[k]) == BCQ_KERNEL_PLANE_MFMA;
+    for (int k = 0; together && !streams && k < count; ++k) together = choose(mats[k]) == BCQ_KERNEL_PLANE_MFMA;
     if (together) {
-        g_last = "plane_mfma";
+        g_last = streams ? "plane_mfma_rows" : "plane_mfma";
         return bcq::plane_mfma_launch_multi(mats, count, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
     }
     // larger batches: one launch of the large-batch kernels when the matrices taken together (one matrix of all their

@@ -51,6 +51,7 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream);
 
 // `count` matrices that share n, precision, batch and activations as ONE launch
 bool plane_mfma_supports_multi(const GemmArgs *mats, int count);
+bool plane_mfma_streams_multi(const GemmArgs *mats, int count);   // ... and the row-streaming form takes them together
 hipError_t plane_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t stream);
 
 bool dequant_mfma_supports(const GemmArgs &a);

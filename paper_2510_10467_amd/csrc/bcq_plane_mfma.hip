@@ -628,7 +628,7 @@ struct StreamActivations {
 // PH: planes fetched (the precision, or with per-request precision the deepest one present); p_own[t]: the precision of
 // the request this lane reports on in tile t (PH when uniform, 0: none), sbase[t] its scale set
 template <int PH, int NB, int NS, int KH, bool MIXED>
-__device__ __forceinline__ void rowstream_body(const PlaneMfmaParams &pr, unsigned char *lds, const StreamActivations<NB, NS, KH> &xs,
+__device__ __forceinline__ void rowstream_body(const PlaneMfmaParams &pr, uint32_t wg, unsigned char *lds, const StreamActivations<NB, NS, KH> &xs,
                                                const int *p_own, const unsigned char *const *sbase)
 {
     using L = Lds<NB>;
@@ -647,7 +647,7 @@ __device__ __forceinline__ void rowstream_body(const PlaneMfmaParams &pr, unsign
     const int rb = wave & (W - 1), kh = wave >> 2;                   // row block of the workgroup, part of the K range
     static_assert(W == 4, "wave -> (row block, K part)");
     const int c0 = kh * NC;                                          // first chunk of this wave
-    const uint32_t block_row0 = (blockIdx.x * (uint32_t)W + rb) * 16;
+    const uint32_t block_row0 = (wg * (uint32_t)W + rb) * 16;        // wg: this workgroup's index inside its matrix
     const uint32_t last_row = pr.m - 1;
 
     // plane loads: lane (l >> 3, l & 7) takes group l & 7 (16 bytes) of block rows l >> 3 and 8 + (l >> 3); rows past
@@ -837,15 +837,31 @@ __device__ __forceinline__ void rowstream_body(const PlaneMfmaParams &pr, unsign
 
 // P: the uniform precision, or with per-request precision (MIXED) the number of planes stored
 template <int P, int NB, int NS, int KH, bool MIXED = false>
-__global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr)
+__global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr_in)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     StreamActivations<NB, NS, KH> xs;
-    xs.load(pr);
+    xs.load(pr_in);
+    // Several matrices with the same n, precision and activations in one launch: the grid is the concatenation of
+    // their workgroups, matrix k owning the ids mat_blk0[k] .. mat_blk0[k + 1] - 1 (a single matrix: all of them); which
+    // one this workgroup belongs to is picked by comparison, without a branch.
+    PlaneMfmaParams pr = pr_in;
+    uint32_t wg = blockIdx.x;
+    if constexpr (!MIXED) {
+        static_assert(BCQ_MAX_MULTI == 4, "the selection below is written for four matrices");
+        const bool g1 = wg >= pr_in.mat_blk0[1], g2 = wg >= pr_in.mat_blk0[2], g3 = wg >= pr_in.mat_blk0[3];
+        pr.planes = g3 ? pr_in.mat_planes[3] : g2 ? pr_in.mat_planes[2] : g1 ? pr_in.mat_planes[1] : pr_in.mat_planes[0];
+        pr.scales[P] = g3 ? pr_in.mat_scales[3] : g2 ? pr_in.mat_scales[2] : g1 ? pr_in.mat_scales[1] : pr_in.mat_scales[0];
+        pr.y = g3 ? pr_in.mat_y[3] : g2 ? pr_in.mat_y[2] : g1 ? pr_in.mat_y[1] : pr_in.mat_y[0];
+        pr.m = g3 ? pr_in.mat_m[3] : g2 ? pr_in.mat_m[2] : g1 ? pr_in.mat_m[1] : pr_in.mat_m[0];
+        wg -= g3 ? pr_in.mat_blk0[3] : g2 ? pr_in.mat_blk0[2] : g1 ? pr_in.mat_blk0[1] : 0u;
+        pr.plane_stride = pr.m * pr.row_stride;
+        pr.scale_plane_stride = pr.m * pr.scale_row_stride;
+    }
     if constexpr (!MIXED) {
         const int p_own[1] = {P};
         const unsigned char *const sbase[1] = {pr.scales[P]};
-        rowstream_body<P, NB, NS, KH, false>(pr, lds, xs, p_own, sbase);
+        rowstream_body<P, NB, NS, KH, false>(pr, wg, lds, xs, p_own, sbase);
     } else {
         // Section 3.3: requests at different precisions share the plane sweep.  A lane reports one request per tile of
         // four, so it simply reads the scale set of that request's precision (zero from plane p_b on); the planes are
@@ -870,10 +886,10 @@ __global__ __launch_bounds__(512) void plane_rowstream_kernel(PlaneMfmaParams pr
 #pragma unroll
         for (int t = 0; t < NT; ++t) sbase[t] = pick(p_own[t] > 0 ? p_own[t] : p_hi);
         switch (p_hi) {           // the same in every wave of the launch
-        case 1: if constexpr (P >= 1) rowstream_body<1, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
-        case 2: if constexpr (P >= 2) rowstream_body<2, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
-        case 3: if constexpr (P >= 3) rowstream_body<3, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
-        case 4: if constexpr (P >= 4) rowstream_body<4, NB, NS, KH, true>(pr, lds, xs, p_own, sbase); break;
+        case 1: if constexpr (P >= 1) rowstream_body<1, NB, NS, KH, true>(pr, wg, lds, xs, p_own, sbase); break;
+        case 2: if constexpr (P >= 2) rowstream_body<2, NB, NS, KH, true>(pr, wg, lds, xs, p_own, sbase); break;
+        case 3: if constexpr (P >= 3) rowstream_body<3, NB, NS, KH, true>(pr, wg, lds, xs, p_own, sbase); break;
+        case 4: if constexpr (P >= 4) rowstream_body<4, NB, NS, KH, true>(pr, wg, lds, xs, p_own, sbase); break;
         default: {                // no request has a scale set: zeros
             const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
             const uint32_t row = (blockIdx.x * (uint32_t)kStreamWaves + (wave & 3)) * 16 + (lane & 15);
@@ -1067,10 +1083,21 @@ hipError_t launch_stream_p(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3
     return launch_stream_one<P, 8, 4, 2>(pr, sp, grid, stream);
 }
 
-hipError_t launch_stream(const GemmArgs &a, const PlaneMfmaParams &pr, const StreamPlan &sp, hipStream_t stream)
+// `mats`: the matrices of the launch (one, or several with the same n, precision, batch and activations)
+hipError_t launch_stream(const GemmArgs *mats, int count, PlaneMfmaParams pr, const StreamPlan &sp, hipStream_t stream)
 {
-    const int64_t row_blocks = (a.m + 15) / 16;
-    dim3 grid((unsigned)((row_blocks + kStreamWaves - 1) / kStreamWaves));
+    const GemmArgs &a = mats[0];
+    uint32_t wgs = 0;
+    for (int k = 0; k < BCQ_MAX_MULTI; ++k) {
+        pr.mat_blk0[k] = wgs;                 // unused entries: the total, which no workgroup reaches
+        if (k >= count) continue;
+        pr.mat_planes[k] = reinterpret_cast<const unsigned char *>(mats[k].planes);
+        pr.mat_scales[k] = reinterpret_cast<const unsigned char *>(a.uniform_p > 0 ? mats[k].scales[a.uniform_p] : nullptr);
+        pr.mat_y[k] = mats[k].y;
+        pr.mat_m[k] = (uint32_t)mats[k].m;
+        wgs += (uint32_t)(((mats[k].m + 15) / 16 + kStreamWaves - 1) / kStreamWaves);
+    }
+    dim3 grid(wgs);
     if (a.uniform_p == 0) {
         switch (a.p_max) {
         case 1: return launch_stream_mixed<1>(pr, sp, grid, stream);
@@ -1090,6 +1117,20 @@ hipError_t launch_stream(const GemmArgs &a, const PlaneMfmaParams &pr, const Str
 }  // namespace
 
 bool plane_mfma_streams(const GemmArgs &a) { return plane_mfma_supports(a) && make_stream_plan(a).ok; }
+
+// Several matrices in one launch: the row-streaming form takes them when it would take one matrix of all their rows
+static StreamPlan make_stream_plan_multi(const GemmArgs *mats, int count)
+{
+    GemmArgs all = mats[0];
+    all.m = 0;
+    for (int k = 0; k < count; ++k) all.m += mats[k].m;
+    return make_stream_plan(all);
+}
+
+bool plane_mfma_streams_multi(const GemmArgs *mats, int count)
+{
+    return plane_mfma_supports_multi(mats, count) && make_stream_plan_multi(mats, count).ok;
+}
 
 bool plane_mfma_supports(const GemmArgs &a)
 {
@@ -1145,7 +1186,7 @@ hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream)
     pr.inv_span = 1.0f / (float)(8 * pr.ntiles);
     pr.inv_ks = 1.0f / (float)pl.KS;
     dim3 block(64 * pl.KS * pl.RB);
-    if (const StreamPlan sp = make_stream_plan(a); sp.ok) return launch_stream(a, pr, sp, stream);
+    if (const StreamPlan sp = make_stream_plan(a); sp.ok) return launch_stream(&a, 1, pr, sp, stream);
     if (with_offsets) {
         switch (pl.NB) {
         case 1: return launch_nb<1, true>(a, pr, pl, grid, block, stream);
@@ -1189,6 +1230,7 @@ hipError_t plane_mfma_launch_multi(const GemmArgs *mats, int count, hipStream_t 
     pr.batch = a.batch;
     pr.p_max = a.p_max;
     pr.uniform_p = a.uniform_p;
+    if (const StreamPlan sp = make_stream_plan_multi(mats, count); sp.ok) return launch_stream(mats, count, pr, sp, stream);
     pr.KS = pl.KS;
     pr.RB = 1;
     pr.nchunk = pl.nchunk;

@@ -146,6 +146,36 @@ def test_row_streaming_form_per_request_precision(gpu, oracle, m):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("ms,n", [((6400, 6400), 4096), ((12300, 1000, 20), 4096), ((14336, 14336), 4096), ((5000, 3000, 2000, 300), 8192)])
+def test_row_streaming_form_several_matrices(gpu, oracle, ms, n):
+    """bcq_gemv_multi on the row-streaming form: the matrices are taken together when all their rows make a matrix tall
+    enough (each of them may be too short on its own); a matrix's last workgroup may hold absent row blocks.  Sampled
+    rows against the oracle, and bit for bit the separate calls wherever those run the same form."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    layers = [syn.make_layer(m, n, seed=(273, k, m), signed=True) for k, m in enumerate(ms)]
+    dls = [gpu.DeviceLayer(L) for L in layers]
+    rng = np.random.default_rng([syn.BASE_SEED, 273, len(ms)])
+    for batch in (2, 4, 7):
+        x = syn.make_x(batch, n, seed=(273, batch))
+        xd = gpu.to_dev(x)
+        for p in (2, 4):
+            if batch > 4 and n != 4096:
+                continue                    # (five to eight requests stream at 4096 columns only)
+            outs = [gpu.Guarded((batch, m)) for m in ms]
+            bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[p] for d in dls], p, xd, ys=[o.t for o in outs])
+            assert bcq.last_kernel() == "plane_mfma_rows", (ms, batch, p, bcq.last_kernel())
+            for k, (L, d, o) in enumerate(zip(layers, dls, outs)):
+                y = o.check(f"multi matrix {k} of {ms} batch={batch} p={p}")
+                m = L.m
+                rows = np.unique(np.concatenate([[0, min(15, m - 1), m - 1, max(m - 17, 0)], rng.integers(0, m, size=40)]))
+                sampled_rows_check(gpu, oracle, L, d, p, x, rows, y, f"multi matrix {k} of {ms} batch={batch} p={p}")
+                alone = bcq.bcq_gemv(d.planes, d.scales[p], p, xd)
+                if bcq.last_kernel() == "plane_mfma_rows":
+                    assert torch.equal(alone, y), f"matrix {k} of {ms}: differs from the separate call on the same form"
+
+
 def test_row_streaming_form_reads_every_binary16_activation_exactly(gpu):
     """The row-streaming form builds its operand image with code of its own: every finite binary16 value, alone in its
     scale group, against rows whose only non-zero scale (1.0, one plane) sits on that group, comes back bit for bit

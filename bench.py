@@ -624,7 +624,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "Llama-3-8B-shaped linear set (q,k,v,o,gate,up,down), batch 1, group 128, p in {2,3,4}; "
                                "one step = 21 bcq_gemv calls", "kernel": kernel_name,
-                   "arithmetic": "fp16 in/out; exact E5M2 activation terms x FP4 weight signs on the MFMA pipe, fp32 accumulate",
+                   "arithmetic": "fp16 in/out; four E5M2 terms per activation (exact over all of binary16) x FP4 weight signs on the MFMA pipe, fp32 accumulate",
                    "weight_copies_rotated": copies, "rotation_bytes": copies * set_bytes,
                    "launch": "python loop" if args.no_graph else "hip graph replay per step"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),

@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a reference kernel of known traffic for counter runs)")
-    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused", "offset", "quant", "step"], default=None,
+    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused", "offset", "quant", "step", "issue"], default=None,
                     help="instead of the headline workload, time another workload family and print its table")
     return ap.parse_args()
 
@@ -242,6 +242,27 @@ def run_suite(args, torch, bcq, syn, dev):
                              "ms_per_token": round(ms / batch, 4), "GBps": round(by / ms / 1e6, 1),
                              "pct_of_hbm_peak": round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 2),
                              "tokens_per_s_upper_bound": round(batch * 1e3 / ms, 1)})
+    elif args.suite == "issue":
+        # What one SIMD issues when matrix and vector instructions alternate (include/bcq_bench.h): shader-clock ticks per
+        # matrix instruction for one wave per SIMD (4 waves) and for two (8).  A matrix instruction keeps its SIMD from
+        # issuing anything else for about 20 ticks whatever its size, a vector instruction for 4: the product kernels'
+        # time after their data have arrived is the sum of these over their instructions, not the larger of the pipes.
+        ticks = torch.zeros(32, dtype=torch.int64, device=dev)
+        sink = torch.zeros(1024, dtype=torch.float32, device=dev)
+        iters = 4000
+        names = {0: "v_mfma_f32_16x16x32_f16", 1: "v_mfma_f32_32x32x16_f16", 2: "v_mfma_f32_16x16x128_f8f6f4 (E5M2 x FP4)"}
+        for kind in (0, 1, 2):
+            for valu in (0, 4, 8, 16):
+                for waves in (4, 8):
+                    bcq.bench_issue_probe(kind, valu, waves, iters, ticks, sink)      # warm-up (instruction cache)
+                    bcq.bench_issue_probe(kind, valu, waves, iters, ticks, sink)
+                    torch.cuda.synchronize()
+                    t = ticks.cpu().numpy().reshape(16, 2)[:waves]
+                    per_simd = waves // 4                                             # waves that share a SIMD
+                    rows.append({"instruction": names[kind], "vector_fmas_per_matrix_instruction": valu, "waves_per_simd": per_simd,
+                                 "ticks_per_matrix_instruction_per_simd": round(float(t[:, 0].max()) / (4 * iters) / per_simd, 1),
+                                 "shader_clock_MHz": round(float(t[:, 0].max()) / float(t[:, 1].max()) * 100.0, 0)})
+        return {"suite": args.suite, "unit": "shader-clock ticks", "data": "none", "rows": rows}
     elif args.suite == "quant":
         # The offline quantiser (Algorithm 1, p_L = 2, p_H = 4, T = 20, g = 128) on Llama-3-8B layer shapes.
         # Bound by double-precision vector arithmetic: per weight and cycle the base stage adds p signed terms

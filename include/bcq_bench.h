@@ -72,6 +72,15 @@ int bcq_bench_stream_read(const void *src, int64_t bytes, uint32_t *sink, void *
  */
 int bcq_bench_fp16_gemv(const uint16_t *w, const uint16_t *x, uint16_t *y, int64_t m, int64_t n, void *stream);
 
+/*
+ * Instruction-issue probe: ONE workgroup of `waves` wavefronts (1 .. 16; beyond four they share SIMDs) runs `iters`
+ * times four matrix instructions, each followed by `valu` (0, 4, 8 or 16) independent fp32 vector FMAs.  kind 0:
+ * v_mfma_f32_16x16x32_f16, 1: v_mfma_f32_32x32x16_f16, 2: v_mfma_f32_16x16x128_f8f6f4 (E5M2 x FP4 operands).
+ * ticks[2w] receives the shader-clock ticks and ticks[2w + 1] the 100 MHz ticks that wave w's loop took (ticks: room
+ * for 32 values); sink: room for 1024 floats, written with values that mean nothing.  Returns -3 for other arguments.
+ */
+int bcq_bench_issue_probe(int kind, int valu, int waves, int iters, uint64_t *ticks, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.bcq_bench_stream_read.restype = i32
         L.bcq_bench_fp16_gemv.argtypes = [vp, vp, vp, i64, i64, vp]
         L.bcq_bench_fp16_gemv.restype = i32
+        L.bcq_bench_issue_probe.argtypes = [i32, i32, i32, i32, vp, vp, vp]
+        L.bcq_bench_issue_probe.restype = i32
         for f in (L.bcq_select_kernel, L.bcq_pack, L.bcq_unpack, L.bcq_gemv, L.bcq_gemm_mixed, L.bcq_gemv_offset,
                   L.bcq_gemm_mixed_offset):
             f.restype = i32
@@ -263,3 +265,13 @@ def bench_fp16_gemv(w: torch.Tensor, x: torch.Tensor, y: torch.Tensor) -> torch.
     _check(lib().bcq_bench_fp16_gemv(_dev(w, torch.float16, "w"), _dev(x, torch.float16, "x"), _dev(y, torch.float16, "y"), m, n,
                                      _stream()), "bcq_bench_fp16_gemv")
     return y
+
+
+def bench_issue_probe(kind: int, valu: int, waves: int, iters: int, ticks: torch.Tensor, sink: torch.Tensor) -> torch.Tensor:
+    """Benchmark reference: one workgroup of ``waves`` wavefronts alternates matrix instructions of ``kind`` with ``valu``
+    vector FMAs; ``ticks`` (int64[32]) receives per wavefront the shader-clock and the 100 MHz ticks of its loop."""
+    if ticks.numel() < 32 or sink.numel() < 1024:
+        raise ValueError("bench_issue_probe: ticks needs 32 values, sink 1024")
+    _check(lib().bcq_bench_issue_probe(int(kind), int(valu), int(waves), int(iters), _dev(ticks, torch.int64, "ticks"),
+                                       _dev(sink, torch.float32, "sink"), _stream()), "bcq_bench_issue_probe")
+    return ticks

@@ -1,6 +1,8 @@
 // Reference points for the benchmark, not part of the method: what the same GPU reaches on a pure
 // streaming read of as many bytes as a product call moves, and on a plain binary16 matrix-vector product
-// that does not depend on a library's choice of kernel.  Both are ordinary bandwidth-bound kernels.
+// that does not depend on a library's choice of kernel (both ordinary bandwidth-bound kernels); and what one
+// SIMD issues per clock when matrix and vector instructions alternate, which is what bounds the product kernels
+// once their data are there.
 #include <hip/hip_runtime.h>
 
 #include "bcq_bench.h"
@@ -50,9 +52,97 @@ __global__ __launch_bounds__(256) void fp16_gemv_kernel(const _Float16 *w, const
     if (lane == 0) y[row] = (_Float16)acc;
 }
 
+// What a SIMD can issue: `valu` independent vector FMAs behind every matrix instruction, a fixed number of times, in
+// every wave of ONE workgroup (waves beyond four share SIMDs).  Lane 0 of each wave reports the shader-clock ticks and
+// the 100 MHz ticks its loop took.  KIND 0: v_mfma_f32_16x16x32_f16, 1: v_mfma_f32_32x32x16_f16, 2:
+// v_mfma_f32_16x16x128_f8f6f4 with an E5M2 and an FP4 operand.
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+template <int KIND, int NV>
+__global__ __launch_bounds__(1024) void issue_probe_kernel(uint64_t *ticks, float *sink, int iters)
+{
+    half8v a, b;
+    i32x8 a8, b8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        a[j] = (_Float16)(0.001f * (float)threadIdx.x + (float)j);
+        b[j] = (_Float16)(0.5f * (float)j);
+        a8[j] = (int)threadIdx.x * 77 + j;
+        b8[j] = 0x22222222;
+    }
+    f32x16 c[4];
+    f32x4 d[4];
+    float f[8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) c[u][j] = 0.f;
+        d[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) f[j] = (float)threadIdx.x + (float)j;
+    const float k1 = 1.0001f, k2 = 0.5f;
+    __syncthreads();
+    const uint64_t t0 = __builtin_readcyclecounter(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if constexpr (KIND == 0) d[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, d[u], 0, 0, 0);
+            if constexpr (KIND == 1) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c[u], 0, 0, 0);
+            if constexpr (KIND == 2) d[u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, d[u], 1, 4, 0, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) f[v & 7] = __builtin_fmaf(f[v & 7], k1, k2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    const uint64_t t1 = __builtin_readcyclecounter(), r1 = wall_clock64();
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += f[j];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += c[u][j];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s += d[u][j];
+    }
+    sink[threadIdx.x] = s;
+    if ((threadIdx.x & 63) == 0) {
+        ticks[2 * (threadIdx.x >> 6)] = t1 - t0;
+        ticks[2 * (threadIdx.x >> 6) + 1] = r1 - r0;
+    }
+}
+
+template <int KIND>
+bool launch_issue_probe(int valu, int waves, int iters, uint64_t *ticks, float *sink, hipStream_t stream)
+{
+    switch (valu) {
+    case 0: hipLaunchKernelGGL((issue_probe_kernel<KIND, 0>), dim3(1), dim3(64 * waves), 0, stream, ticks, sink, iters); return true;
+    case 4: hipLaunchKernelGGL((issue_probe_kernel<KIND, 4>), dim3(1), dim3(64 * waves), 0, stream, ticks, sink, iters); return true;
+    case 8: hipLaunchKernelGGL((issue_probe_kernel<KIND, 8>), dim3(1), dim3(64 * waves), 0, stream, ticks, sink, iters); return true;
+    case 16: hipLaunchKernelGGL((issue_probe_kernel<KIND, 16>), dim3(1), dim3(64 * waves), 0, stream, ticks, sink, iters); return true;
+    default: return false;
+    }
+}
+
 }  // namespace
 
 extern "C" {
+
+int bcq_bench_issue_probe(int kind, int valu, int waves, int iters, uint64_t *ticks, float *sink, void *stream)
+{
+    if (!ticks || !sink) return -1;
+    if (waves < 1 || waves > 16 || iters < 1 || iters > (1 << 20)) return -3;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool known = kind == 0 ? launch_issue_probe<0>(valu, waves, iters, ticks, sink, st)
+                     : kind == 1 ? launch_issue_probe<1>(valu, waves, iters, ticks, sink, st)
+                     : kind == 2 ? launch_issue_probe<2>(valu, waves, iters, ticks, sink, st) : false;
+    if (!known) return -3;
+    return hipGetLastError() == hipSuccess ? 0 : -5;
+}
 
 int bcq_bench_stream_read(const void *src, int64_t bytes, uint32_t *sink, void *stream)
 {

@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"bcq_pack", "bcq_unpack", "bcq_gemv", "bcq_gemm_mixed", "bcq_gemv_offset", "bcq_gemm_mixed_offset", "bcq_gemv_multi",
-            "bcq_quantize", "bcq_bench_stream_read", "bcq_bench_fp16_gemv", "bcq_strerror", "bcq_select_kernel", "bcq_select_dequant_shape", "bcq_last_kernel"} <= set(names)
+            "bcq_quantize", "bcq_bench_stream_read", "bcq_bench_fp16_gemv", "bcq_bench_issue_probe", "bcq_strerror", "bcq_select_kernel", "bcq_select_dequant_shape", "bcq_last_kernel"} <= set(names)
     for name in names:
         assert hasattr(lib, name), f"{name} declared in include/ but not exported"
 
@@ -125,6 +125,10 @@ def test_argument_validation_without_device(lib):
     assert lib.bcq_bench_fp16_gemv(0x1000, 0x2000, None, 4, 64, None) == -1
     assert lib.bcq_bench_fp16_gemv(0x1000, 0x2000, 0x3000, 4, 60, None) == -3
     assert lib.bcq_bench_fp16_gemv(0x1002, 0x2000, 0x3000, 4, 64, None) == -4
+    assert lib.bcq_bench_issue_probe(0, 8, 4, 100, None, 0x2000, None) == -1
+    assert lib.bcq_bench_issue_probe(0, 8, 17, 100, 0x1000, 0x2000, None) == -3
+    assert lib.bcq_bench_issue_probe(3, 8, 4, 100, 0x1000, 0x2000, None) == -3
+    assert lib.bcq_bench_issue_probe(0, 5, 4, 100, 0x1000, 0x2000, None) == -3
     assert lib.bcq_pack(0x1000, 0x2000, 4, 8, 48, None) == -3
     assert lib.bcq_pack(0x1000, 0x2000, 0, 8, 64, None) == -2
     assert lib.bcq_unpack(None, 0x2000, 4, 8, 64, None) == -1

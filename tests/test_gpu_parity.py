@@ -574,6 +574,17 @@ def test_benchmark_reference_kernels(gpu):
     bcq.bench_stream_read(buf, sink)
     torch.cuda.synchronize()
     assert int(sink.abs().sum()) == 0
+    # the instruction-issue probe reports a positive tick count for every wave it ran, and more ticks with more vector work
+    ticks = torch.zeros(32, dtype=torch.int64, device=gpu.DEV)
+    scratch = torch.zeros(1024, dtype=torch.float32, device=gpu.DEV)
+    per_kind = []
+    for valu in (0, 16):
+        bcq.bench_issue_probe(2, valu, 4, 500, ticks, scratch)
+        torch.cuda.synchronize()
+        t = ticks.cpu().numpy().reshape(16, 2)
+        assert np.all(t[:4] > 0)
+        per_kind.append(int(t[:4, 0].max()))
+    assert per_kind[1] > per_kind[0]
 
 
 @pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])

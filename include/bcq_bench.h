@@ -56,7 +56,7 @@ int bcq_select_dequant_shape(int request_tiles, int row_blocks);
 
 /* Name of the variant the calling thread's most recent successful launch used ("" before any): "sign_select",
  * "plane_mfma" ("plane_mfma_rows" where that family ran in its row-streaming form: tall matrices with two to eight
- * requests), "dequant_mfma", "plane_f16", "quantize". */
+ * requests, or with one request at one or two planes), "dequant_mfma", "plane_f16", "quantize". */
 const char *bcq_last_kernel(void);
 
 /*

@@ -74,8 +74,8 @@ int choose(const bcq::GemmArgs &a)
             pays = a.batch * a.m >= 70000;
             tiles16 = a.batch <= 256;
         }
-        // Tall matrices with up to eight requests: the row-streaming form of the FP4 kernel beats both (14336 x 4096,
-        // eight requests: 13.7 us at p = 4 and 9.0 us at p = 2 against 19.4 and 11.9 us).
+        // Tall matrices with up to eight requests (one request: at one or two planes): the row-streaming form of the
+        // FP4 kernel beats both (14336 x 4096, eight requests: 13.7 us at p = 4 and 9.0 us at p = 2 against 19.4 and 11.9 us).
         if (plane_mfma_streams(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         else if (dequant_mfma_supports(a) && pays) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
@@ -288,7 +288,8 @@ int bcq_gemv_multi(int count, const uint32_t *const *planes, const bcq_half *con
     }
     if (batch == 0) return BCQ_OK;
     // one launch when every matrix would run on the plane-wise kernel anyway
-    // (or when the row-streaming form takes all their rows together: two to eight requests, 640 row blocks in all)
+    // (or when the row-streaming form takes all their rows together: two to eight requests, or one request at one or
+    // two planes, 640 row blocks in all)
     const bool forced_elsewhere = g_forced != BCQ_KERNEL_AUTO && g_forced != BCQ_KERNEL_PLANE_MFMA;
     const bool streams = count > 1 && !forced_elsewhere && bcq::plane_mfma_streams_multi(mats, count);
     bool together = count > 1 && bcq::plane_mfma_supports_multi(mats, count);

@@ -559,7 +559,7 @@ __global__ __launch_bounds__(64 * max_waves(NB, MIXED, GS)) void plane_mfma_kern
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Row-streaming form for tall matrices and two to eight requests.  A workgroup owns four blocks of 16 rows and
+// Row-streaming form for tall matrices and two to eight requests (and for one request at one or two planes).  A workgroup owns four blocks of 16 rows and
 // builds ONE operand image of the whole activation vectors; after that its waves run free: a wave takes a row block
 // and all of its columns (KH = 1) or half of them (KH = 2, the halves meet in LDS at the end) in chunks of 1024,
 // with the loads of the chunk after next already under way while it works, so that what arrives is consumed while
@@ -1003,7 +1003,8 @@ hipError_t launch_multi_nb(int p, const PlaneMfmaParams &pr, const Plan &pl, dim
 // Row streaming: which problems take it, and its launch.  Measured against the kernel above on 14336 x 4096,
 // 17920 x 5120 and 28672 x 8192 at p = 1 .. 4 and two to eight requests: never slower, up to 45 % faster (14336 x 4096,
 // p = 4: two requests 10.9 -> 9.5 us, four 12.1 -> 9.7, eight 19.4 -> 12.2; 28672 x 8192, four requests, p = 2: 33 -> 21).
-// With one request it is no faster (one or two waves per SIMD then do all of a row block's arithmetic in turn).
+// With one request it wins at one or two planes only (see make_stream_plan): one or two waves per SIMD then do all of
+// a row block's arithmetic in turn, and from three planes on the waits for the next chunk outweigh the shared conversion.
 struct StreamPlan {
     bool ok;
     int NB, NS, KH;
@@ -1021,16 +1022,28 @@ StreamPlan make_stream_plan(const GemmArgs &a)
     // five to eight, 8192 x 4096 13.5 -> 11.6 us); whole chunks; 4 to 8 of them
     const bool mixed = a.uniform_p == 0;
     if ((mixed ? a.p_req == nullptr || a.p_max < 1 || a.p_max > kMaxP : a.uniform_p < 1 || a.uniform_p > kMaxP) || any_offsets ||
-        a.group != 128 || a.batch < 2 || a.batch > 2 * kMaxBatchTile ||
+        a.group != 128 || a.batch < 1 || a.batch > 2 * kMaxBatchTile ||
         row_blocks < (a.batch > kMaxBatchTile ? 512 : 640) || a.n % kSliceCols != 0)
         return sp;
+    // One request: only at one or two planes, where the conversion of the activations, which this form does once per
+    // four row blocks, is a large part of a wave's work, and only where its one or two waves per row block spread
+    // evenly over the SIMDs: from 896 row blocks on with rows of four or eight chunks (28672 x 8192: p = 1 12.0 -> 8.6 us,
+    // p = 2 16.2 -> 14.9; 14336 x 4096: 4.7 -> 4.1 and 6.2 -> 6.0; gate and up projection in one launch at p = 2:
+    // 9.5 -> 9.1).  Shorter matrices and other widths win or lose a few per cent at one plane and lose up to 17 % at
+    // two (10240 x 8192: 8.1 -> 9.5 us), and from three planes on the kernel that asks for all of a wave's data up
+    // front is ahead everywhere (28672 x 8192, p = 4: 25.6 against 27.8 us).
+    if (a.batch == 1 && (mixed || a.uniform_p > 2 || row_blocks < 896 || (a.n != 4 * kSliceCols && a.n != 8 * kSliceCols))) return sp;
     sp.NS = (int)(a.n / kSliceCols);
     if (sp.NS < 4 || sp.NS > 8) return sp;
     if (mixed && sp.NS != 4) return sp;        // per-request precision (four sweep depths per kernel): instantiated for 4096 columns
-    sp.NB = a.batch <= 2 ? 2 : a.batch <= 4 ? 4 : 8;
+    sp.NB = a.batch == 1 ? 1 : a.batch <= 2 ? 2 : a.batch <= 4 ? 4 : 8;
     sp.KH = sp.NB == 8 ? 2 : 1;                // eight requests: two waves per SIMD hide each other's matrix instructions
+    // one request: two waves per row block wherever one wave per row block leaves a SIMD less than two waves
+    // (rows of four chunks at either depth, rows of eight at one plane)
+    if (sp.NB == 1 && (sp.NS == 4 || a.uniform_p == 1)) sp.KH = 2;
     if (sp.KH == 2 && sp.NS % 2 != 0) return sp;
-    const size_t image = (size_t)sp.NS * (sp.NB == 2 ? Lds<2>::kSliceImage : sp.NB == 4 ? Lds<4>::kSliceImage : Lds<8>::kSliceImage);
+    const size_t image = (size_t)sp.NS * (sp.NB == 1 ? Lds<1>::kSliceImage : sp.NB == 2 ? Lds<2>::kSliceImage
+                                          : sp.NB == 4 ? Lds<4>::kSliceImage : Lds<8>::kSliceImage);
     const int waves = kStreamWaves * sp.KH;
     sp.lds_bytes = image + (size_t)waves * Lds<1>::kWaveTile + (sp.KH > 1 ? (size_t)waves * 2 * 64 * sizeof(float) : 0);
     sp.ok = sp.lds_bytes <= lds_budget() && (sp.NB < 8 || sp.NS == 4);      // (eight requests: instantiated for four chunks)
@@ -1075,9 +1088,22 @@ hipError_t launch_stream_mixed(const PlaneMfmaParams &pr, const StreamPlan &sp, 
     return launch_stream_mixed_one<P, 8, 2>(pr, sp, grid, stream);
 }
 
+// one request (one or two planes, rows of four or eight chunks): one or two waves per row block
+template <int P>
+hipError_t launch_stream_single(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
+{
+    if constexpr (P <= 2) {
+        if (sp.NS == 4 && sp.KH == 2) return launch_stream_one<P, 1, 4, 2>(pr, sp, grid, stream);
+        if (sp.NS == 8 && sp.KH == 2) return launch_stream_one<P, 1, 8, 2>(pr, sp, grid, stream);
+        if (sp.NS == 8 && sp.KH == 1) return launch_stream_one<P, 1, 8, 1>(pr, sp, grid, stream);
+    }
+    return hipErrorInvalidValue;                  // make_stream_plan plans nothing else
+}
+
 template <int P>
 hipError_t launch_stream_p(const PlaneMfmaParams &pr, const StreamPlan &sp, dim3 grid, hipStream_t stream)
 {
+    if (sp.NB == 1) return launch_stream_single<P>(pr, sp, grid, stream);
     if (sp.NB == 2) return launch_stream_ns<P, 2>(pr, sp, grid, stream);
     if (sp.NB == 4) return launch_stream_ns<P, 4>(pr, sp, grid, stream);
     return launch_stream_one<P, 8, 4, 2>(pr, sp, grid, stream);

@@ -51,19 +51,20 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
             sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"{name} p={p} batch={batch} ({bcq.last_kernel()})")
 
 
-@pytest.mark.parametrize("m,n", [(12300, 4096), (12290, 5120), (12400, 6144), (12500, 7168), (12304, 8192), (10236, 4096), (8200, 4096)])
+@pytest.mark.parametrize("m,n", [(12300, 4096), (12290, 5120), (12400, 6144), (12500, 7168), (12304, 8192), (10236, 4096), (8200, 4096),
+                                 (14330, 4096), (14350, 8192), (14336, 5120)])
 def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):
-    """Tall matrices with two to eight requests run the FP4 family in its row-streaming form (one operand image per
-    four row blocks, chunks of 1024 columns prefetched two ahead): 4 to 8 chunks per row, one and two request tiles,
-    a last workgroup with absent row blocks and a ragged last block; the shapes and batches it leaves to the other
-    kernels are checked in the same loop."""
+    """Tall matrices with two to eight requests (and with one request at one or two planes) run the FP4 family in its
+    row-streaming form (one operand image per four row blocks, chunks of 1024 columns prefetched one ahead): 4 to 8
+    chunks per row, one and two request tiles, one and two waves per row block, a last workgroup with absent row blocks
+    and a ragged last block; the shapes and batches it leaves to the other kernels are checked in the same loop."""
     import paper_2510_10467_amd as bcq
     layer = syn.make_layer(m, n, seed=(270, m, n), signed=True)
     dl = gpu.DeviceLayer(layer)
     rng = np.random.default_rng([syn.BASE_SEED, 270, m])
     rows = np.unique(np.concatenate([[0, 15, 16, 63, 64, m - 65, m - 64, m - 17, m - 16, m - 13, m - 2, m - 1], rng.integers(0, m, size=150)]))
     streamed = 0
-    for batch in (2, 3, 4, 5, 7, 8):
+    for batch in (1, 2, 3, 4, 5, 7, 8):
         x = syn.make_x(batch, n, seed=(270, batch))
         xd = gpu.to_dev(x)
         for p in (1, 2, 3, 4):
@@ -76,8 +77,10 @@ def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):
             if used == "plane_mfma_rows":
                 again = bcq.bcq_gemv(dl.planes, dl.scales[p], p, xd)
                 assert np.array_equal(again.cpu().numpy().view(np.uint16), y.cpu().numpy().view(np.uint16)), "not deterministic"
-    # up to four requests at every width from 640 row blocks on, five to eight at 4096 columns from 512 row blocks on
-    assert streamed == (0 if m < 10225 else 12) + (12 if n == 4096 else 0), streamed
+    # two to four requests at every width from 640 row blocks on, five to eight at 4096 columns from 512 row blocks on, one
+    # request at one or two planes from 896 row blocks on with 4096 or 8192 columns
+    single = 2 if m > 895 * 16 and n in (4096, 8192) else 0
+    assert streamed == (0 if m < 10225 else 12) + (12 if n == 4096 else 0) + single, streamed
 
 
 @pytest.mark.parametrize("m", [12300, 8200])
@@ -157,7 +160,7 @@ def test_row_streaming_form_several_matrices(gpu, oracle, ms, n):
     layers = [syn.make_layer(m, n, seed=(273, k, m), signed=True) for k, m in enumerate(ms)]
     dls = [gpu.DeviceLayer(L) for L in layers]
     rng = np.random.default_rng([syn.BASE_SEED, 273, len(ms)])
-    for batch in (2, 4, 7):
+    for batch in (1, 2, 4, 7):
         x = syn.make_x(batch, n, seed=(273, batch))
         xd = gpu.to_dev(x)
         for p in (2, 4):
@@ -165,7 +168,9 @@ def test_row_streaming_form_several_matrices(gpu, oracle, ms, n):
                 continue                    # (five to eight requests stream at 4096 columns only)
             outs = [gpu.Guarded((batch, m)) for m in ms]
             bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[p] for d in dls], p, xd, ys=[o.t for o in outs])
-            assert bcq.last_kernel() == "plane_mfma_rows", (ms, batch, p, bcq.last_kernel())
+            # (one request streams at one or two planes only, from 896 row blocks in all on)
+            single = p <= 2 and sum(ms) > 895 * 16
+            assert bcq.last_kernel() == ("plane_mfma_rows" if batch > 1 or single else "plane_mfma"), (ms, batch, p, bcq.last_kernel())
             for k, (L, d, o) in enumerate(zip(layers, dls, outs)):
                 y = o.check(f"multi matrix {k} of {ms} batch={batch} p={p}")
                 m = L.m
@@ -179,13 +184,12 @@ def test_row_streaming_form_several_matrices(gpu, oracle, ms, n):
 def test_row_streaming_form_reads_every_binary16_activation_exactly(gpu):
     """The row-streaming form builds its operand image with code of its own: every finite binary16 value, alone in its
     scale group, against rows whose only non-zero scale (1.0, one plane) sits on that group, comes back bit for bit
-    (two, four and eight requests: one and two request tiles)."""
+    (one, two, four and eight requests: one and two request tiles, one and two waves per row block)."""
     import paper_2510_10467_amd as bcq
-    m = 12288
     values = np.arange(65536, dtype=np.uint16).view(np.float16)
     values = values[np.isfinite(values)]                              # 63488 values
     seen = set()
-    for n, batch, launches in ((8192, 4, None), (8192, 2, 40), (4096, 8, 40)):
+    for n, batch, launches, m in ((8192, 4, None, 12288), (8192, 2, 40, 12288), (4096, 8, 40, 12288), (8192, 1, 40, 14336), (4096, 1, 40, 14336)):
         groups = n // 128
         rng = np.random.default_rng([syn.BASE_SEED, 271, n])
         planes = rng.integers(0, 2 ** 32, size=(1, m, n // 32), dtype=np.uint32)

@@ -51,6 +51,34 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
             sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"{name} p={p} batch={batch} ({bcq.last_kernel()})")
 
 
+@pytest.mark.parametrize("m,n,p,batches,kernels", [
+    # two planes of just under 2 GiB each (16 K slices in four chunks per wave; 32-bit offsets inside a plane at their limit)
+    (262144 - 11, 65536, 2, (1, 3, 16, 80), {"plane_mfma", "plane_f16", "dequant_mfma"}),
+    # one plane of more than 2 GiB: past what the tuned kernels address, the generic kernel takes every batch
+    (262144 + 5, 65536, 1, (1, 3), {"sign_select"}),
+])
+def test_planes_at_the_limit_of_32_bit_offsets(gpu, oracle, m, n, p, batches, kernels):
+    """Maximum sizes: byte offsets inside one plane are 32-bit in the tuned kernels, which take planes below 2 GiB; a
+    larger plane goes to the generic kernel, which indexes in 64 bits.  Sampled rows (first, last, the rows around 2^31
+    bytes into a plane) against the oracle, every output guarded."""
+    import paper_2510_10467_amd as bcq
+    layer = syn.make_layer(m, n, p_max=p, seed=(280, m, p), precisions=[p], signed=True)
+    dl = gpu.DeviceLayer(layer)
+    rng = np.random.default_rng([syn.BASE_SEED, 280, m])
+    rows = np.unique(np.concatenate([[0, 15, 16, m - 17, m - 16, m - 2, m - 1, 262143 - 16, min(262143, m - 1), min(262144, m - 1)],
+                                     rng.integers(0, m, size=60)]))
+    seen = set()
+    for batch in batches:
+        x = syn.make_x(batch, n, seed=(280, batch))
+        out = gpu.Guarded((batch, m))
+        bcq.bcq_gemv(dl.planes, dl.scales[p], p, gpu.to_dev(x), y=out.t)
+        used = bcq.last_kernel()
+        seen.add(used)
+        y = out.check(f"m={m} n={n} p={p} batch={batch} ({used})")
+        sampled_rows_check(gpu, oracle, layer, dl, p, x, rows, y, f"m={m} n={n} p={p} batch={batch} ({used})")
+    assert seen == kernels, seen
+
+
 @pytest.mark.parametrize("m,n", [(12300, 4096), (12290, 5120), (12400, 6144), (12500, 7168), (12304, 8192), (10236, 4096), (8200, 4096),
                                  (14330, 4096), (14350, 8192), (14336, 5120)])
 def test_row_streaming_form_sampled_rows(gpu, oracle, m, n):

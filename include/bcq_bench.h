@@ -29,7 +29,8 @@ typedef enum {
     BCQ_KERNEL_SIGN_SELECT = 1, /* generic per-bit add/subtract kernel, any legal shape */
     BCQ_KERNEL_PLANE_MFMA = 2,  /* bit-planes fed to the FP4 matrix pipe, small batches */
     BCQ_KERNEL_DEQUANT_MFMA = 3,/* dequantise to fp16 tiles in LDS + fp16 MFMA, large batches */
-    BCQ_KERNEL_PLANE_F16 = 4    /* +-1 planes as fp16 MFMA operands, group sums scaled in fp32 by each request's own scales; groups >= 128 */
+    BCQ_KERNEL_PLANE_F16 = 4,   /* +-1 planes as fp16 MFMA operands, group sums scaled in fp32 by each request's own scales; groups >= 128 */
+    BCQ_KERNEL_LUT = 5          /* table look-ups: 16 signed sums per four activations in LDS, a nibble of a plane word picks one; any legal shape */
 } bcq_kernel;
 
 /*
@@ -55,7 +56,7 @@ int bcq_selected_kernel(void);
 int bcq_select_dequant_shape(int request_tiles, int row_blocks);
 
 /* Name of the variant the calling thread's most recent successful launch used ("" before any): "sign_select",
- * "plane_mfma" ("plane_mfma_rows" where that family ran in its row-streaming form: tall matrices with two to eight
+ * "lut", "plane_mfma" ("plane_mfma_rows" where that family ran in its row-streaming form: tall matrices with two to eight
  * requests, or with one request at one or two planes), "dequant_mfma", "plane_f16", "quantize". */
 const char *bcq_last_kernel(void);
 

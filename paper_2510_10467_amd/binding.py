@@ -18,7 +18,7 @@ _lib = None
 
 BCQ_MAX_PLANES = 8
 KERNEL_AUTO, KERNEL_SIGN_SELECT, KERNEL_PLANE_MFMA, KERNEL_DEQUANT_MFMA = 0, 1, 2, 3
-KERNEL_IDS = {"auto": 0, "sign_select": 1, "plane_mfma": 2, "dequant_mfma": 3, "plane_f16": 4}
+KERNEL_IDS = {"auto": 0, "sign_select": 1, "plane_mfma": 2, "dequant_mfma": 3, "plane_f16": 4, "lut": 5}
 
 
 class BcqError(RuntimeError):

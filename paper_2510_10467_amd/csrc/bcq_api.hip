@@ -82,7 +82,9 @@ int choose(const bcq::GemmArgs &a)
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all
         // of its work per request, so the dequantising one wins from the second request on
         else if (dequant_mfma_supports(a) && a.batch >= 2 && a.m >= 1024) choice = BCQ_KERNEL_DEQUANT_MFMA;
-        else choice = BCQ_KERNEL_SIGN_SELECT;
+        // everything else (groups of 32, groups of 64 with offsets, odd widths, more than four planes): table look-ups,
+        // a third of the per-bit kernel's operations
+        else choice = lut_supports(a) ? BCQ_KERNEL_LUT : BCQ_KERNEL_SIGN_SELECT;
     }
     return choice;
 }
@@ -96,6 +98,11 @@ int run(const bcq::GemmArgs &a, hipStream_t stream)
         if (!sign_select_supports(a)) return BCQ_ERR_VARIANT;
         err = sign_select_launch(a, stream);
         g_last = "sign_select";
+        break;
+    case BCQ_KERNEL_LUT:
+        if (!lut_supports(a)) return BCQ_ERR_VARIANT;
+        err = lut_launch(a, stream);
+        g_last = "lut";
         break;
     case BCQ_KERNEL_PLANE_MFMA:
         if (!plane_mfma_supports(a)) return BCQ_ERR_VARIANT;
@@ -158,7 +165,7 @@ const char *bcq_strerror(int status)
 
 int bcq_select_kernel(int variant)
 {
-    if (variant < BCQ_KERNEL_AUTO || variant > BCQ_KERNEL_PLANE_F16) return BCQ_ERR_VARIANT;
+    if (variant < BCQ_KERNEL_AUTO || variant > BCQ_KERNEL_LUT) return BCQ_ERR_VARIANT;
     g_forced = variant;
     return BCQ_OK;
 }

@@ -45,6 +45,10 @@ hipError_t allow_dynamic_lds(const void *kernel, int bytes);
 bool sign_select_supports(const GemmArgs &a);
 hipError_t sign_select_launch(const GemmArgs &a, hipStream_t stream);
 
+// table look-ups (section 3.3's LUT formulation): any legal shape; the fallback ahead of sign_select
+bool lut_supports(const GemmArgs &a);
+hipError_t lut_launch(const GemmArgs &a, hipStream_t stream);
+
 bool plane_mfma_supports(const GemmArgs &a);
 bool plane_mfma_streams(const GemmArgs &a);     // tall matrix, 2 to 8 requests: the row-streaming form takes it
 hipError_t plane_mfma_launch(const GemmArgs &a, hipStream_t stream);

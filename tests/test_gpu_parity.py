@@ -43,25 +43,32 @@ SMALL_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("m,n,group", SMALL_SHAPES)
-def test_sign_select_uniform(gpu, m, n, group):
+GENERIC_KERNELS = ("sign_select", "lut")      # the two kernels that take every legal shape
+
+
+@pytest.mark.parametrize("kernel", GENERIC_KERNELS)
+@pytest.mark.parametrize("m,n,group", SMALL_SHAPES + [(200, 6240, 96), (67, 2080, 32), (129, 4096, 128)])
+def test_generic_kernels_uniform(gpu, m, n, group, kernel):
+    """(with the table look-ups: one and several table tiles of 2048 columns, a ragged last tile, more and fewer rows
+    than a workgroup's 64, one and two request tiles of four)"""
     layer = syn.make_layer(m, n, group=group, seed=(110, m), signed=True)
     dl = gpu.DeviceLayer(layer)
     for batch in (1, 3, 5):
         x = syn.make_x(batch, n, seed=(110, batch))
         for p in (1, 2, 3, 4):
-            used, _ = gpu.check_gemv(dl, p, x, "sign_select", group)
-            assert used == "sign_select"
+            used, _ = gpu.check_gemv(dl, p, x, kernel, group)
+            assert used == kernel
 
 
-@pytest.mark.parametrize("m,n,group", [(37, 2048, 128), (16, 1024, 128), (19, 256, 64)])
-def test_sign_select_mixed(gpu, m, n, group):
+@pytest.mark.parametrize("kernel", GENERIC_KERNELS)
+@pytest.mark.parametrize("m,n,group", [(37, 2048, 128), (16, 1024, 128), (19, 256, 64), (70, 4160, 32)])
+def test_generic_kernels_mixed(gpu, m, n, group, kernel):
     layer = syn.make_layer(m, n, group=group, seed=(120, m), signed=True)
     dl = gpu.DeviceLayer(layer)
     for batch in (1, 6, 16):
         x = syn.make_x(batch, n, seed=(120, batch))
         p_req = syn.make_p_req(batch, 1, 4, seed=(120, batch))
-        gpu.check_mixed(dl, p_req, x, "sign_select", group)
+        gpu.check_mixed(dl, p_req, x, kernel, group)
 
 
 @pytest.fixture
@@ -437,17 +444,18 @@ def test_offsets_plane_mfma(gpu, m, n):
         gpu.check_mixed(dl, p_req, x, "plane_mfma", offsets_by_p={2: zs[2], 4: zs[4]})   # precisions 1 and 3 have none
 
 
-@pytest.mark.parametrize("m,n,group", [(37, 2048, 128), (33, 640, 128), (9, 512, 64), (5, 96, 32)])
-def test_offsets_sign_select(gpu, m, n, group):
+@pytest.mark.parametrize("kernel", GENERIC_KERNELS)
+@pytest.mark.parametrize("m,n,group", [(37, 2048, 128), (33, 640, 128), (9, 512, 64), (5, 96, 32), (70, 4160, 64)])
+def test_offsets_generic_kernels(gpu, m, n, group, kernel):
     layer = syn.make_layer(m, n, group=group, seed=(182, m), signed=True)
     dl = gpu.DeviceLayer(layer)
     zs = {p: syn.make_offsets(p, m, n, group, seed=(182, m)) for p in (1, 2, 3, 4)}
     for batch in (1, 5):
         x = syn.make_x(batch, n, seed=(182, batch))
         for p in (1, 3, 4):
-            gpu.check_gemv(dl, p, x, "sign_select", group, offsets=zs[p])
+            gpu.check_gemv(dl, p, x, kernel, group, offsets=zs[p])
         p_req = syn.make_p_req(batch, 1, 4, seed=(182, batch))
-        gpu.check_mixed(dl, p_req, x, "sign_select", group, offsets_by_p={1: zs[1], 3: zs[3]})
+        gpu.check_mixed(dl, p_req, x, kernel, group, offsets_by_p={1: zs[1], 3: zs[3]})
 
 
 @pytest.mark.parametrize("m,n", [(37, 2048), (131, 4096), (64, 640)])
@@ -550,7 +558,7 @@ def test_gemv_multi_falls_back_to_separate_launches(gpu, oracle):
     xh = syn.make_x(2, 640, seed=(191, 0))
     ys = bcq.bcq_gemv_multi([d.planes for d in dls], [d.scales[3] for d in dls], 3, gpu.to_dev(xh))
     torch.cuda.synchronize()
-    assert bcq.last_kernel() == "sign_select"
+    assert bcq.last_kernel() == "lut"
     for d, y in zip(dls, ys):
         y_ref, a_ref = oracle.gemv(d.layer.planes, d.layer.scales[3], xh)
         gpu.assert_within_tolerance(y, y_ref, a_ref, "bcq_gemv_multi fallback")

@@ -54,12 +54,12 @@ def test_full_size_layers_sampled_rows(gpu, oracle, name, m, n):
 @pytest.mark.parametrize("m,n,p,batches,kernels", [
     # two planes of just under 2 GiB each (16 K slices in four chunks per wave; 32-bit offsets inside a plane at their limit)
     (262144 - 11, 65536, 2, (1, 3, 16, 80), {"plane_mfma", "plane_f16", "dequant_mfma"}),
-    # one plane of more than 2 GiB: past what the tuned kernels address, the generic kernel takes every batch
-    (262144 + 5, 65536, 1, (1, 3), {"sign_select"}),
+    # one plane of more than 2 GiB: past what the tuned kernels address, the table look-up kernel takes every batch
+    (262144 + 5, 65536, 1, (1, 3), {"lut"}),
 ])
 def test_planes_at_the_limit_of_32_bit_offsets(gpu, oracle, m, n, p, batches, kernels):
     """Maximum sizes: byte offsets inside one plane are 32-bit in the tuned kernels, which take planes below 2 GiB; a
-    larger plane goes to the generic kernel, which indexes in 64 bits.  Sampled rows (first, last, the rows around 2^31
+    larger plane goes to the table look-up kernel, which indexes in 64 bits.  Sampled rows (first, last, the rows around 2^31
     bytes into a plane) against the oracle, every output guarded."""
     import paper_2510_10467_amd as bcq
     layer = syn.make_layer(m, n, p_max=p, seed=(280, m, p), precisions=[p], signed=True)
@@ -253,7 +253,7 @@ def test_prefix_invariance_and_determinism(gpu):
     m, n = 300, 4096
     layer = syn.make_layer(m, n, seed=(210, 0))
     x = gpu.to_dev(syn.make_x(2, n, seed=(210, 0)))
-    for kernel in ("plane_mfma", "sign_select", "dequant_mfma", "plane_f16"):
+    for kernel in ("plane_mfma", "sign_select", "lut", "dequant_mfma", "plane_f16"):
         bcq.select_kernel(kernel)
         try:
             for p in (1, 2, 3):
@@ -286,7 +286,7 @@ def test_one_hot_readout_and_symmetries(gpu, oracle):
     for b, j in enumerate(cols):
         x[b, j] = 1.0
     xr = syn.make_x(4, n, seed=(220, 1))
-    for kernel in ("plane_mfma", "sign_select", "dequant_mfma", "plane_f16"):
+    for kernel in ("plane_mfma", "sign_select", "lut", "dequant_mfma", "plane_f16"):
         bcq.select_kernel(kernel)
         try:
             y = bcq.bcq_gemv(gpu.to_dev(planes), gpu.to_dev(scales), p, gpu.to_dev(x)).cpu().numpy().astype(np.float64)
@@ -351,7 +351,7 @@ def test_p_req_is_clamped_and_missing_scale_set_gives_zeros(gpu, oracle):
     layer = syn.make_layer(m, n, seed=(240, 0))
     dl = gpu.DeviceLayer(layer)
     x = syn.make_x(4, n, seed=(240, 1))
-    for kernel in ("plane_mfma", "sign_select"):
+    for kernel in ("plane_mfma", "sign_select", "lut"):
         bcq.select_kernel(kernel)
         try:
             y = bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(np.array([0, 9, -3, 4], dtype=np.int32)), gpu.to_dev(x))
@@ -369,7 +369,7 @@ def test_p_req_is_clamped_and_missing_scale_set_gives_zeros(gpu, oracle):
             bcq.select_kernel("auto")
 
 
-ALL_FAMILIES = ("plane_mfma", "sign_select", "dequant_mfma", "plane_f16")
+ALL_FAMILIES = ("plane_mfma", "sign_select", "lut", "dequant_mfma", "plane_f16")
 
 
 def test_extreme_activation_magnitudes(gpu, oracle):

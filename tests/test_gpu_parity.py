@@ -71,6 +71,24 @@ def test_generic_kernels_mixed(gpu, m, n, group, kernel):
         gpu.check_mixed(dl, p_req, x, kernel, group)
 
 
+@pytest.mark.parametrize("kernel", GENERIC_KERNELS + ("auto",))
+@pytest.mark.parametrize("m,n,group", [(70, 4224, 128), (9, 256, 64), (300, 2048, 128)])
+def test_five_to_eight_planes(gpu, m, n, group, kernel):
+    """The ABI takes up to eight planes; beyond four they run on the table look-ups (the default) or the per-bit kernel:
+    uniform precision 5 to 8, and per-request precision drawn from 1 to 8 with planes stored to 8."""
+    layer = syn.make_layer(m, n, p_max=8, group=group, seed=(125, m), signed=True)
+    dl = gpu.DeviceLayer(layer)
+    for batch in (1, 3):
+        x = syn.make_x(batch, n, seed=(125, batch))
+        for p in (5, 6, 7, 8):
+            used, _ = gpu.check_gemv(dl, p, x, kernel, group)
+            assert used == ("lut" if kernel == "auto" else kernel)
+        p_req = syn.make_p_req(batch, 1, 8, seed=(125, batch))
+        p_req[0] = 8
+        used, _ = gpu.check_mixed(dl, p_req, x, kernel, group)
+        assert used == ("lut" if kernel == "auto" else kernel)
+
+
 @pytest.fixture
 def forced_shape():
     """Force a workgroup shape of the large-batch kernel ("tiles,row blocks") for one test."""

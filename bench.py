@@ -455,6 +455,17 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_note,
                 "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3)}
 
+    # The same product in the other formulations the library holds (section 3.3 names table look-ups; the per-bit
+    # add/subtract form is its plain reading): why the matrix-pipe kernel is the one that runs.
+    formulations = {"workload": f"m={dm} n={dn} batch 1 p={dom_p}, us per call over cold copies",
+                    "plane_mfma": round(dom_us, 3)}
+    for variant in ("lut", "sign_select"):
+        bcq.select_kernel(variant)
+        try:
+            formulations[variant] = round(kernel_time_us(dom_li, dom_p, launches=16), 3)
+        finally:
+            bcq.select_kernel("auto")
+
     # What a pure streaming read reaches on this GPU: as many bytes as the dominant kernel moves (cold, rotating
     # over distinct buffers, back-to-back launches in a graph), and 1 GiB in one launch.
     sink = torch.zeros(64, dtype=torch.int32, device=dev)
@@ -654,6 +665,7 @@ def main():
         "multi_call": multi_call,
         "fp16_gemv": fp16_gemv,
         "single_gemv_4096": single_gemv_4096,
+        "formulations": formulations,
         "llama70b_batch1": llama70b,
         "mixed_vs_uniform": mixed_vs_uniform,
         "decode_batches": decode_batches,

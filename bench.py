@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--details", action="store_true", help="also time every (layer, p) kernel and an fp16 GEMV")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a reference kernel of known traffic for counter runs)")
-    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused", "offset", "quant", "step", "issue"], default=None,
+    ap.add_argument("--suite", choices=["decode", "mixed", "large", "phi4", "fused", "offset", "quant", "step", "issue", "generic"], default=None,
                     help="instead of the headline workload, time another workload family and print its table")
     return ap.parse_args()
 
@@ -174,6 +174,21 @@ def run_suite(args, torch, bcq, syn, dev):
         for (m, n) in ((4096, 4096), (14336, 4096), (4096, 14336)):
             bench_shape(m, n, (1, 64), PRECISIONS)
             bench_shape(m, n, (1, 64), PRECISIONS, offsets=True)
+    elif args.suite == "generic":
+        # the table look-up kernel and the per-bit kernel, which take every legal shape, beside the default choice: on
+        # shapes of the main workload, and on a width only they take (4224 columns: not a multiple of 256)
+        for variant in ("auto", "lut", "sign_select"):
+            bcq.select_kernel(variant)
+            try:
+                first = len(rows)
+                bench_shape(14336, 4096, (1, 2, 8), (2, 4))
+                bench_shape(4096, 4096, (1,), (2, 4))
+                bench_shape(1024, 4096, (1,), (4,))
+                bench_shape(14336, 4224, (1, 8), (4,))
+                for r in rows[first:]:
+                    r["forced"] = variant
+            finally:
+                bcq.select_kernel("auto")
     elif args.suite == "phi4":
         # second model of the paper's GEMV table; 17920 columns end in a half slice
         for (_, m, n) in syn.PHI4_14B_SHAPES:

@@ -77,8 +77,9 @@ __global__ __launch_bounds__(64 * kLutWaves) void lut_kernel(GemmArgs a)
         for (int t = 0; t < NR; ++t) acc[k][t] = 0.f;
 
     // table building: a thread takes two runs of four columns (c0 and c0 + 1) of a tile with all 16 entries of each;
-    // run c belongs to word c >> 3 (the lane that will look it up) and nibble c & 7
-    const int c0 = 2 * tid;
+    // run c belongs to word c >> 3 (the lane that will look it up) and nibble c & 7.  The 64 threads of a wave take
+    // the same pair of nibbles of 64 different words, so that their stores fall into 64 consecutive LDS words.
+    const int c0 = (lane << 3) + 2 * wave;
     unsigned char *build_at = lds + ((c0 & 7) * 16 * 64 + (c0 >> 3)) * 4;
     const unsigned char *lane_tables = lds + lane * 4;
 

@@ -147,6 +147,8 @@ def test_argument_validation_without_device(lib):
     assert lib.bcq_select_dequant_shape(-1, 4) == -6
     assert lib.bcq_select_dequant_shape(0, 0) == 0
     assert lib.bcq_select_kernel(17) == -6
+    assert lib.bcq_select_kernel(5) == 0            # the table look-up kernel is the last variant
+    assert lib.bcq_select_kernel(6) == -6
     assert lib.bcq_select_kernel(0) == 0
 
 

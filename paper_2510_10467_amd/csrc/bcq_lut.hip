@@ -36,7 +36,8 @@ __device__ __forceinline__ float wave_sum(float v)
 // PU: planes the loops are unrolled for (4 or 8; planes beyond the deepest precision present are skipped)
 // RPW: rows per wave (4, 2 or 1: 16, 8 or 4 rows per workgroup, so that short matrices still fill the chip)
 // TT: tiles per stretch; NR: requests per workgroup (TT * NR tables of 32 KiB)
-template <int PU, int RPW, int TT, int NR>
+// UNI: one precision for all requests (their scales are fetched with the plane words)
+template <int PU, int RPW, int TT, int NR, bool UNI>
 __global__ __launch_bounds__(64 * kLutWaves) void lut_kernel(GemmArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(64 * kLutWaves) void lut_kernel(GemmArgs a)
         pb[t] = __builtin_amdgcn_readfirstlane((b0 + t < a.batch) ? request_precision(a, b0 + t) : 0);
         p_hi = pb[t] > p_hi ? pb[t] : p_hi;
     }
-    const bool uniform = a.uniform_p > 0;
+    constexpr bool uniform = UNI;
     const _Float16 *const uniform_set = a.scales[uniform ? a.uniform_p : 0];
     // rows of this wave; rows past the end repeat the last row (their sums are never stored).  Word and scale indices
     // inside one plane fit 32 bits (checked on the host): a load is a scalar base per plane plus a lane offset.
@@ -110,20 +111,21 @@ __global__ __launch_bounds__(64 * kLutWaves) void lut_kernel(GemmArgs a)
             g[tt] = w_at / (uint32_t)words_per_group;
 #pragma unroll
             for (int i = 0; i < PU; ++i) {
-                const uint32_t *plane = a.planes + (int64_t)i * plane_words;
-                const _Float16 *scale_plane = uniform_set + (int64_t)i * plane_scales;
+                // (planes beyond the deepest precision present repeat its last plane: a load without a branch around it
+                // stays up here, ahead of the table building, and those words are never looked up)
+                const int ii = i < p_hi ? i : (p_hi > 0 ? p_hi - 1 : 0);
+                const uint32_t *plane = a.planes + (int64_t)ii * plane_words;
+                const _Float16 *scale_plane = uniform_set + (int64_t)ii * plane_scales;
 #pragma unroll
                 for (int k = 0; k < RPW; ++k) {
-                    w[tt][i][k] = 0;
+                    w[tt][i][k] = plane[row_word0[k] + w_at];
                     alpha_u[tt][i][k] = (_Float16)0.f;
-                    if (i < p_hi) {
-                        w[tt][i][k] = plane[row_word0[k] + w_at];
-                        if (uniform) alpha_u[tt][i][k] = scale_plane[row_scale0[k] + g[tt]];
-                    }
+                    if constexpr (uniform) alpha_u[tt][i][k] = scale_plane[row_scale0[k] + g[tt]];
                 }
             }
         }
 
+        __builtin_amdgcn_sched_barrier(0);                  // (the loads stay ahead of everything below)
         if (tile0 > 0) __syncthreads();                     // the previous stretch's tables are no longer read
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
@@ -215,11 +217,11 @@ int lut_rows_per_wave(const GemmArgs &a) { return a.m >= 8192 ? 4 : a.m >= 2048 
 
 constexpr int kLutRequests = 2;           // requests per workgroup from two requests on (64 KiB of tables: two workgroups per compute unit)
 
-template <int PU, int RPW, int TT, int NR>
+template <int PU, int RPW, int TT, int NR, bool UNI>
 hipError_t lut_launch_as(const GemmArgs &a, hipStream_t stream)
 {
     constexpr int lds_bytes = TT * NR * kLutTileBytes;
-    auto kernel = lut_kernel<PU, RPW, TT, NR>;
+    auto kernel = lut_kernel<PU, RPW, TT, NR, UNI>;
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds_bytes)) return e;
     constexpr int rows = kLutWaves * RPW;
     dim3 grid((unsigned)((a.m + rows - 1) / rows), (unsigned)((a.batch + NR - 1) / NR));
@@ -231,8 +233,9 @@ template <int PU, int RPW>
 hipError_t lut_launch_rows(const GemmArgs &a, hipStream_t stream)
 {
     // one request: two tiles per stretch (one trip to memory and one pair of barriers for 4096 columns)
-    if (a.batch == 1) return lut_launch_as<PU, RPW, 2, 1>(a, stream);
-    return lut_launch_as<PU, RPW, 1, kLutRequests>(a, stream);
+    if (a.uniform_p > 0)
+        return a.batch == 1 ? lut_launch_as<PU, RPW, 2, 1, true>(a, stream) : lut_launch_as<PU, RPW, 1, kLutRequests, true>(a, stream);
+    return a.batch == 1 ? lut_launch_as<PU, RPW, 2, 1, false>(a, stream) : lut_launch_as<PU, RPW, 1, kLutRequests, false>(a, stream);
 }
 
 }  // namespace

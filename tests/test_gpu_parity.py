@@ -684,3 +684,52 @@ def test_seeded_random_cases_against_the_oracle(gpu):
         finally:
             bcq.select_dequant_shape(0, 0)
         done += 1
+
+
+def test_seeded_random_cases_on_the_table_look_up_kernel(gpu):
+    """Forty seeded random cases forced onto the table look-ups: widths that are multiples of 32 only (one to four table
+    tiles, ragged last tile), groups of 32 to 416 columns, planes stored to 3..8, ragged row counts on both sides of the
+    4, 8 and 16 rows of a workgroup, one request (two tiles per stretch) and several, precisions uniform or per request,
+    inside and outside [1, p_max], offsets for some precisions."""
+    import torch
+
+    import paper_2510_10467_amd as bcq
+    rng = np.random.default_rng([syn.BASE_SEED, 920])
+    done = 0
+    while done < 40:
+        group = int(rng.choice([32, 64, 96, 128, 160, 256, 416]))
+        n = group * int(rng.integers(1, 1 + min(40, 8320 // group)))
+        m = int(rng.choice([1, 3, 4, 5, 17, 63, 130, 2047, 2050, 8191, 8200]))
+        batch = int(rng.choice([1, 1, 1, 2, 3, 5, 8, 9]))
+        p_max = int(rng.integers(3, 9))
+        if m * n > 24_000_000:
+            continue
+        layer = syn.make_layer(m, n, p_max=p_max, group=group, seed=(921, done), signed=bool(rng.integers(2)))
+        dl = gpu.DeviceLayer(layer)
+        x = syn.make_x(batch, n, seed=(922, done))
+        kind = int(rng.integers(3))
+        if kind == 0:
+            p_req = syn.make_p_req(batch, 1, p_max, seed=(923, done))
+        elif kind == 1:
+            p_req = np.full(batch, int(rng.integers(1, p_max + 1)), dtype=np.int32)
+        else:
+            p_req = rng.choice([1, p_max, p_max, 11, -2], size=batch).astype(np.int32)
+        zs = None
+        if rng.integers(3) == 0:
+            zs = {p: syn.make_offsets(p, m, n, group, seed=(924, done, p)) for p in range(1, p_max + 1) if rng.integers(2)}
+        what = f"lut case {done}: m={m} n={n} group={group} batch={batch} p_max={p_max} kind={kind} offsets={sorted(zs) if zs else None}"
+        bcq.select_kernel("lut")
+        try:
+            out = gpu.Guarded((batch, m))
+            bcq.bcq_gemm_mixed(dl.planes, dl.scales, gpu.to_dev(p_req.astype(np.int32)), gpu.to_dev(x), y=out.t, group=group,
+                               offsets_by_p={q: gpu.to_dev(z) for q, z in zs.items()} if zs else None)
+            assert bcq.last_kernel() == "lut"
+            y = out.check(what)
+        finally:
+            bcq.select_kernel("auto")
+        y_ref, a_ref = gpu.oracle.gemm_mixed(layer.planes, layer.scales, np.clip(p_req, 1, p_max).astype(np.int32), x, group, offsets_by_p=zs)
+        gpu.assert_within_tolerance(y, y_ref, a_ref, what)
+        p = int(rng.integers(1, p_max + 1))
+        used, _ = gpu.check_gemv(dl, p, x, "lut", group, offsets=zs[p] if zs and p in zs else None)
+        assert used == "lut"
+        done += 1

@@ -81,7 +81,14 @@ int choose(const bcq::GemmArgs &a)
         else if (plane_mfma_supports(a)) choice = BCQ_KERNEL_PLANE_MFMA;
         // shapes the plane-wise kernel does not take (groups of 64, odd widths): the generic kernel repeats all
         // of its work per request, so the dequantising one wins from the second request on
-        else if (dequant_mfma_supports(a) && a.batch >= 2 && a.m >= 1024) choice = BCQ_KERNEL_DEQUANT_MFMA;
+        // (the plane-wise fp16 variant up to 32 requests, as on the shapes above)
+        else if (dequant_mfma_supports(a) && a.batch >= 2 && a.m >= 1024) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
+        // one request on a width the plane-wise kernel does not take, 4096 rows and more, not too large: the large-batch
+        // kernels, whose time is flat from one request on, are ahead of the table look-ups (14336 x 4224 at p = 4:
+        // 20.8 us plane-wise fp16 and 23.1 us dequantising against 26.4 us; 4096 x 4224: 7.7 against 9.8), while
+        // 1024 rows (7.9 against 6.7) and 28672 x 8320 (72 against 68) stay with the look-ups
+        else if (dequant_mfma_supports(a) && a.uniform_p > 0 && a.m >= 4096 && a.m * a.n < (int64_t)150000000)
+            choice = f16_ok ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         // everything else (groups of 32, groups of 64 with offsets, odd widths, more than four planes): table look-ups,
         // a third of the per-bit kernel's operations
         else choice = lut_supports(a) ? BCQ_KERNEL_LUT : BCQ_KERNEL_SIGN_SELECT;

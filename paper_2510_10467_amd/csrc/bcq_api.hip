@@ -83,11 +83,13 @@ int choose(const bcq::GemmArgs &a)
         // of its work per request, so the dequantising one wins from the second request on
         // (the plane-wise fp16 variant up to 32 requests, as on the shapes above)
         else if (dequant_mfma_supports(a) && a.batch >= 2 && a.m >= 1024) choice = tiles16 ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
-        // one request on a width the plane-wise kernel does not take, 4096 rows and more, not too large: the large-batch
-        // kernels, whose time is flat from one request on, are ahead of the table look-ups (14336 x 4224 at p = 4:
-        // 20.8 us plane-wise fp16 and 23.1 us dequantising against 26.4 us; 4096 x 4224: 7.7 against 9.8), while
-        // 1024 rows (7.9 against 6.7) and 28672 x 8320 (72 against 68) stay with the look-ups
-        else if (dequant_mfma_supports(a) && a.uniform_p > 0 && a.m >= 4096 && a.m * a.n < (int64_t)150000000)
+        // one request on a width the plane-wise kernel does not take, not too large: the large-batch kernels, whose time is
+        // flat from one request on, are ahead of the table look-ups: the plane-wise fp16 variant from 2048 rows on (14336 x
+        // 4224 at p = 4: 20.8 against 26.4 us; 2048 x 4224: 7.3 against 8.5; 14336 x 640: 5.5 against 12.4) and from 1024
+        // rows on narrow matrices (1024 x 640: 3.2 against 4.1), the dequantising one (groups of 64) from 4096 rows on
+        // (23.1 against 26.4 us), while 1024 x 4224 (7.1 against 6.7) and 28672 x 8320 (72 against 68) stay with the look-ups
+        else if (dequant_mfma_supports(a) && a.uniform_p > 0 && a.m * a.n < (int64_t)150000000 &&
+                 (f16_ok ? a.m >= 2048 || (a.m >= 1024 && a.n <= 2048) : a.m >= 4096))
             choice = f16_ok ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
         // everything else (groups of 32, groups of 64 with offsets, odd widths, more than four planes): table look-ups,
         // a third of the per-bit kernel's operations

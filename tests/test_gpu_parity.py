@@ -736,14 +736,16 @@ def test_seeded_random_cases_on_the_table_look_up_kernel(gpu):
 
 
 def test_auto_dispatch_on_widths_the_plane_wise_kernel_does_not_take(gpu):
-    """n = 1152 (a multiple of 128, not of 256): with 4096 rows and more the large-batch kernels take it from one request
-    on (plane-wise fp16 up to 32 requests); shorter matrices go to the table look-ups at one request and to the large-batch
-    kernels from two; groups of 32 always run on the table look-ups."""
+    """n = 1152 (a multiple of 128, not of 256): with 1024 rows and more (2048 on wider matrices) the large-batch kernels take
+    it from one request on (plane-wise fp16 up to 32 requests); shorter matrices go to the table look-ups at one request and to
+    the large-batch kernels from two; groups of 32 always run on the table look-ups."""
     tall = gpu.DeviceLayer(syn.make_layer(4100, 1152, seed=(175, 0)))
-    short = gpu.DeviceLayer(syn.make_layer(1100, 1152, seed=(175, 1)))
+    short = gpu.DeviceLayer(syn.make_layer(1000, 1152, seed=(175, 1)))
     fine = gpu.DeviceLayer(syn.make_layer(4100, 1152, group=32, seed=(175, 2)))
-    for dl, batch, group, want in ((tall, 1, 128, "plane_f16"), (tall, 3, 128, "plane_f16"), (tall, 40, 128, "dequant_mfma"),
-                                   (short, 1, 128, "lut"), (short, 3, 128, "plane_f16"), (fine, 1, 32, "lut"), (fine, 5, 32, "lut")):
+    mid = gpu.DeviceLayer(syn.make_layer(1100, 1152, seed=(175, 3)))
+    for dl, batch, group, want in ((mid, 1, 128, "plane_f16"), (mid, 2, 128, "plane_f16"),
+                                   (tall, 1, 128, "plane_f16"), (tall, 3, 128, "plane_f16"), (tall, 40, 128, "dequant_mfma"),
+                                   (short, 1, 128, "lut"), (short, 3, 128, "lut"), (fine, 1, 32, "lut"), (fine, 5, 32, "lut")):
         for p in (2, 4):
             used, _ = gpu.check_gemv(dl, p, syn.make_x(batch, 1152, seed=(175, batch)), "auto", group)
             assert used == want, (dl.layer.m, batch, group, p, used)

@@ -176,7 +176,7 @@ def run_suite(args, torch, bcq, syn, dev):
             bench_shape(m, n, (1, 64), PRECISIONS, offsets=True)
     elif args.suite == "generic":
         # the table look-up kernel and the per-bit kernel, which take every legal shape, beside the default choice: on
-        # shapes of the main workload, and on a width only they take (4224 columns: not a multiple of 256)
+        # shapes of the main workload, and on a width the plane-wise FP4 kernel does not take (4224 columns: not a multiple of 256)
         for variant in ("auto", "lut", "sign_select"):
             bcq.select_kernel(variant)
             try:

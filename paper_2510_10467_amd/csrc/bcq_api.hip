@@ -91,7 +91,7 @@ int choose(const bcq::GemmArgs &a)
         else if (dequant_mfma_supports(a) && a.uniform_p > 0 && a.m * a.n < (int64_t)150000000 &&
                  (f16_ok ? a.m >= 2048 || (a.m >= 1024 && a.n <= 2048) : a.m >= 4096))
             choice = f16_ok ? BCQ_KERNEL_PLANE_F16 : BCQ_KERNEL_DEQUANT_MFMA;
-        // everything else (groups of 32, groups of 64 with offsets, odd widths, more than four planes): table look-ups,
+        // everything else (groups of 32, odd widths on short or very large matrices, more than four planes): table look-ups,
         // a third of the per-bit kernel's operations
         else choice = lut_supports(a) ? BCQ_KERNEL_LUT : BCQ_KERNEL_SIGN_SELECT;
     }

@@ -61,7 +61,7 @@ struct PlaneMfmaParams {
     const unsigned char *x;                 // activations of request 0 of the whole batch
     _Float16 *y;
     const unsigned char *scales[BCQ_MAX_PLANES + 1];   // scale set per precision (bytes)
-    const unsigned char *offsets[BCQ_MAX_PLANES + 1];  // offsets [m][n/128] per precision, or nullptr (asymmetric scheme)
+    const unsigned char *offsets[BCQ_MAX_PLANES + 1];  // offsets [m][n/group] per precision, or nullptr (asymmetric scheme)
     const int32_t *p_req;                   // per-request precisions (mixed) or nullptr
     uint32_t set_mask;                      // bit k set: scales[k] is there (k = 1 .. 4)
     uint32_t offset_mask;                   // bit k set: offsets[k] is there
@@ -142,6 +142,7 @@ struct SliceLoads {
     u32x4 sc[PH];                           // the 8 scales of the lane's row, per plane (groups of 64: the first 8 of 16)
     u32x4 sc2[PH];                          // groups of 64 columns only: scales 8..15 of the slice
     u32x4 zc;                               // the 8 offsets of the lane's row (asymmetric scheme only)
+    u32x4 zc2;                              // groups of 64 columns only: offsets 8..15 of the slice
     u32x4 wa[PH], wb[PH];                   // plane words: rows 0-7 and rows 8-15 of the block
 };
 
@@ -210,7 +211,10 @@ __device__ __forceinline__ void issue_loads(SliceLoads<PH, NB> &ld, const PlaneM
             if constexpr (GS < 0) ld.sc2[i] = load_scales(s_base + off.s + 16);
         }
     }
-    if constexpr (OFFSET) ld.zc = load_scales(zbase + s_slice + off.s);
+    if constexpr (OFFSET) {
+        ld.zc = load_scales(zbase + s_slice + off.s);
+        if constexpr (GS < 0) ld.zc2 = load_scales(zbase + s_slice + off.s + 16);
+    }
     const uint32_t wa = off.wa + w_lane, wb = off.wb + w_lane;
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
@@ -293,8 +297,16 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
                     xsum += (float)pair[0];
                     xsum += (float)pair[1];
                 }
-                xsum = sum_over_8_lanes(xsum);
-                if (u16 == 0) *reinterpret_cast<float *>(img_group + 4 * L::kRows * 16 + b * 4) = xsum;
+                if constexpr (GS < 0) {
+                    // groups of 64 columns: the units 0-3 and 4-7 of the 128 columns are two groups; each sum goes into the
+                    // padding behind its own half of the image
+                    xsum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, xsum), 0xB1, 0xf, 0xf, false));
+                    xsum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, xsum), 0x4E, 0xf, 0xf, false));
+                    if ((u16 & 3) == 0) *reinterpret_cast<float *>(img_group + (u16 >> 2) * L::kHalfBytes + 4 * L::kRows * 16 + b * 4) = xsum;
+                } else {
+                    xsum = sum_over_8_lanes(xsum);
+                    if (u16 == 0) *reinterpret_cast<float *>(img_group + 4 * L::kRows * 16 + b * 4) = xsum;
+                }
             }
 #pragma unroll
             for (int low = 0; low < 4; ++low) {
@@ -339,7 +351,10 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
             }
         }
         if constexpr (OFFSET) {
-            if (!z_on || !slice_ok) ld.zc = u32x4{0, 0, 0, 0};
+            if (!z_on || !slice_ok) {
+                ld.zc = u32x4{0, 0, 0, 0};
+                if constexpr (GS < 0) ld.zc2 = u32x4{0, 0, 0, 0};
+            }
         }
         // scales of planes this lane must not use (beyond its precision, or a slice past the end) become zero
         if (MIXED || !slice_ok) {
@@ -372,7 +387,15 @@ __device__ __forceinline__ float sweep(const PlaneMfmaParams &pr, unsigned char 
 #pragma unroll
         for (int gl = 0; gl < kSliceGroups; ++gl) {
             const v8i xa = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-            if constexpr (OFFSET) {
+            if constexpr (OFFSET && GS < 0) {
+                // groups of 64 columns: offsets 2 gl and 2 gl + 1 of the slice times the sums of the two halves
+                const uint32_t zw = gl < 4 ? ld.zc[gl & 3] : ld.zc2[gl & 3];
+                const float z_lo = (float)__builtin_bit_cast(_Float16, (unsigned short)(zw & 0xffffu));
+                const float z_hi = (float)__builtin_bit_cast(_Float16, (unsigned short)(zw >> 16));
+                const float xsum_hi = *reinterpret_cast<const float *>(img_xsum + gl * L::kGroupBytes + L::kHalfBytes);
+                acc = fmaf(z_lo, xsum, acc);
+                acc = fmaf(z_hi, xsum_hi, acc);
+            } else if constexpr (OFFSET) {
                 // offset of the group times the sum of its activations
                 const uint32_t zw = ld.zc[gl >> 1];
                 const float z = (float)__builtin_bit_cast(_Float16, (unsigned short)((gl & 1) ? (zw >> 16) : (zw & 0xffffu)));
@@ -982,9 +1005,7 @@ hipError_t launch_group(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan
 template <int NB, bool OFFSET>
 hipError_t launch_nb(const GemmArgs &a, const PlaneMfmaParams &pr, const Plan &pl, dim3 grid, dim3 block, hipStream_t stream)
 {
-    if constexpr (!OFFSET) {
-        if (a.group == 64) return launch_group<NB, false, -1>(a, pr, pl, grid, block, stream);
-    }
+    if (a.group == 64) return launch_group<NB, OFFSET, -1>(a, pr, pl, grid, block, stream);
     return a.group == 256 ? launch_group<NB, OFFSET, 1>(a, pr, pl, grid, block, stream)
                           : launch_group<NB, OFFSET, 0>(a, pr, pl, grid, block, stream);
 }
@@ -1165,11 +1186,9 @@ bool plane_mfma_supports(const GemmArgs &a)
                               a.m < (int64_t(1) << 24) && a.n < (int64_t(1) << 24);
     // whole scale groups, 4-byte aligned scale rows, and at least eight groups of 128 per row (the scales of
     // a short last slice are fetched as the last ones of the row); scale groups of 128 or 256 columns
-    // groups of 64 (two matrix instructions per 128 columns, one per half): whole K slices, symmetric scheme
-    bool any_offsets = false;
-    for (int q = 1; q <= kMaxP; ++q) any_offsets = any_offsets || a.offsets[q] != nullptr;
+    // groups of 64 (two matrix instructions per 128 columns, one per half): whole K slices
     const bool group_ok = (a.group == 128 && (a.n % 256) == 0) || (a.group == 256 && (a.n % 512) == 0) ||
-                          (a.group == 64 && (a.n % kSliceCols) == 0 && !any_offsets);
+                          (a.group == 64 && (a.n % kSliceCols) == 0);
     return group_ok && a.n >= kSliceCols && a.p_max <= kMaxP && small_enough &&
            ((a.m + 15) / 16 + 8) * ((a.batch + kMaxBatchTile - 1) / kMaxBatchTile) < (int64_t(1) << 21);
 }

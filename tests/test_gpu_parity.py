@@ -197,10 +197,18 @@ def test_plane_mfma_groups_of_64(gpu, m, n):
         gpu.check_mixed(dl, p_req, x, "plane_mfma", 64)
     used, _ = gpu.check_gemv(dl, 2, syn.make_x(1, n, seed=(156, 99)), "auto", 64)
     assert used == "plane_mfma"
-    # the asymmetric scheme and ragged widths stay on the other kernels
-    z = syn.make_offsets(2, m, n, 64, seed=(156, 1))
-    used, _ = gpu.check_gemv(dl, 2, syn.make_x(1, n, seed=(156, 98)), "auto", 64, offsets=z)
-    assert used != "plane_mfma"
+    # the asymmetric scheme: an offset per 64 columns times the sum of that half of a matrix instruction's columns
+    zs = {p: syn.make_offsets(p, m, n, 64, seed=(156, p)) for p in (1, 2, 3, 4)}
+    for batch in (1, 2, 4, 7):
+        x = syn.make_x(batch, n, seed=(157, batch))
+        for p in (1, 2, 4):
+            used, _ = gpu.check_gemv(dl, p, x, "plane_mfma", 64, offsets=zs[p])
+            assert used == "plane_mfma"
+        p_req = syn.make_p_req(batch, 1, 4, seed=(157, batch))
+        gpu.check_mixed(dl, p_req, x, "plane_mfma", 64, offsets_by_p=zs)
+        gpu.check_mixed(dl, p_req, x, "plane_mfma", 64, offsets_by_p={2: zs[2], 4: zs[4]})   # precisions 1 and 3 have none
+    used, _ = gpu.check_gemv(dl, 2, syn.make_x(1, n, seed=(156, 98)), "auto", 64, offsets=zs[2])
+    assert used == "plane_mfma"
 
 
 @pytest.mark.parametrize("kernel", ["dequant_mfma", "plane_f16"])

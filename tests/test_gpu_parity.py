@@ -670,7 +670,7 @@ def test_seeded_random_cases_against_the_oracle(gpu):
         else:
             p_req = rng.choice([1, 4, 4, 4, 7, -2], size=batch).astype(np.int32)
         zs = None
-        if rng.integers(3) == 0 and group != 64:
+        if rng.integers(3) == 0:
             zs = {p: syn.make_offsets(p, m, n, group, seed=(914, done, p)) for p in (1, 2, 3, 4) if rng.integers(2)}
         kernel = str(rng.choice(["auto", "auto", "dequant_mfma"]))
         shape = shapes[int(rng.integers(len(shapes)))]
